@@ -1,0 +1,247 @@
+/*
+ * GranQ activation fake-quantizer -- plain CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the parity authority for the HIP
+ * library and shares nothing with it: no header, no helper, no table.  Only
+ * the tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+ * It is written to be checked against the paper by eye, not to be fast: scalar
+ * nested loops, one channel at a time, one element at a time.
+ *
+ * Arithmetic: IEEE-754 binary32, round-to-nearest-even, every operation
+ * rounded on its own (build with -ffp-contract=off, no fast-math), subnormals
+ * kept.  The paper names no precision; binary32 is what the quantizer's users
+ * feed it, and integer codes are only comparable bit for bit when both sides
+ * round the same operations the same way.
+ *
+ * Tensor layout: dense NCHW, x[n][c][h][w].  The spatial dimensions only ever
+ * appear as the product hw = H*W (the paper's reshape of C x H x W into
+ * C x (HW), Sec. 4.2.1 "Activation Decomposition").
+ *
+ * Readings of points the paper leaves open (each is repeated where it is used):
+ *   - the per-channel range runs over batch and space, (n,h,w)   [Sec. 5.1]
+ *   - the rounding bracket is round-half-to-even                  [Eq. 1, 2]
+ *   - codes are clamped to [0, 2^b - 1] after rounding            [not in Eq. 1]
+ *   - a channel whose scale is zero, subnormal or NaN uses scale 1
+ *   - zero-point -0 is stored as +0
+ *   - the straight-through estimator passes the gradient where the clamp was
+ *     inactive and treats scale / zero-point as constants          [Sec. 2.1]
+ * Parity unpinned with respect to the authors' own code for the first, fourth
+ * and last of these: the paper gives nothing that could confirm them.
+ *
+ * dtype: 0 = binary32 storage, 1 = bfloat16 storage (uint16 bit patterns).
+ * With bfloat16 storage only loads and stores change: a load widens exactly,
+ * a store rounds to nearest even; ranges, scale, zero-point and all arithmetic
+ * stay binary32.
+ */
+#include <math.h>
+#include <float.h>
+#include <stdint.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+/* bfloat16 is the top half of a binary32: widening appends 16 zero bits. */
+static float bf16_widen(uint16_t h)
+{
+    uint32_t bits = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+/* Narrow a finite binary32 to bfloat16, round to nearest, ties to even:
+ * look at the 16 bits that are dropped; above half -> up, below half -> down,
+ * exactly half -> towards the even kept pattern.  A carry out of the mantissa
+ * moves into the exponent, which is the correct next value. */
+static uint16_t bf16_narrow(float f)
+{
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    uint32_t kept = bits >> 16;
+    uint32_t dropped = bits & 0xFFFFu;
+    if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))
+        kept += 1u;
+    return (uint16_t)kept;
+}
+
+static float load_elem(const void *base, int64_t i, int dtype)
+{
+    if (dtype == ORACLE_BF16)
+        return bf16_widen(((const uint16_t *)base)[i]);
+    return ((const float *)base)[i];
+}
+
+static void store_elem(void *base, int64_t i, int dtype, float v)
+{
+    if (dtype == ORACLE_BF16)
+        ((uint16_t *)base)[i] = bf16_narrow(v);
+    else
+        ((float *)base)[i] = v;
+}
+
+/* Largest code, 2^b - 1, as a float (Eq. 2 denominator). */
+static float code_max(int bits)
+{
+    return (float)((1 << bits) - 1);
+}
+
+/*
+ * Activation decomposition (Eq. 4; Alg. 1, the min/max step): per-channel
+ * minimum and maximum.  The paper's tensor has no batch axis; with a batch the
+ * statistics are taken "per channel at the batch level" (Sec. 5.1), i.e. over
+ * n as well as (h,w), giving one range per channel.
+ */
+void granq_oracle_range_reduce(const void *x, int dtype,
+                               int64_t n, int64_t c, int64_t hw,
+                               float *ch_min, float *ch_max)
+{
+    for (int64_t ic = 0; ic < c; ++ic) {
+        float mn = INFINITY;
+        float mx = -INFINITY;
+        for (int64_t in = 0; in < n; ++in) {
+            for (int64_t k = 0; k < hw; ++k) {
+                float v = load_elem(x, (in * c + ic) * hw + k, dtype);
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+        }
+        ch_min[ic] = mn;
+        ch_max[ic] = mx;
+    }
+}
+
+/*
+ * Vectorized scale / zero-point (Eq. 2 per channel = Eq. 5; Alg. 1, the two
+ * steps after the min/max):
+ *     s_c = (max_c - min_c) / (2^b - 1)
+ *     z_c = round(-min_c / s_c)
+ * A channel with max == min (a dead post-ReLU channel) would divide by zero;
+ * the paper is silent.  Reading: when s is zero, subnormal or NaN it is
+ * replaced by 1, so a dead channel reproduces 0 exactly.  "+ 0.0f" turns a
+ * zero-point of -0 (min = +0) into +0.
+ */
+void granq_oracle_prescale(const float *ch_min, const float *ch_max,
+                           int64_t c, int bits, float *scale, float *zero_point)
+{
+    float qmax = code_max(bits);
+    for (int64_t ic = 0; ic < c; ++ic) {
+        float range = ch_max[ic] - ch_min[ic];
+        float s = range / qmax;
+        if (!(s >= FLT_MIN))
+            s = 1.0f;
+        float z = rintf((-ch_min[ic]) / s) + 0.0f;
+        scale[ic] = s;
+        zero_point[ic] = z;
+    }
+}
+
+/* The unclamped code of one element: Eq. 1, round(x / s + z). */
+static float raw_code(float x, float s, float z)
+{
+    float t = x / s;
+    float v = t + z;
+    return rintf(v);
+}
+
+/*
+ * Quantize, clamp, dequantize (Eq. 1 then the dequantization of Eq. 6; Alg. 1,
+ * the quantize and the "dequantize & pre-scale" steps):
+ *     u     = round(x / s_c + z_c)
+ *     q     = clamp(u, 0, 2^b - 1)         (the clamp is this build's reading)
+ *     x_hat = s_c * (q - z_c)
+ * codes may be NULL.
+ */
+void granq_oracle_fakequant_fwd(const void *x, int dtype,
+                                int64_t n, int64_t c, int64_t hw,
+                                const float *scale, const float *zero_point,
+                                int bits, void *x_hat, uint8_t *codes)
+{
+    float qmax = code_max(bits);
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t ic = 0; ic < c; ++ic) {
+            float s = scale[ic];
+            float z = zero_point[ic];
+            for (int64_t k = 0; k < hw; ++k) {
+                int64_t i = (in * c + ic) * hw + k;
+                float u = raw_code(load_elem(x, i, dtype), s, z);
+                float q = fminf(fmaxf(u, 0.0f), qmax);
+                if (codes)
+                    codes[i] = (uint8_t)q;
+                float d = q - z;
+                store_elem(x_hat, i, dtype, s * d);
+            }
+        }
+    }
+}
+
+/*
+ * Straight-through estimator (named in Sec. 2.1, no formula given).  Reading:
+ * the rounding is treated as the identity and the clamp as a hard gate, so
+ *     dx = dy   where 0 <= u <= 2^b - 1   (u the rounded, unclamped code)
+ *     dx = 0    elsewhere,
+ * with scale and zero-point held constant (no gradient into the ranges).
+ */
+void granq_oracle_fakequant_bwd(const void *x, const void *dy, int dtype,
+                                int64_t n, int64_t c, int64_t hw,
+                                const float *scale, const float *zero_point,
+                                int bits, void *dx)
+{
+    float qmax = code_max(bits);
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t ic = 0; ic < c; ++ic) {
+            float s = scale[ic];
+            float z = zero_point[ic];
+            for (int64_t k = 0; k < hw; ++k) {
+                int64_t i = (in * c + ic) * hw + k;
+                float u = raw_code(load_elem(x, i, dtype), s, z);
+                float g = load_elem(dy, i, dtype);
+                if (!(u >= 0.0f && u <= qmax))
+                    g = 0.0f;
+                store_elem(dx, i, dtype, g);
+            }
+        }
+    }
+}
+
+/*
+ * The two accumulation forms the paper contrasts, on a 1x1 weighted channel
+ * sum with one weight per channel (fp32 storage only; accumulation in channel
+ * order c = 0, 1, ...):
+ *   in-loop scaling (Eq. 3):  y[n,k] = sum_c  w_c * s_c * (code[n,c,k] - z_c)
+ *   pre-scaled (Eq. 6/Alg. 1): y[n,k] = sum_c  w_c * x_hat[n,c,k]
+ * Eq. 3 is evaluated left to right: (w_c * s_c) * (code - z_c).
+ */
+void granq_oracle_accumulate_inloop(const uint8_t *codes,
+                                    int64_t n, int64_t c, int64_t hw,
+                                    const float *scale, const float *zero_point,
+                                    const float *weight, float *y)
+{
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t k = 0; k < hw; ++k) {
+            float acc = 0.0f;
+            for (int64_t ic = 0; ic < c; ++ic) {
+                float d = (float)codes[(in * c + ic) * hw + k] - zero_point[ic];
+                float ws = weight[ic] * scale[ic];
+                float term = ws * d;
+                acc = acc + term;
+            }
+            y[in * hw + k] = acc;
+        }
+    }
+}
+
+void granq_oracle_accumulate_prescaled(const float *x_hat,
+                                       int64_t n, int64_t c, int64_t hw,
+                                       const float *weight, float *y)
+{
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t k = 0; k < hw; ++k) {
+            float acc = 0.0f;
+            for (int64_t ic = 0; ic < c; ++ic) {
+                float term = weight[ic] * x_hat[(in * c + ic) * hw + k];
+                acc = acc + term;
+            }
+            y[in * hw + k] = acc;
+        }
+    }
+}

@@ -1,0 +1,454 @@
+"""Pins for the CPU oracle: checks against what the paper and the mathematics fix.
+
+Every function takes ``lib`` (a loaded oracle library, None = the committed
+one) and raises AssertionError when the oracle disagrees with
+
+  * the hand-derived worked examples under tests/golden/,
+  * exact rational arithmetic (tests/exact_ref.py) on small tensors,
+  * library routines in the special cases that reduce to them
+    (numpy min/max, numpy rint/clip, torch's bfloat16 conversion),
+  * invariants that follow from Eq. 1, 2, 6 (code range, end codes,
+    monotonicity, half-step error bound, idempotence, equivariances,
+    collapse to layer-wise, power-of-two covariance).
+
+``test_oracle_pins.py`` runs them on the real oracle; ``test_oracle_mutants.py``
+runs them on copies of the oracle with one planted mistake each and expects a
+failure, which shows the set is tight enough to notice such mistakes.
+"""
+from fractions import Fraction as F
+
+import numpy as np
+import torch
+
+import oracle
+import workloads
+from exact_ref import (f32_to_fraction, real_fakequant, real_prescale, rn_bf16, soft_fakequant,
+                       soft_prescale)
+from golden_cases import from_storage, load_cases, to_storage
+
+
+def _eq(a, b, what):
+    a = np.asarray(a)
+    b = np.asarray(b)
+    assert a.shape == b.shape, "%s: shape %s vs %s" % (what, a.shape, b.shape)
+    bad = np.nonzero(~(a == b))
+    assert bad[0].size == 0, "%s: %d mismatches, first at %s: %r vs %r" % (
+        what, bad[0].size, tuple(ix[0] for ix in bad), a[bad][0], b[bad][0])
+
+
+# ---------------------------------------------------------------------------
+# P1: hand-derived worked examples
+# ---------------------------------------------------------------------------
+
+def check_golden(lib=None):
+    cases = load_cases()
+    assert len(cases) >= 9
+    for cs in cases:
+        name, bits, dt = cs["name"], cs["bits"], cs["dtype"]
+        x = to_storage(cs["x"], dt).reshape(cs["shape"])
+        if "given_scale" in cs:
+            s = cs["given_scale"].astype(np.float32)
+            z = cs["given_zero_point"].astype(np.float32)
+        else:
+            mn, mx = oracle.range_reduce(x, lib)
+            _eq(mn, cs["min"].astype(np.float32), name + ": min")
+            _eq(mx, cs["max"].astype(np.float32), name + ": max")
+            s, z = oracle.prescale(mn, mx, bits, lib)
+            _eq(s, cs["scale"].astype(np.float32), name + ": scale")
+            _eq(z, cs["zero_point"].astype(np.float32), name + ": zero_point")
+            assert not np.any(np.signbit(z) & (z == 0)), name + ": zero_point must not be -0"
+        xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+        _eq(codes.ravel(), cs["codes"].astype(np.uint8), name + ": codes")
+        _eq(from_storage(xhat).ravel(), cs["xhat"].astype(np.float32), name + ": xhat")
+        # backward with dy = 1 + index/8 (bf16-exact for the small cases), mask from the fixture
+        dyv = 1.0 + np.arange(x.size) / 8.0
+        dy = to_storage(dyv, dt).reshape(cs["shape"])
+        dx = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
+        _eq(from_storage(dx).ravel(), (dyv * cs["mask"]).astype(np.float32), name + ": dx")
+
+
+# ---------------------------------------------------------------------------
+# P2: exact rational arithmetic
+# ---------------------------------------------------------------------------
+
+def check_dyadic_grid_exhaustive(lib=None):
+    """Every grid point of dyadic ranges, against the formulas over the rationals.
+
+    Channel = (min, step): max = min + (2^b - 1) * step, values = all multiples
+    of 1/8 in [min, max].  step is a power of two, so s = step exactly, x / s is
+    exact and nothing is rounded except by the bracket of Eq. 1 / Eq. 2."""
+    for bits in (1, 2, 3, 4):
+        qmax = 2 ** bits - 1
+        chans = [(F(mn8, 8), F(1, 2 ** k)) for mn8 in (-16, -10, -6, -3, 0, 4, 9) for k in (0, 1, 2)]
+        length = max(int((qmax * st) * 8) + 1 for _, st in chans)
+        vals = []
+        for mn, st in chans:
+            grid = [mn + F(i, 8) for i in range(int(qmax * st * 8) + 1)]
+            grid += [grid[-1]] * (length - len(grid))
+            # keep min first and max last, shuffle nothing: order must not matter
+            vals.append(grid)
+        # layout (N=2, C, HW): split every channel's list over two samples
+        half = (length + 1) // 2
+        for g in vals:
+            g += [g[0]] * (2 * half - len(g))
+        x = np.empty((2, len(chans), half), np.float32)
+        for c, g in enumerate(vals):
+            x[0, c, :] = [float(v) for v in g[:half]]
+            x[1, c, :] = [float(v) for v in g[half:]]
+        mn, mx = oracle.range_reduce(x, lib)
+        s, z = oracle.prescale(mn, mx, bits, lib)
+        xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+        dy = np.full(x.shape, 3.0, np.float32)
+        dx = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
+        for c, (cmin, st) in enumerate(chans):
+            es, ez = real_prescale(cmin, cmin + qmax * st, bits)
+            assert es == st
+            assert f32_to_fraction(mn[c]) == cmin and f32_to_fraction(mx[c]) == cmin + qmax * st
+            assert f32_to_fraction(s[c]) == es and f32_to_fraction(z[c]) == ez, (bits, c)
+            for n in range(2):
+                for k in range(half):
+                    q, xh, inr = real_fakequant(f32_to_fraction(x[n, c, k]), es, ez, bits)
+                    assert codes[n, c, k] == q, (bits, c, n, k)
+                    assert f32_to_fraction(xhat[n, c, k]) == xh, (bits, c, n, k)
+                    assert dx[n, c, k] == (3.0 if inr else 0.0), (bits, c, n, k)
+
+
+def check_tiny_shapes_softfloat(lib=None):
+    """All shapes N,C,H,W <= 3 and awkward scales, against per-operation binary32
+    rounding done with integers; ranges reduced in Python over (n,h,w)."""
+    rng = np.random.default_rng(1234)
+    shapes = [(n, c, h, w) for n in (1, 2, 3) for c in (1, 2, 3) for h in (1, 3) for w in (1, 2)]
+    for i, shp in enumerate(shapes):
+        bits = (1, 2, 3, 4, 5, 8)[i % 6]
+        kind = i % 3
+        if kind == 0:
+            x = rng.integers(-24, 40, size=shp).astype(np.float32) / 8.0
+        elif kind == 1:
+            x = np.abs(rng.standard_normal(shp)).astype(np.float32) * (10.0 ** rng.uniform(-2, 2))
+        else:
+            x = rng.standard_normal(shp).astype(np.float32) * 3.0 + 1.0
+        mn, mx = oracle.range_reduce(x, lib)
+        s, z = oracle.prescale(mn, mx, bits, lib)
+        xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+        dy = rng.standard_normal(shp).astype(np.float32)
+        dx = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
+        for c in range(shp[1]):
+            col = [f32_to_fraction(v) for v in x[:, c].ravel()]
+            emn, emx = min(col), max(col)
+            assert f32_to_fraction(mn[c]) == emn and f32_to_fraction(mx[c]) == emx, (shp, c)
+            es, ez = soft_prescale(emn, emx, bits)
+            assert f32_to_fraction(s[c]) == es and f32_to_fraction(z[c]) == ez, (shp, c, bits)
+            for n in range(shp[0]):
+                for h in range(shp[2]):
+                    for w in range(shp[3]):
+                        q, xh, inr = soft_fakequant(f32_to_fraction(x[n, c, h, w]), es, ez, bits)
+                        assert codes[n, c, h, w] == q, (shp, n, c, h, w)
+                        assert f32_to_fraction(xhat[n, c, h, w]) == xh, (shp, n, c, h, w)
+                        assert dx[n, c, h, w] == (dy[n, c, h, w] if inr else 0.0)
+
+
+def check_stale_ranges_softfloat(lib=None):
+    """Scale / zero-point handed in (not from x): both clamp sides and the mask."""
+    rng = np.random.default_rng(99)
+    x = (rng.standard_normal((2, 3, 2, 5)) * 4).astype(np.float32)
+    s = np.array([0.37, 1.0 / 7.0, 2.5], np.float32)
+    z = np.array([3.0, 0.0, -2.0], np.float32)
+    for bits in (2, 3, 5):
+        xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+        dy = rng.standard_normal(x.shape).astype(np.float32)
+        dx = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
+        seen = set()
+        for idx in np.ndindex(*x.shape):
+            c = idx[1]
+            q, xh, inr = soft_fakequant(f32_to_fraction(x[idx]), f32_to_fraction(s[c]),
+                                        int(z[c]), bits)
+            assert codes[idx] == q and f32_to_fraction(xhat[idx]) == xh, (bits, idx)
+            assert dx[idx] == (dy[idx] if inr else 0.0), (bits, idx)
+            seen.add(inr)
+        assert seen == {True, False}
+
+
+def check_near_ties_softfloat(lib=None):
+    """Inputs built to sit on or next to a rounding tie of Eq. 1: x ~ s * (k + 1/2).
+    There the code depends on the quotient being the correctly rounded binary32
+    one: a reciprocal-multiply, a fused multiply-add or a double-precision
+    intermediate moves x / s by an ulp and flips the code.  numpy only searches
+    for such inputs; the expected values come from integer arithmetic."""
+    rng = np.random.default_rng(77)
+    bits = 5
+    s_all = (rng.uniform(0.01, 3.0, size=40000)).astype(np.float32)
+    k_all = rng.integers(0, 31, size=40000).astype(np.float32)
+    x_all = (s_all * (k_all + np.float32(0.5))).astype(np.float32)
+    exact = (x_all / s_all)                                        # correctly rounded
+    recip = (x_all * (np.float32(1.0) / s_all)).astype(np.float32)
+    wide = (x_all.astype(np.float64) / s_all.astype(np.float64))
+    pick = np.nonzero((np.rint(exact) != np.rint(recip)) | (np.rint(exact) != np.rint(wide)))[0]
+    assert pick.size >= 64, "search found too few near-tie inputs"
+    pick = pick[:160]
+    c = pick.size
+    x = np.stack([x_all[pick], x_all[pick] * np.float32(0.5)], axis=0).reshape(2, c, 1, 1).copy()
+    s = s_all[pick].copy()
+    z = np.zeros(c, np.float32)
+    xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+    dy = np.ones_like(x)
+    dx = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
+    for n in range(2):
+        for j in range(c):
+            q, xh, inr = soft_fakequant(f32_to_fraction(x[n, j, 0, 0]), f32_to_fraction(s[j]), 0, bits)
+            assert codes[n, j, 0, 0] == q, (n, j, float(x[n, j, 0, 0]), float(s[j]))
+            assert f32_to_fraction(xhat[n, j, 0, 0]) == xh
+            assert dx[n, j, 0, 0] == (1.0 if inr else 0.0)
+
+
+# ---------------------------------------------------------------------------
+# P4: special cases that reduce to library routines
+# ---------------------------------------------------------------------------
+
+def check_minmax_vs_numpy(lib=None):
+    rng = np.random.default_rng(5)
+    for shp in [(4, 5, 3, 7), (1, 9, 1, 1), (7, 1, 2, 2), (3, 4, 7, 7)]:
+        x = rng.standard_normal(shp).astype(np.float32)
+        mn, mx = oracle.range_reduce(x, lib)
+        _eq(mn, x.min(axis=(0, 2, 3)), "min vs numpy %s" % (shp,))
+        _eq(mx, x.max(axis=(0, 2, 3)), "max vs numpy %s" % (shp,))
+
+
+def check_unit_scale_is_clip_rint(lib=None):
+    """min 0 and max 2^b - 1 give s = 1, z = 0: forward = clip(rint(x)) (numpy's
+    rint is round-half-to-even)."""
+    rng = np.random.default_rng(6)
+    for bits in (1, 3, 4, 8):
+        qmax = float(2 ** bits - 1)
+        x = (rng.uniform(0, qmax, size=(3, 2, 4, 8))).astype(np.float32)
+        x[..., 0] = np.arange(2 * 3 * 4).reshape(3, 2, 4) % (qmax + 1) + 0.5   # plant ties
+        x = np.minimum(x, qmax).astype(np.float32)
+        x[0, :, 0, 1] = 0.0
+        x[0, :, 0, 2] = qmax
+        mn, mx = oracle.range_reduce(x, lib)
+        s, z = oracle.prescale(mn, mx, bits, lib)
+        _eq(s, np.ones(2, np.float32), "unit scale")
+        _eq(z, np.zeros(2, np.float32), "zero zero-point")
+        xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+        want = np.clip(np.rint(x), 0, qmax)
+        _eq(xhat, want, "xhat vs clip(rint)")
+        _eq(codes, want.astype(np.uint8), "codes vs clip(rint)")
+
+
+def check_bf16_vs_torch(lib=None):
+    """bfloat16 storage: loads widen exactly and stores round to nearest even,
+    checked against torch's own float32 <-> bfloat16 conversion."""
+    g = torch.Generator().manual_seed(3)
+    xt = (torch.randn(3, 4, 5, 6, generator=g) * 3).to(torch.bfloat16)
+    xb = xt.view(torch.int16).numpy().view(np.uint16)
+    x32 = xt.to(torch.float32).numpy()
+    mnb, mxb = oracle.range_reduce(xb, lib)
+    _eq(mnb, x32.min(axis=(0, 2, 3)), "bf16 min")
+    _eq(mxb, x32.max(axis=(0, 2, 3)), "bf16 max")
+    for bits in (3, 8):
+        s, z = oracle.prescale(mnb, mxb, bits, lib)
+        xh_b, codes_b = oracle.fakequant_fwd(xb, s, z, bits, lib)
+        xh_32, codes_32 = oracle.fakequant_fwd(x32, s, z, bits, lib)
+        _eq(codes_b, codes_32, "bf16 codes == f32 codes on the same values")
+        want = torch.from_numpy(xh_32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        _eq(xh_b, want, "bf16 xhat == torch RNE narrowing of the f32 xhat")
+        dyt = torch.randn(3, 4, 5, 6, generator=g).to(torch.bfloat16)
+        dyb = dyt.view(torch.int16).numpy().view(np.uint16)
+        dxb = oracle.fakequant_bwd(xb, dyb, s, z, bits, lib)
+        dx32 = oracle.fakequant_bwd(x32, dyt.to(torch.float32).numpy(), s, z, bits, lib)
+        _eq(oracle.f32_from_bf16_bits(dxb), dx32, "bf16 dx")
+    # narrowing alone, against integer arithmetic, on values that need rounding
+    s = np.array([1.0 / 3.0], np.float32)
+    z = np.array([0.0], np.float32)
+    q = np.arange(0, 256, dtype=np.float32).reshape(1, 1, 16, 16)
+    xq = torch.from_numpy(q * s[0]).to(torch.bfloat16)     # any input that lands on code ~q
+    xb = xq.view(torch.int16).numpy().view(np.uint16)
+    xh_b, codes = oracle.fakequant_fwd(xb, s, z, 8, lib)
+    for cb, hb in zip(codes.ravel(), xh_b.ravel()):
+        exact = f32_to_fraction(np.float32(s[0]) * np.float32(cb))
+        assert f32_to_fraction(oracle.f32_from_bf16_bits(np.array([hb]))[0]) == rn_bf16(exact)
+
+
+# ---------------------------------------------------------------------------
+# P3 / P5: invariants on workload-like tensors
+# ---------------------------------------------------------------------------
+
+def _workload_tensor(law, shape, seed):
+    return workloads.make_activation(shape, law, (0.05, 20.0), seed).numpy()
+
+
+def check_invariants(lib=None):
+    rng = np.random.default_rng(11)
+    for law, shape, bits in [("relu", (8, 16, 32, 32), 3), ("relu", (4, 32, 7, 7), 4),
+                             ("linear", (4, 24, 14, 14), 4), ("laplace", (4, 64, 7, 7), 3),
+                             ("relu6", (4, 32, 8, 8), 5)]:
+        x = _workload_tensor(law, shape, seed=bits)
+        if law == "relu":
+            x[0, :, 0, 0] = 0.0             # real ReLU outputs contain exact zeros
+        qmax = 2 ** bits - 1
+        mn, mx = oracle.range_reduce(x, lib)
+        s, z = oracle.prescale(mn, mx, bits, lib)
+        xhat, codes = oracle.fakequant_fwd(x, s, z, bits, lib)
+        sb = s.reshape(1, -1, 1, 1)
+        # (a) code range
+        assert codes.min() >= 0 and codes.max() <= qmax
+        # (b) the channel minimum always maps to code 0
+        cmin_codes = np.where(x == mn.reshape(1, -1, 1, 1), codes, 0)
+        assert cmin_codes.max() == 0
+        # (c) with min == 0 (post-ReLU) the channel maximum maps to the top code
+        if law == "relu":
+            assert np.all(mn == 0) and np.all(z == 0)
+            top = np.where(x == mx.reshape(1, -1, 1, 1), codes, qmax)
+            assert top.min() == qmax
+        # (d) codes are monotone in x within a channel
+        for c in range(shape[1]):
+            xs = x[:, c].ravel()
+            order = np.argsort(xs, kind="stable")
+            assert np.all(np.diff(codes[:, c].ravel()[order].astype(np.int32)) >= 0)
+        # (e) half-step error bound wherever the clamp was inactive
+        dy = np.ones_like(x)
+        mask = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
+        assert set(np.unique(mask).tolist()) <= {0.0, 1.0}
+        err = np.abs(xhat.astype(np.float64) - x.astype(np.float64))
+        bound = 0.5 * sb.astype(np.float64) * (1 + 1e-5) + 1e-30
+        assert np.all((err <= bound) | (mask == 0))
+        # the clamp only ever bites at the top, by one step at most
+        assert np.all(err <= 1.0 * sb.astype(np.float64) * (1 + 1e-5) + 1e-30)
+        assert np.all(codes[mask == 0] == qmax)
+        assert (mask == 0).mean() < 0.01
+        # (f) idempotence with the same (s, z)
+        xhat2, codes2 = oracle.fakequant_fwd(xhat, s, z, bits, lib)
+        _eq(codes2, codes, "idempotent codes")
+        _eq(xhat2, xhat, "idempotent xhat")
+        # (g) channel permutation equivariance, batch permutation invariance
+        perm = rng.permutation(shape[1])
+        xp = np.ascontiguousarray(x[:, perm])
+        xh_p, codes_p, s_p, z_p = oracle.fakequant(xp, bits, lib)
+        _eq(s_p, s[perm], "perm scale")
+        _eq(codes_p, codes[:, perm], "perm codes")
+        _eq(xh_p, xhat[:, perm], "perm xhat")
+        bperm = rng.permutation(shape[0])
+        xh_b, codes_b, s_b, z_b = oracle.fakequant(np.ascontiguousarray(x[bperm]), bits, lib)
+        _eq(s_b, s, "batch perm scale")
+        _eq(codes_b, codes[bperm], "batch perm codes")
+        # (i) scaling the input by 2^k scales the output by 2^k and keeps the codes
+        for k in (-3, 5):
+            xh_k, codes_k, s_k, z_k = oracle.fakequant((x * np.float32(2.0 ** k)), bits, lib)
+            _eq(codes_k, codes, "pow2 codes")
+            _eq(xh_k, xhat * np.float32(2.0 ** k), "pow2 xhat")
+            _eq(z_k, z, "pow2 zero-point")
+        # (j) backward returns dy or 0, bitwise
+        dyr = rng.standard_normal(shape).astype(np.float32)
+        dx = oracle.fakequant_bwd(x, dyr, s, z, bits, lib)
+        assert np.all((dx == dyr) | (dx == 0))
+        _eq(dx, dyr * mask, "dx == dy * mask")
+        # every code value is used somewhere on these wide tensors, in every channel with spread
+        assert len(np.unique(codes)) == qmax + 1
+
+
+def check_collapse_to_layerwise(lib=None):
+    """Channels that all contain the same extremes: per-channel == per-layer."""
+    x = _workload_tensor("linear", (3, 6, 5, 5), seed=2)
+    x = np.clip(x, -4.0, 9.0)
+    x[0, :, 0, 0] = -4.0
+    x[1, :, 2, 3] = 9.0
+    for bits in (3, 4):
+        xh_c, codes_c, s_c, z_c = oracle.fakequant(x, bits, lib)
+        flat = x.reshape(1, 1, 1, -1)
+        xh_l, codes_l, s_l, z_l = oracle.fakequant(flat, bits, lib)
+        assert np.all(s_c == s_l[0]) and np.all(z_c == z_l[0])
+        _eq(codes_c.ravel(), codes_l.ravel(), "collapse codes")
+        _eq(xh_c.ravel(), xh_l.ravel(), "collapse xhat")
+
+
+def check_per_sample_view(lib=None):
+    """Ranges per sample and channel (the paper's C x H x W tensor without a
+    batch) are the batch-level call on the (1, N*C, H, W) view."""
+    x = _workload_tensor("relu", (3, 4, 5, 5), seed=8)
+    xh_v, codes_v, s_v, z_v = oracle.fakequant(x.reshape(1, 12, 5, 5), 3, lib)
+    for n in range(3):
+        xh_n, codes_n, s_n, z_n = oracle.fakequant(x[n:n + 1].copy(), 3, lib)
+        _eq(s_n, s_v[n * 4:(n + 1) * 4], "per-sample scale")
+        _eq(codes_n.ravel(), codes_v.reshape(3, -1)[n], "per-sample codes")
+
+
+def check_error_halves_per_bit(lib=None):
+    x = _workload_tensor("relu", (8, 16, 16, 16), seed=4)
+    prev = None
+    for bits in range(2, 9):
+        xh, _, s, _ = oracle.fakequant(x, bits, lib)
+        rel = np.linalg.norm((xh - x).astype(np.float64)) / np.linalg.norm(x.astype(np.float64))
+        if prev is not None:
+            assert 0.35 < rel / prev < 0.65, (bits, rel, prev)
+        prev = rel
+
+
+def check_channelwise_beats_layerwise(lib=None):
+    """Direction of the paper's Table 2 on channels with very different spreads:
+    per-channel ranges give higher cosine similarity and lower relative error."""
+    x = _workload_tensor("relu", (8, 16, 32, 32), seed=0)
+    xd = x.astype(np.float64).ravel()
+
+    def metrics(xh):
+        q = xh.astype(np.float64).ravel()
+        return (xd @ q) / (np.linalg.norm(xd) * np.linalg.norm(q)), \
+            np.linalg.norm(xd - q) / np.linalg.norm(xd)
+
+    xh_c = oracle.fakequant(x, 3, lib)[0]
+    xh_l = oracle.fakequant(x.reshape(1, 1, 1, -1), 3, lib)[0]
+    cos_c, rel_c = metrics(xh_c)
+    cos_l, rel_l = metrics(xh_l)
+    assert cos_c > cos_l and rel_c < rel_l
+    # per channel the gap is large: small-sigma channels are wiped out layer-wise
+    per_c = np.linalg.norm((xh_c - x).reshape(8, 16, -1).transpose(1, 0, 2).reshape(16, -1), axis=1)
+    per_l = np.linalg.norm((xh_l.reshape(x.shape) - x).reshape(8, 16, -1).transpose(1, 0, 2)
+                           .reshape(16, -1), axis=1)
+    assert np.all(per_c <= per_l * (1 + 1e-6))
+
+
+def check_accumulation_forms(lib=None):
+    """Eq. 3 (scale inside the loop) and Eq. 6 (pre-scaled) compute the same sum.
+    On dyadic data both are exact and equal to the rational sum; on general data
+    they agree with a float64 einsum to rounding."""
+    # dyadic: s in {1/2, 1, 2}, integer z, weights multiples of 1/4
+    rng = np.random.default_rng(21)
+    n, c, hw = 2, 5, 6
+    codes = rng.integers(0, 8, size=(n, c, hw)).astype(np.uint8)
+    s = np.array([0.5, 1, 2, 0.25, 1], np.float32)
+    z = np.array([0, 2, 3, 1, 7], np.float32)
+    w = np.array([0.25, -1.5, 2, 0.75, -0.5], np.float32)
+    xhat = (s.reshape(1, c, 1) * (codes.astype(np.float32) - z.reshape(1, c, 1))).astype(np.float32)
+    y3 = oracle.accumulate_inloop(codes, s, z, w, lib)
+    y6 = oracle.accumulate_prescaled(xhat, w, lib)
+    for i in range(n):
+        for k in range(hw):
+            exact = sum(F(float(w[j])) * F(float(s[j])) * (int(codes[i, j, k]) - int(z[j]))
+                        for j in range(c))
+            assert F(float(y3[i, k])) == exact and F(float(y6[i, k])) == exact
+    # general
+    x = _workload_tensor("linear", (3, 12, 4, 4), seed=5)
+    xh, cd, s, z = oracle.fakequant(x, 4, lib)
+    w = rng.standard_normal(12).astype(np.float32)
+    y3 = oracle.accumulate_inloop(cd, s, z, w, lib)
+    y6 = oracle.accumulate_prescaled(xh, w, lib)
+    ref = np.einsum("c,nchw->nhw", w.astype(np.float64), xh.astype(np.float64))
+    scale = np.abs(w).astype(np.float64) @ np.abs(xh.astype(np.float64)).max(axis=(0, 2, 3))
+    assert np.max(np.abs(y3 - ref)) <= 1e-5 * scale
+    assert np.max(np.abs(y6 - ref)) <= 1e-5 * scale
+
+
+ALL_CHECKS = [
+    check_golden,
+    check_dyadic_grid_exhaustive,
+    check_tiny_shapes_softfloat,
+    check_stale_ranges_softfloat,
+    check_near_ties_softfloat,
+    check_minmax_vs_numpy,
+    check_unit_scale_is_clip_rint,
+    check_bf16_vs_torch,
+    check_invariants,
+    check_collapse_to_layerwise,
+    check_per_sample_view,
+    check_error_halves_per_bit,
+    check_channelwise_beats_layerwise,
+    check_accumulation_forms,
+]

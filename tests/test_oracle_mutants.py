@@ -1,0 +1,78 @@
+"""Are the oracle's pins tight?  Plant one plausible mistake at a time into a
+COPY of the oracle's source (on the CPU, in a temp directory), build it, and
+require that at least one pin in tests/oracle_pins.py fails for it.  The
+committed oracle is never modified."""
+import os
+
+import pytest
+
+import oracle
+import oracle_pins
+
+# (name, text in granq_oracle.c, replacement, how many occurrences are replaced)
+MUTANTS = [
+    ("zero_point_wrong_sign_in_code", "float v = t + z;", "float v = t - z;", 1),
+    ("round_half_up", "return rintf(v);", "return floorf(v + 0.5f);", 1),
+    ("round_truncates", "return rintf(v);", "return truncf(v);", 1),
+    ("dequant_drops_zero_point", "float d = q - z;", "float d = q;", 1),
+    ("dequant_adds_zero_point", "float d = q - z;", "float d = q + z;", 1),
+    ("batch_and_channel_transposed", "(in * c + ic) * hw + k", "(ic * n + in) * hw + k", 5),
+    ("range_over_first_sample_only",
+     "float mx = -INFINITY;\n        for (int64_t in = 0; in < n; ++in) {",
+     "float mx = -INFINITY;\n        for (int64_t in = 0; in < 1; ++in) {", 1),
+    ("scale_drops_min", "float range = ch_max[ic] - ch_min[ic];", "float range = ch_max[ic];", 1),
+    ("zero_point_sign", "rintf((-ch_min[ic]) / s)", "rintf((ch_min[ic]) / s)", 1),
+    ("zero_point_not_rounded", "rintf((-ch_min[ic]) / s) + 0.0f", "(-ch_min[ic]) / s + 0.0f", 1),
+    ("zero_point_keeps_minus_zero", "rintf((-ch_min[ic]) / s) + 0.0f", "rintf((-ch_min[ic]) / s)", 1),
+    ("levels_off_by_one", "(float)((1 << bits) - 1)", "(float)(1 << bits)", 1),
+    ("no_clamp", "float q = fminf(fmaxf(u, 0.0f), qmax);", "float q = u;", 1),
+    ("clamp_low_side_missing", "float q = fminf(fmaxf(u, 0.0f), qmax);", "float q = fminf(u, qmax);", 1),
+    ("mask_strict", "u >= 0.0f && u <= qmax", "u > 0.0f && u < qmax", 1),
+    ("mask_on_clamped_code_always_true", "if (!(u >= 0.0f && u <= qmax))", "if (0)", 1),
+    ("mask_inverted", "if (!(u >= 0.0f && u <= qmax))", "if ((u >= 0.0f && u <= qmax))", 1),
+    ("degenerate_scale_not_replaced", "s = 1.0f;", "s = FLT_MIN;", 1),
+    ("min_max_swapped", "ch_min[ic] = mn;\n        ch_max[ic] = mx;",
+     "ch_min[ic] = mx;\n        ch_max[ic] = mn;", 1),
+    ("multiply_instead_of_divide", "float t = x / s;", "float t = x * s;", 1),
+    ("reciprocal_instead_of_divide", "float t = x / s;", "float t = x * (1.0f / s);", 1),
+    ("double_precision_intermediate", "float t = x / s;\n    float v = t + z;\n    return rintf(v);",
+     "double t = (double)x / s;\n    double v = t + z;\n    return (float)rint(v);", 1),
+    ("fused_multiply_add", "float t = x / s;\n    float v = t + z;",
+     "float v = fmaf(x, 1.0f / s, z);", 1),
+    ("bf16_ties_round_up", "(dropped == 0x8000u && (kept & 1u))", "(dropped == 0x8000u)", 1),
+    ("bf16_truncates", "if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))", "if (0)", 1),
+    ("inloop_drops_scale", "float ws = weight[ic] * scale[ic];", "float ws = weight[ic];", 1),
+    ("inloop_drops_zero_point", "- zero_point[ic];\n                float ws", ";\n                float ws", 1),
+    ("prescaled_sum_skips_last_channel",
+     "for (int64_t ic = 0; ic < c; ++ic) {\n                float term = weight[ic] * x_hat",
+     "for (int64_t ic = 0; ic + 1 < c; ++ic) {\n                float term = weight[ic] * x_hat", 1),
+]
+
+
+def _first_failure(lib):
+    for check in oracle_pins.ALL_CHECKS:
+        try:
+            check(lib)
+        except AssertionError:
+            return check.__name__
+    return None
+
+
+@pytest.mark.parametrize("name,old,new,count", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new, count):
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "granq_oracle.c")).read()
+    assert src.count(old) == count, "anchor text for %s not found exactly %d time(s)" % (name, count)
+    mutated = tmp_path / "mutant.c"
+    mutated.write_text(src.replace(old, new))
+    so = str(tmp_path / "mutant.so")
+    oracle.build(out=so, src=str(mutated), extra_flags=("-w",))
+    lib = oracle.load(so)
+    assert _first_failure(lib) is not None, "no pin notices the planted mistake %r" % name
+
+
+def test_unmodified_copy_passes(tmp_path):
+    """The harness itself: an unmutated copy built the same way passes every pin."""
+    src = os.path.join(os.path.dirname(oracle.__file__), "granq_oracle.c")
+    so = str(tmp_path / "copy.so")
+    oracle.build(out=so, src=src)
+    assert _first_failure(oracle.load(so)) is None
