@@ -1,0 +1,160 @@
+/*
+ * granq.h -- C ABI of the GranQ activation fake-quantizer for AMD MI355X (gfx950).
+ *
+ * The library implements the activation quantizer of GranQ (arXiv 2503.18339,
+ * Alg. 1 without its final accumulation): for a dense NCHW activation tensor
+ *
+ *   1. granq_range_reduce   per-channel minimum / maximum            (Eq. 4)
+ *   2. granq_prescale       per-channel scale and zero-point vectors (Eq. 5)
+ *   3. granq_fakequant_fwd  quantize, clamp, dequantize each element (Eq. 1, 6)
+ *   4. granq_fakequant_bwd  straight-through-estimator gradient      (Sec. 2.1)
+ *
+ * Common conventions
+ * ------------------
+ *  - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *    never allocates, frees or keeps a pointer after the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call only enqueues kernels on that stream and returns without
+ *    synchronising; results are ready when the stream reaches that point.
+ *  - Tensors are dense, contiguous NCHW: element (n,c,h,w) of a tensor with
+ *    descriptor {n,c,h,w} lives at index ((n*C + c)*H + h)*W + w.  x, x_hat, dy
+ *    and dx of one call share the descriptor's dtype; range, scale and
+ *    zero-point vectors are always float32 of length C.
+ *  - Arithmetic is IEEE-754 binary32 with round-to-nearest-even, each operation
+ *    rounded on its own (true division, no fused multiply-add, subnormals
+ *    kept).  With bfloat16 storage only loads (exact widening) and stores
+ *    (round to nearest even) differ.
+ *  - Inputs must be finite.  NaN or infinity in x gives unspecified values
+ *    (never a fault or a hang).
+ *  - Data pointers should be 16-byte aligned and C*H*W*sizeof(element) a
+ *    multiple of 16 for the vectorised kernels; anything else is handled by a
+ *    slower element-wise path with the same results.  Pointers must be aligned
+ *    to their element size.
+ *  - Other granularities are views, no extra entry points:
+ *      layer-wise (one range per tensor)       desc {1, 1, 1, N*C*H*W}
+ *      per sample and channel (Alg. 1's
+ *      C x H x W tensor with no batch axis)    desc {1, N*C, H, W}
+ *      channel-wise weights, OIHW              desc {1, O, 1, I*kh*kw}
+ *  - Errors: every function returns a granq_status_t; on any status other than
+ *    GRANQ_OK nothing has been enqueued.  Calls are re-entrant; the library has
+ *    no global mutable state.  Calls may be captured into a HIP graph.
+ */
+#ifndef GRANQ_H
+#define GRANQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRANQ_OK = 0,
+    GRANQ_ERR_INVALID_ARG = 1,   /* null pointer, non-positive dimension, bits outside 1..8 */
+    GRANQ_ERR_UNSUPPORTED = 2,   /* unknown dtype, misaligned pointer, tensor too large     */
+    GRANQ_ERR_WORKSPACE = 3,     /* workspace missing or smaller than required             */
+    GRANQ_ERR_HIP = 4            /* the HIP runtime rejected a launch                      */
+} granq_status_t;
+
+typedef enum {
+    GRANQ_F32 = 0,               /* IEEE binary32 storage */
+    GRANQ_BF16 = 1               /* bfloat16 storage      */
+} granq_dtype_t;
+
+/* Dense contiguous NCHW tensor. */
+typedef struct {
+    int64_t n, c, h, w;
+    granq_dtype_t dtype;
+} granq_desc_t;
+
+/* Static string naming a status code (never NULL). */
+const char *granq_status_string(granq_status_t status);
+
+/* Library version as a static string. */
+const char *granq_version(void);
+
+/*
+ * Bytes of device workspace granq_range_reduce needs for this descriptor
+ * (host-only, no GPU call).  The workspace holds per-block partial minima and
+ * maxima between the two passes of the reduction.
+ */
+granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out);
+
+/*
+ * Host-only introspection (no GPU call): how the vectorised kernels would tile
+ * this descriptor.  Fills out[0..9] with
+ *   [0] 1 if the shape is eligible for the 128-bit column kernels, else 0
+ *   [1] rows  [2] row length  [3] elements per channel within a row
+ *   [4] columns per block  [5] column tiles  [6] row groups  [7] rows per group
+ *   [8] partial slots per column tile  [9] 1 if no 16-byte vector straddles channels
+ * of the matrix view (rows x row length) the kernels walk.  For tests and tuning.
+ */
+granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[10]);
+
+/*
+ * Activation decomposition (Eq. 4; Alg. 1's min/max step; Sec. 5.1: channel-wise
+ * quantization is done per channel at the batch level):
+ *     ch_min[c] = min over (n,h,w) of x[n,c,h,w],   ch_max[c] likewise.
+ * x           [in]  device, N*C*H*W elements of desc->dtype
+ * ch_min/max  [out] device, C floats each
+ * workspace   [tmp] device, at least granq_workspace_bytes() bytes, 16-byte
+ *                   aligned; contents before and after the call are garbage
+ */
+granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc,
+                                  float *ch_min, float *ch_max,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/*
+ * Vectorized pre-scaling parameters (Eq. 2 per channel = Eq. 5; Alg. 1's two
+ * steps after the min/max), all channels in one launch:
+ *     scale[c]      = (ch_max[c] - ch_min[c]) / (2^bits - 1)
+ *     zero_point[c] = round_half_even(-ch_min[c] / scale[c])      (stored as float)
+ * A channel whose scale comes out zero, subnormal or NaN (max == min: a dead
+ * channel) gets scale 1, so that a dead channel reproduces 0 exactly.  A
+ * zero-point of -0 is stored as +0.
+ * ch_min/max [in] device, c floats;  scale/zero_point [out] device, c floats.
+ * bits in 1..8.
+ */
+granq_status_t granq_prescale(const float *ch_min, const float *ch_max,
+                              int64_t c, int bits,
+                              float *scale, float *zero_point, void *stream);
+
+/*
+ * Quantize, clamp, dequantize (Eq. 1, then the dequantization of Eq. 6; Alg. 1's
+ * "quantize" and "dequantize & pre-scale" steps):
+ *     u     = round_half_even(x / scale[c] + zero_point[c])
+ *     q     = min(max(u, 0), 2^bits - 1)
+ *     x_hat = scale[c] * (q - zero_point[c])
+ * The clamp is not in the paper's Eq. 1; it keeps codes inside b bits when the
+ * top of the range lands on a rounding tie or when scale / zero-point come
+ * from another tensor.
+ * x      [in]  device, desc elements
+ * x_hat  [out] device, desc elements (may alias x: in-place)
+ * codes  [out] device, N*C*H*W bytes holding q, or NULL to skip them
+ */
+granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc,
+                                   const float *scale, const float *zero_point,
+                                   int bits, void *x_hat, uint8_t *codes_or_null,
+                                   void *stream);
+
+/*
+ * Straight-through estimator (Sec. 2.1 names it; the formula is this
+ * library's): rounding is treated as the identity and the clamp as a gate,
+ *     dx = dy   where 0 <= u <= 2^bits - 1   (u as in granq_fakequant_fwd)
+ *     dx = 0    elsewhere,
+ * with scale and zero-point treated as constants (no gradient flows into the
+ * ranges).
+ * x, dy [in] device;  dx [out] device (may alias dy).
+ */
+granq_status_t granq_fakequant_bwd(const void *x, const void *dy,
+                                   const granq_desc_t *desc,
+                                   const float *scale, const float *zero_point,
+                                   int bits, void *dx, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* GRANQ_H */

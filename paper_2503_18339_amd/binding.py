@@ -1,0 +1,196 @@
+"""ctypes binding of the GranQ C ABI (include/granq.h).
+
+Argument marshalling only: every function here turns torch tensors into device
+pointers plus a descriptor, calls the entry point of the same name in
+``libgranq.so`` and raises on a non-zero status.  No arithmetic of the method is
+done in Python and there is no CPU fallback: without the built library, or with
+tensors that are not on a GPU, the calls fail.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+GRANQ_OK = 0
+GRANQ_ERR_INVALID_ARG = 1
+GRANQ_ERR_UNSUPPORTED = 2
+GRANQ_ERR_WORKSPACE = 3
+GRANQ_ERR_HIP = 4
+
+GRANQ_F32 = 0
+GRANQ_BF16 = 1
+
+EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
+           "granq_range_reduce",
+           "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd")
+
+
+class granq_desc_t(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("c", ctypes.c_int64), ("h", ctypes.c_int64),
+                ("w", ctypes.c_int64), ("dtype", ctypes.c_int)]
+
+
+class GranqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_string(status)))
+
+
+_lib: Optional[ctypes.CDLL] = None
+_vp = ctypes.c_void_p
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libgranq.so (building it with hipcc first if it has never been built)."""
+    global _lib
+    if path is None and _lib is not None:
+        return _lib
+    p = path or _build.LIB
+    if path is None and not os.path.exists(p):
+        _build.build()
+    lib = ctypes.CDLL(p)
+    dp = ctypes.POINTER(granq_desc_t)
+    lib.granq_status_string.argtypes = [ctypes.c_int]
+    lib.granq_status_string.restype = ctypes.c_char_p
+    lib.granq_version.argtypes = []
+    lib.granq_version.restype = ctypes.c_char_p
+    lib.granq_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.granq_plan_describe.argtypes = [dp, ctypes.POINTER(ctypes.c_int64 * 10)]
+    lib.granq_range_reduce.argtypes = [_vp, dp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.granq_prescale.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int, _vp, _vp, _vp]
+    lib.granq_fakequant_fwd.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
+    lib.granq_fakequant_bwd.argtypes = [_vp, _vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp]
+    for name in EXPORTS[2:]:
+        getattr(lib, name).restype = ctypes.c_int
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().granq_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return load().granq_version().decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != GRANQ_OK:
+        raise GranqError(status, where)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GRANQ_F32
+    if t.dtype == torch.bfloat16:
+        return GRANQ_BF16
+    raise TypeError("GranQ takes float32 or bfloat16 tensors, got %s" % t.dtype)
+
+
+def make_desc(n: int, c: int, h: int, w: int, dtype: int) -> granq_desc_t:
+    return granq_desc_t(int(n), int(c), int(h), int(w), int(dtype))
+
+
+def desc_of(x: torch.Tensor) -> granq_desc_t:
+    """Descriptor of a contiguous (N, C, ...) tensor; trailing dims fold into H*W."""
+    if x.dim() < 2:
+        raise ValueError("need an (N, C, ...) tensor")
+    if not x.is_contiguous():
+        raise ValueError("GranQ takes dense contiguous NCHW tensors")
+    hw = 1
+    for d in x.shape[2:]:
+        hw *= int(d)
+    h = int(x.shape[2]) if x.dim() > 2 else 1
+    return make_desc(x.shape[0], x.shape[1], h, hw // h if h else 0, _dtype_code(x))
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU (the library takes device pointers)" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def _vec(t: torch.Tensor, c: int, name: str) -> int:
+    if t.dtype != torch.float32 or t.numel() != c:
+        raise ValueError("%s must be float32 with %d entries" % (name, c))
+    return _dev(t, name)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def granq_workspace_bytes(desc: granq_desc_t) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().granq_workspace_bytes(ctypes.byref(desc), ctypes.byref(out)), "granq_workspace_bytes")
+    return int(out.value)
+
+
+def granq_plan_describe(desc: granq_desc_t) -> dict:
+    out = (ctypes.c_int64 * 10)()
+    _check(load().granq_plan_describe(ctypes.byref(desc), ctypes.byref(out)), "granq_plan_describe")
+    keys = ("vector_path", "rows", "row_len", "hw", "span", "col_tiles", "row_groups",
+            "rows_per_group", "kmax", "uniform")
+    return dict(zip(keys, [int(v) for v in out]))
+
+
+def granq_range_reduce(x: torch.Tensor, ch_min: torch.Tensor, ch_max: torch.Tensor,
+                       workspace: torch.Tensor, stream=None, desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    _check(load().granq_range_reduce(_dev(x, "x"), ctypes.byref(d), _vec(ch_min, d.c, "ch_min"),
+                                     _vec(ch_max, d.c, "ch_max"), _dev(workspace, "workspace"),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)),
+           "granq_range_reduce")
+
+
+def granq_prescale(ch_min: torch.Tensor, ch_max: torch.Tensor, bits: int, scale: torch.Tensor,
+                   zero_point: torch.Tensor, stream=None) -> None:
+    c = ch_min.numel()
+    _check(load().granq_prescale(_vec(ch_min, c, "ch_min"), _vec(ch_max, c, "ch_max"), c, int(bits),
+                                 _vec(scale, c, "scale"), _vec(zero_point, c, "zero_point"),
+                                 _stream(stream)), "granq_prescale")
+
+
+def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
+                        x_hat: torch.Tensor, codes: Optional[torch.Tensor] = None, stream=None,
+                        desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    if x_hat.dtype != x.dtype or x_hat.numel() != x.numel():
+        raise ValueError("x_hat must match x")
+    cp = 0
+    if codes is not None:
+        if codes.dtype != torch.uint8 or codes.numel() != x.numel():
+            raise ValueError("codes must be uint8 with one entry per element")
+        cp = _dev(codes, "codes")
+    _check(load().granq_fakequant_fwd(_dev(x, "x"), ctypes.byref(d), _vec(scale, d.c, "scale"),
+                                      _vec(zero_point, d.c, "zero_point"), int(bits),
+                                      _dev(x_hat, "x_hat"), cp, _stream(stream)),
+           "granq_fakequant_fwd")
+
+
+def granq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, scale: torch.Tensor,
+                        zero_point: torch.Tensor, bits: int, dx: torch.Tensor, stream=None,
+                        desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    if dy.dtype != x.dtype or dx.dtype != x.dtype or dy.numel() != x.numel() or dx.numel() != x.numel():
+        raise ValueError("dy and dx must match x")
+    _check(load().granq_fakequant_bwd(_dev(x, "x"), _dev(dy, "dy"), ctypes.byref(d),
+                                      _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"),
+                                      int(bits), _dev(dx, "dx"), _stream(stream)),
+           "granq_fakequant_bwd")

@@ -1,0 +1,721 @@
+// GranQ activation fake-quantizer: gfx950 kernels and the C ABI around them.
+//
+// Four operations, as in the paper's Alg. 1 up to (not including) the
+// accumulation:
+//   range_reduce   per-channel min / max over (n,h,w)          Eq. 4, Sec. 5.1
+//   prescale       scale and zero-point vectors, all channels  Eq. 5
+//   fakequant_fwd  quantize, clamp, dequantize                 Eq. 1, Eq. 6
+//   fakequant_bwd  straight-through gate                       Sec. 2.1
+//
+// All of them are bound by HBM bandwidth, so the kernels are organised around
+// memory traffic: each element is loaded once with a 128-bit load and stored
+// once with a 128-bit store, and everything per-channel sits in registers (see
+// granq_plan.h for the column-tile decomposition that makes this possible).
+// Tensors whose rows are not a whole number of 16-byte vectors, or whose
+// pointers are not 16-byte aligned, take element-wise kernels ("row" kernels:
+// one wavefront per (n,c) slab, scale and zero-point wave-uniform).
+#include <hip/hip_runtime.h>
+#include <float.h>
+#include <stdint.h>
+
+#include "granq.h"
+#include "granq_device.h"
+#include "granq_plan.h"
+
+namespace granq {
+
+// Vectors per lane and row in the column kernels, and rows in flight per lane.
+#ifndef GRANQ_V_F32
+#define GRANQ_V_F32 2
+#endif
+#ifndef GRANQ_V_BF16
+#define GRANQ_V_BF16 1
+#endif
+#ifndef GRANQ_UNROLL
+#define GRANQ_UNROLL 4
+#endif
+// Non-temporal stores for outputs nobody re-reads soon (x_hat, dx, codes).
+#ifndef GRANQ_NT_STORE
+#define GRANQ_NT_STORE 1
+#endif
+
+template <typename V>
+__device__ inline V load_vec(const V *p) { return *p; }
+
+template <typename V>
+__device__ inline void store_vec(V *p, const V &v) {
+#if GRANQ_NT_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// Per-lane channel parameters for the NS elements (1 if the vector lies inside
+// one channel, else VEC) of a vector starting at column `col`.
+template <int NS>
+__device__ inline void lane_channels(int64_t col, int64_t hw, int32_t (&ch)[NS]) {
+    int64_t c0 = col / hw;
+    int64_t rem = col - c0 * hw;
+    ch[0] = (int32_t)c0;
+#pragma unroll
+    for (int e = 1; e < NS; ++e) {
+        rem += 1;
+        if (rem == hw) { rem = 0; c0 += 1; }
+        ch[e] = (int32_t)c0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// fake-quant forward, column kernel
+// ---------------------------------------------------------------------------
+
+template <typename T, int V, bool UNIFORM, bool CODES>
+__global__ __launch_bounds__(kBlock) void fq_fwd_cols(
+    const typename T::vec_t *__restrict__ x, typename T::vec_t *__restrict__ x_hat,
+    typename T::code_t *__restrict__ codes, const float *__restrict__ scale,
+    const float *__restrict__ zero_point, float qmax, ColPlan plan)
+{
+    constexpr int VEC = T::VEC;
+    constexpr int NS = UNIFORM ? 1 : VEC;
+    constexpr int U = GRANQ_UNROLL;
+    using vec_t = typename T::vec_t;
+
+    const int32_t j = blockIdx.x % plan.col_tiles;
+    const int32_t p = blockIdx.x / plan.col_tiles;
+    const int64_t row_vecs = plan.row_len / VEC;
+
+    float s[V][NS], z[V][NS];
+    int64_t cv[V];           // vector index of this lane's v-th vector within a row
+    bool active[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        int64_t col = (int64_t)j * plan.span + (int64_t)(threadIdx.x + v * kBlock) * VEC;
+        active[v] = col < plan.row_len;
+        cv[v] = col / VEC;
+        int32_t ch[NS];
+        lane_channels<NS>(active[v] ? col : 0, plan.hw, ch);
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            s[v][e] = scale[ch[e]];
+            z[v][e] = zero_point[ch[e]];
+        }
+    }
+
+    const int64_t r0 = (int64_t)p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
+
+    auto body = [&](int64_t r, const int nrows) {
+        vec_t in[U][V];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (u < nrows && active[v]) in[u][v] = load_vec(x + (r + u) * row_vecs + cv[v]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (u < nrows && active[v]) {
+                    float f[VEC], q[VEC];
+                    T::unpack(in[u][v], f);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const float se = s[v][UNIFORM ? 0 : e], ze = z[v][UNIFORM ? 0 : e];
+                        q[e] = clamp_code(raw_code(f[e], se, ze), qmax);
+                        f[e] = dequant(q[e], se, ze);
+                    }
+                    const int64_t at = (r + u) * row_vecs + cv[v];
+                    store_vec(x_hat + at, T::pack(f));
+                    if (CODES) store_vec(codes + at, T::pack_codes(q));
+                }
+    };
+
+    int64_t r = r0;
+    for (; r + U <= r1; r += U) body(r, U);
+    if (r < r1) body(r, (int)(r1 - r));
+}
+
+// ---------------------------------------------------------------------------
+// straight-through backward, column kernel
+// ---------------------------------------------------------------------------
+
+template <typename T, int V, bool UNIFORM>
+__global__ __launch_bounds__(kBlock) void fq_bwd_cols(
+    const typename T::vec_t *__restrict__ x, const typename T::vec_t *__restrict__ dy,
+    typename T::vec_t *__restrict__ dx, const float *__restrict__ scale,
+    const float *__restrict__ zero_point, float qmax, ColPlan plan)
+{
+    constexpr int VEC = T::VEC;
+    constexpr int NS = UNIFORM ? 1 : VEC;
+    constexpr int U = GRANQ_UNROLL;
+    using vec_t = typename T::vec_t;
+
+    const int32_t j = blockIdx.x % plan.col_tiles;
+    const int32_t p = blockIdx.x / plan.col_tiles;
+    const int64_t row_vecs = plan.row_len / VEC;
+
+    float s[V][NS], z[V][NS];
+    int64_t cv[V];
+    bool active[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        int64_t col = (int64_t)j * plan.span + (int64_t)(threadIdx.x + v * kBlock) * VEC;
+        active[v] = col < plan.row_len;
+        cv[v] = col / VEC;
+        int32_t ch[NS];
+        lane_channels<NS>(active[v] ? col : 0, plan.hw, ch);
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            s[v][e] = scale[ch[e]];
+            z[v][e] = zero_point[ch[e]];
+        }
+    }
+
+    const int64_t r0 = (int64_t)p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
+
+    auto body = [&](int64_t r, const int nrows) {
+        vec_t in[U][V], g[U][V];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (u < nrows && active[v]) {
+                    const int64_t at = (r + u) * row_vecs + cv[v];
+                    in[u][v] = load_vec(x + at);
+                    g[u][v] = load_vec(dy + at);
+                }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (u < nrows && active[v]) {
+                    float f[VEC];
+                    bool keep[VEC];
+                    T::unpack(in[u][v], f);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        keep[e] = in_range(raw_code(f[e], s[v][UNIFORM ? 0 : e], z[v][UNIFORM ? 0 : e]), qmax);
+                    store_vec(dx + (r + u) * row_vecs + cv[v], T::gate(g[u][v], keep));
+                }
+    };
+
+    int64_t r = r0;
+    for (; r + U <= r1; r += U) body(r, U);
+    if (r < r1) body(r, (int)(r1 - r));
+}
+
+// ---------------------------------------------------------------------------
+// range reduce, column kernel (pass 1) and its pass 2
+// ---------------------------------------------------------------------------
+//
+// Pass 1: every lane keeps a running min / max per element position of its
+// vectors while walking down its rows.  At the end of the block the lanes'
+// results are combined per channel: a wavefront whose lanes all hold the same
+// channel reduces with DPP and issues one LDS atomic, otherwise each lane issues
+// its own; the per-channel LDS slots are then written to the workspace as
+// partials  ws[(p * J + j) * kmax + (channel - first channel of tile j)].
+// Pass 2: one wavefront per channel gathers the partials of all column tiles
+// that overlap the channel and of all row groups.
+
+template <typename T, int V, bool UNIFORM>
+__global__ __launch_bounds__(kBlock) void range_cols_pass1(
+    const typename T::vec_t *__restrict__ x, float *__restrict__ ws_min,
+    float *__restrict__ ws_max, ColPlan plan)
+{
+    constexpr int VEC = T::VEC;
+    constexpr int NS = UNIFORM ? 1 : VEC;
+    constexpr int U = GRANQ_UNROLL;
+    using vec_t = typename T::vec_t;
+    extern __shared__ uint32_t lds_keys[];          // [kmax] min keys, then [kmax] max keys
+
+    const int32_t j = blockIdx.x % plan.col_tiles;
+    const int32_t p = blockIdx.x / plan.col_tiles;
+    const int64_t row_vecs = plan.row_len / VEC;
+    const int32_t kmax = plan.kmax;
+
+    for (int i = threadIdx.x; i < kmax; i += kBlock) {
+        lds_keys[i] = kKeyPosInf;
+        lds_keys[kmax + i] = kKeyNegInf;
+    }
+
+    float mn[V][NS], mx[V][NS];
+    int64_t cv[V];
+    bool active[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        int64_t col = (int64_t)j * plan.span + (int64_t)(threadIdx.x + v * kBlock) * VEC;
+        active[v] = col < plan.row_len;
+        cv[v] = col / VEC;
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            mn[v][e] = __builtin_inff();
+            mx[v][e] = -__builtin_inff();
+        }
+    }
+
+    const int64_t r0 = (int64_t)p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
+
+    auto body = [&](int64_t r, const int nrows) {
+        vec_t in[U][V];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (u < nrows && active[v]) in[u][v] = load_vec(x + (r + u) * row_vecs + cv[v]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                if (u < nrows && active[v]) {
+                    float f[VEC];
+                    T::unpack(in[u][v], f);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        mn[v][UNIFORM ? 0 : e] = __builtin_fminf(mn[v][UNIFORM ? 0 : e], f[e]);
+                        mx[v][UNIFORM ? 0 : e] = __builtin_fmaxf(mx[v][UNIFORM ? 0 : e], f[e]);
+                    }
+                }
+    };
+
+    int64_t r = r0;
+    for (; r + U <= r1; r += U) body(r, U);
+    if (r < r1) body(r, (int)(r1 - r));
+
+    __syncthreads();                                   // LDS slots initialised
+
+    const int32_t ch_first = (int32_t)(((int64_t)j * plan.span) / plan.hw);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        // inactive lanes hold the identities and point at the tile's first channel
+        int64_t col = active[v] ? cv[v] * VEC : (int64_t)j * plan.span;
+        int32_t ch[NS];
+        lane_channels<NS>(col, plan.hw, ch);
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            const int32_t k = ch[e] - ch_first;
+            const int32_t k_lead = __builtin_amdgcn_readfirstlane(k);
+            if (__all(k == k_lead)) {
+                float wmn = wave_min(mn[v][e]);
+                float wmx = wave_max(mx[v][e]);
+                if ((threadIdx.x & (kWave - 1)) == 0) {
+                    atomicMin(&lds_keys[k_lead], float_key(wmn));
+                    atomicMax(&lds_keys[kmax + k_lead], float_key(wmx));
+                }
+            } else {
+                atomicMin(&lds_keys[k], float_key(mn[v][e]));
+                atomicMax(&lds_keys[kmax + k], float_key(mx[v][e]));
+            }
+        }
+    }
+
+    __syncthreads();
+
+    const int64_t slot = ((int64_t)p * plan.col_tiles + j) * kmax;
+    for (int i = threadIdx.x; i < kmax; i += kBlock) {
+        ws_min[slot + i] = key_float(lds_keys[i]);
+        ws_max[slot + i] = key_float(lds_keys[kmax + i]);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void range_cols_pass2(
+    const float *__restrict__ ws_min, const float *__restrict__ ws_max,
+    float *__restrict__ ch_min, float *__restrict__ ch_max, ColPlan plan)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t c = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x / kWave);
+    if (c >= plan.channels) return;                    // whole wavefront leaves together
+    const int64_t j_lo = (c * plan.hw) / plan.span;
+    const int64_t j_hi = ((c + 1) * plan.hw - 1) / plan.span;
+    const int64_t nj = j_hi - j_lo + 1;
+    const int64_t total = nj * plan.row_groups;
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (int64_t i = lane; i < total; i += kWave) {
+        const int64_t jj = j_lo + i % nj;
+        const int64_t pp = i / nj;
+        const int64_t k = c - (jj * plan.span) / plan.hw;
+        const int64_t at = (pp * plan.col_tiles + jj) * plan.kmax + k;
+        mn = __builtin_fminf(mn, ws_min[at]);
+        mx = __builtin_fmaxf(mx, ws_max[at]);
+    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
+    if (lane == 0) {
+        ch_min[c] = mn;
+        ch_max[c] = mx;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// element-wise fallbacks ("row" kernels): any shape, any element alignment
+// ---------------------------------------------------------------------------
+
+// Block (c, p): channel c, rows [p*rpg, (p+1)*rpg).  Per-lane min/max, DPP
+// within the wavefront, LDS across the four wavefronts, one partial per block.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void range_rows_pass1(
+    const void *__restrict__ x, float *__restrict__ ws_min, float *__restrict__ ws_max,
+    int64_t n, int64_t c, int64_t hw, RowPlan plan)
+{
+    __shared__ float part[2][kBlock / kWave];
+    const int64_t ic = blockIdx.x % c;
+    const int64_t p = blockIdx.x / c;
+    const int64_t r0 = p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < n) ? r0 + plan.rows_per_group : n;
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (int64_t in = r0; in < r1; ++in) {
+        const int64_t base = (in * c + ic) * hw;
+        for (int64_t k = threadIdx.x; k < hw; k += kBlock) {
+            float v = T::load1(x, base + k);
+            mn = __builtin_fminf(mn, v);
+            mx = __builtin_fmaxf(mx, v);
+        }
+    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        part[0][wave] = mn;
+        part[1][wave] = mx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlock / kWave; ++w) {
+            mn = __builtin_fminf(mn, part[0][w]);
+            mx = __builtin_fmaxf(mx, part[1][w]);
+        }
+        ws_min[p * c + ic] = mn;
+        ws_max[p * c + ic] = mx;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void range_rows_pass2(
+    const float *__restrict__ ws_min, const float *__restrict__ ws_max,
+    float *__restrict__ ch_min, float *__restrict__ ch_max, int64_t c, int32_t groups)
+{
+    const int64_t ic = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (ic >= c) return;
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (int32_t p = 0; p < groups; ++p) {
+        mn = __builtin_fminf(mn, ws_min[(int64_t)p * c + ic]);
+        mx = __builtin_fmaxf(mx, ws_max[(int64_t)p * c + ic]);
+    }
+    ch_min[ic] = mn;
+    ch_max[ic] = mx;
+}
+
+// One wavefront per (n,c) slab at a time; scale and zero-point are
+// wave-uniform.  `slabs` = N*C.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fq_fwd_rows(
+    const void *__restrict__ x, void *__restrict__ x_hat, uint8_t *__restrict__ codes,
+    const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax,
+    int64_t slabs, int64_t c, int64_t hw)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const int64_t nwaves = (int64_t)gridDim.x * (kBlock / kWave);
+    for (int64_t slab = wave0; slab < slabs; slab += nwaves) {
+        const int64_t ic = slab % c;
+        const float s = scale[ic], z = zero_point[ic];
+        const int64_t base = slab * hw;
+        for (int64_t k = lane; k < hw; k += kWave) {
+            float q = clamp_code(raw_code(T::load1(x, base + k), s, z), qmax);
+            T::store1(x_hat, base + k, dequant(q, s, z));
+            if (codes) codes[base + k] = (uint8_t)q;
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fq_bwd_rows(
+    const void *__restrict__ x, const void *__restrict__ dy, void *__restrict__ dx,
+    const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax,
+    int64_t slabs, int64_t c, int64_t hw)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const int64_t nwaves = (int64_t)gridDim.x * (kBlock / kWave);
+    for (int64_t slab = wave0; slab < slabs; slab += nwaves) {
+        const int64_t ic = slab % c;
+        const float s = scale[ic], z = zero_point[ic];
+        const int64_t base = slab * hw;
+        for (int64_t k = lane; k < hw; k += kWave) {
+            bool keep = in_range(raw_code(T::load1(x, base + k), s, z), qmax);
+            T::store_gated1(dx, dy, base + k, keep);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// prescale: Eq. 5 for all channels at once
+// ---------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void prescale_kernel(
+    const float *__restrict__ ch_min, const float *__restrict__ ch_max, int64_t c, float qmax,
+    float *__restrict__ scale, float *__restrict__ zero_point)
+{
+    const int64_t ic = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (ic >= c) return;
+    const float mn = ch_min[ic];
+    const float range = ch_max[ic] - mn;
+    float s = range / qmax;
+    if (!(s >= FLT_MIN)) s = 1.0f;                     // zero, subnormal or NaN scale
+    const float z = __builtin_rintf((-mn) / s) + 0.0f; // "+ 0" turns -0 into +0
+    scale[ic] = s;
+    zero_point[ic] = z;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+static granq_status_t check_desc(const granq_desc_t *d) {
+    if (!d) return GRANQ_ERR_INVALID_ARG;
+    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0) return GRANQ_ERR_INVALID_ARG;
+    if (d->dtype != GRANQ_F32 && d->dtype != GRANQ_BF16) return GRANQ_ERR_UNSUPPORTED;
+    // element count and every index must fit in int64 with room to spare
+    const int64_t lim = (int64_t)1 << 40;
+    if (d->n > lim || d->c >= ((int64_t)1 << 31) || d->h > lim || d->w > lim) return GRANQ_ERR_UNSUPPORTED;
+    if (d->h * d->w > lim) return GRANQ_ERR_UNSUPPORTED;
+    __int128 e = (__int128)d->n * d->c * (d->h * d->w);
+    if (e > ((__int128)1 << 46)) return GRANQ_ERR_UNSUPPORTED;
+    return GRANQ_OK;
+}
+
+static bool aligned_elem(const void *p, granq_dtype_t dt) {
+    return ((uintptr_t)p & (dt == GRANQ_F32 ? 3u : 1u)) == 0;
+}
+
+static int vec_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? F32::VEC : BF16::VEC; }
+static int v_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? GRANQ_V_F32 : GRANQ_V_BF16; }
+
+static ColPlan col_plan(const granq_desc_t *d) {
+    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), v_of(d->dtype), kBlock);
+}
+
+static granq_status_t launched() {
+    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+}
+
+// Grid of the row kernels: enough wavefronts to fill the chip, no more than slabs.
+static uint32_t row_grid(int64_t slabs) {
+    int64_t blocks = ceil_div(slabs, kBlock / kWave);
+    int64_t cap = (int64_t)GRANQ_TARGET_BLOCKS * 4;
+    return (uint32_t)(blocks < cap ? blocks : cap);
+}
+
+template <typename T, int V>
+static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8_t *codes,
+                            const float *s, const float *z, float qmax, hipStream_t st) {
+    using vec_t = typename T::vec_t;
+    using code_t = typename T::code_t;
+    dim3 grid((uint32_t)(pl.col_tiles * pl.row_groups)), block(kBlock);
+    auto xv = (const vec_t *)x;
+    auto yv = (vec_t *)x_hat;
+    auto cv = (code_t *)codes;
+    if (pl.uniform) {
+        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, true, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+        else hipLaunchKernelGGL((fq_fwd_cols<T, V, true, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+    } else {
+        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, false, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+        else hipLaunchKernelGGL((fq_fwd_cols<T, V, false, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+    }
+}
+
+template <typename T, int V>
+static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, void *dx,
+                            const float *s, const float *z, float qmax, hipStream_t st) {
+    using vec_t = typename T::vec_t;
+    dim3 grid((uint32_t)(pl.col_tiles * pl.row_groups)), block(kBlock);
+    if (pl.uniform)
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, true>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
+    else
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, false>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
+}
+
+template <typename T, int V>
+static void launch_range_cols(const ColPlan &pl, const void *x, float *ws_min, float *ws_max,
+                              hipStream_t st) {
+    using vec_t = typename T::vec_t;
+    dim3 grid((uint32_t)(pl.col_tiles * pl.row_groups)), block(kBlock);
+    size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
+    if (pl.uniform)
+        hipLaunchKernelGGL((range_cols_pass1<T, V, true>), grid, block, lds, st, (const vec_t *)x, ws_min, ws_max, pl);
+    else
+        hipLaunchKernelGGL((range_cols_pass1<T, V, false>), grid, block, lds, st, (const vec_t *)x, ws_min, ws_max, pl);
+}
+
+static size_t col_ws_floats(const ColPlan &pl) {
+    return (size_t)pl.row_groups * pl.col_tiles * pl.kmax;
+}
+
+}  // namespace granq
+
+using namespace granq;
+
+extern "C" {
+
+const char *granq_status_string(granq_status_t status) {
+    switch (status) {
+        case GRANQ_OK: return "GRANQ_OK";
+        case GRANQ_ERR_INVALID_ARG: return "GRANQ_ERR_INVALID_ARG: null pointer, non-positive dimension or bits outside 1..8";
+        case GRANQ_ERR_UNSUPPORTED: return "GRANQ_ERR_UNSUPPORTED: unknown dtype, misaligned pointer or tensor too large";
+        case GRANQ_ERR_WORKSPACE: return "GRANQ_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case GRANQ_ERR_HIP: return "GRANQ_ERR_HIP: the HIP runtime rejected a launch";
+    }
+    return "GRANQ: unknown status";
+}
+
+const char *granq_version(void) { return "granq-gfx950 0.1"; }
+
+granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out) {
+    if (!bytes_out) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    const int64_t hw = desc->h * desc->w;
+    RowPlan rp = make_row_plan(desc->n, desc->c, hw);
+    size_t floats = (size_t)rp.row_groups * (size_t)desc->c;
+    ColPlan cp = col_plan(desc);
+    if (cp.ok && col_ws_floats(cp) > floats) floats = col_ws_floats(cp);
+    *bytes_out = 2 * floats * sizeof(float);
+    return GRANQ_OK;
+}
+
+granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[10]) {
+    if (!out) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    ColPlan cp = col_plan(desc);
+    out[0] = cp.ok ? 1 : 0;
+    out[1] = cp.rows;
+    out[2] = cp.row_len;
+    out[3] = cp.hw;
+    out[4] = cp.span;
+    out[5] = cp.col_tiles;
+    out[6] = cp.row_groups;
+    out[7] = cp.rows_per_group;
+    out[8] = cp.kmax;
+    out[9] = cp.uniform ? 1 : 0;
+    return GRANQ_OK;
+}
+
+granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float *ch_min,
+                                  float *ch_max, void *workspace, size_t workspace_bytes,
+                                  void *stream) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!x || !ch_min || !ch_max) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(x, desc->dtype) || !aligned_elem(ch_min, GRANQ_F32) || !aligned_elem(ch_max, GRANQ_F32))
+        return GRANQ_ERR_UNSUPPORTED;
+    size_t need = 0;
+    granq_workspace_bytes(desc, &need);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return GRANQ_ERR_WORKSPACE;
+    hipStream_t hs = (hipStream_t)stream;
+    const int64_t hw = desc->h * desc->w;
+    ColPlan cp = col_plan(desc);
+    if (cp.ok && aligned16(x)) {
+        const size_t floats = col_ws_floats(cp);
+        float *ws_min = (float *)workspace;
+        float *ws_max = ws_min + floats;
+        if (desc->dtype == GRANQ_F32) launch_range_cols<F32, GRANQ_V_F32>(cp, x, ws_min, ws_max, hs);
+        else launch_range_cols<BF16, GRANQ_V_BF16>(cp, x, ws_min, ws_max, hs);
+        st = launched();
+        if (st != GRANQ_OK) return st;
+        dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave)), block(kBlock);
+        hipLaunchKernelGGL(range_cols_pass2, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp);
+        return launched();
+    }
+    RowPlan rp = make_row_plan(desc->n, desc->c, hw);
+    const size_t floats = (size_t)rp.row_groups * (size_t)desc->c;
+    float *ws_min = (float *)workspace;
+    float *ws_max = ws_min + floats;
+    dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
+    if (desc->dtype == GRANQ_F32)
+        hipLaunchKernelGGL(range_rows_pass1<F32>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
+    else
+        hipLaunchKernelGGL(range_rows_pass1<BF16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
+    st = launched();
+    if (st != GRANQ_OK) return st;
+    dim3 grid2((uint32_t)ceil_div(desc->c, kBlock));
+    hipLaunchKernelGGL(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, rp.row_groups);
+    return launched();
+}
+
+granq_status_t granq_prescale(const float *ch_min, const float *ch_max, int64_t c, int bits,
+                              float *scale, float *zero_point, void *stream) {
+    if (!ch_min || !ch_max || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (c <= 0 || bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (c >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
+    if (!aligned_elem(ch_min, GRANQ_F32) || !aligned_elem(ch_max, GRANQ_F32) ||
+        !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
+        return GRANQ_ERR_UNSUPPORTED;
+    const float qmax = (float)((1 << bits) - 1);
+    dim3 grid((uint32_t)ceil_div(c, kBlock)), block(kBlock);
+    hipLaunchKernelGGL(prescale_kernel, grid, block, 0, (hipStream_t)stream, ch_min, ch_max, c, qmax, scale, zero_point);
+    return launched();
+}
+
+granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, const float *scale,
+                                   const float *zero_point, int bits, void *x_hat,
+                                   uint8_t *codes_or_null, void *stream) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!x || !x_hat || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(x, desc->dtype) || !aligned_elem(x_hat, desc->dtype) ||
+        !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
+        return GRANQ_ERR_UNSUPPORTED;
+    const float qmax = (float)((1 << bits) - 1);
+    hipStream_t hs = (hipStream_t)stream;
+    ColPlan cp = col_plan(desc);
+    // packed codes are stored VEC bytes at a time
+    const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
+    if (cp.ok && aligned16(x) && aligned16(x_hat) && codes_ok) {
+        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_V_F32>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<BF16, GRANQ_V_BF16>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
+        return launched();
+    }
+    const int64_t hw = desc->h * desc->w;
+    const int64_t slabs = desc->n * desc->c;
+    dim3 grid(row_grid(slabs)), block(kBlock);
+    if (desc->dtype == GRANQ_F32)
+        hipLaunchKernelGGL(fq_fwd_rows<F32>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+    else
+        hipLaunchKernelGGL(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+    return launched();
+}
+
+granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_desc_t *desc,
+                                   const float *scale, const float *zero_point, int bits,
+                                   void *dx, void *stream) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!x || !dy || !dx || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(x, desc->dtype) || !aligned_elem(dy, desc->dtype) || !aligned_elem(dx, desc->dtype) ||
+        !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
+        return GRANQ_ERR_UNSUPPORTED;
+    const float qmax = (float)((1 << bits) - 1);
+    hipStream_t hs = (hipStream_t)stream;
+    ColPlan cp = col_plan(desc);
+    if (cp.ok && aligned16(x) && aligned16(dy) && aligned16(dx)) {
+        if (desc->dtype == GRANQ_F32) launch_bwd_cols<F32, GRANQ_V_F32>(cp, x, dy, dx, scale, zero_point, qmax, hs);
+        else launch_bwd_cols<BF16, GRANQ_V_BF16>(cp, x, dy, dx, scale, zero_point, qmax, hs);
+        return launched();
+    }
+    const int64_t hw = desc->h * desc->w;
+    const int64_t slabs = desc->n * desc->c;
+    dim3 grid(row_grid(slabs)), block(kBlock);
+    if (desc->dtype == GRANQ_F32)
+        hipLaunchKernelGGL(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+    else
+        hipLaunchKernelGGL(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+    return launched();
+}
+
+}  // extern "C"

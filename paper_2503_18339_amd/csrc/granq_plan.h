@@ -1,0 +1,110 @@
+// Host-side launch planning for the GranQ kernels.
+//
+// A dense NCHW tensor is a matrix of N rows by L = C*H*W columns, and the
+// channel of an element depends on its COLUMN only: channel = column / (H*W).
+// The vectorised kernels exploit this: a block owns a span of columns and walks
+// down the rows, so every lane works for the same channel(s) during its whole
+// life and keeps their scale / zero-point (or its running min / max) in
+// registers.  No index arithmetic and no table lookup is left in the loop over
+// the data.
+//
+//   columns:  J tiles of `span` = kBlock * VEC * V elements (VEC = 16 bytes'
+//             worth of elements, V vectors per lane and row)
+//   rows:     P groups of `rows_per_group` consecutive rows
+//   grid:     J * P blocks, column tile fastest, so that blocks that are
+//             resident together read neighbouring spans of the same rows.
+//
+// A tensor with a single channel (the layer-wise view {1,1,1,E}) has only one
+// row; since every element then belongs to channel 0 the matrix may be folded
+// to any rows x columns factorisation, and the plan does so.
+#pragma once
+
+#include <stdint.h>
+#include <stddef.h>
+
+namespace granq {
+
+// Resident blocks the plan aims for: 256 compute units x 8 blocks of 4 waves.
+#ifndef GRANQ_TARGET_BLOCKS
+#define GRANQ_TARGET_BLOCKS 2048
+#endif
+// Fewest rows a block should walk before the plan stops splitting the rows.
+#ifndef GRANQ_MIN_ROWS
+#define GRANQ_MIN_ROWS 4
+#endif
+
+struct ColPlan {
+    int64_t rows;            // rows of the (possibly folded) matrix
+    int64_t row_len;         // columns (elements per row)
+    int64_t hw;              // elements per channel within a row
+    int32_t channels;        // channels per row
+    int32_t span;            // columns per block
+    int32_t col_tiles;       // J
+    int32_t row_groups;      // P
+    int32_t rows_per_group;
+    int32_t kmax;            // most channels any column tile touches
+    bool uniform;            // every 16-byte vector lies inside one channel
+    bool ok;                 // false: shape not eligible for the vector kernels
+};
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// vec = elements per 16 bytes, v = vectors per lane and row, block = threads.
+inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, int block) {
+    ColPlan p{};
+    p.ok = false;
+    int64_t rows = n, row_len = c * hw, chan = c, per = hw;
+    if (c == 1) {
+        // fold rows * row_len = E so that rows is a power of two up to 1024
+        // and the row length stays a multiple of the vector width
+        int64_t e = n * hw;
+        if (e % vec != 0) return p;
+        int64_t r = 1;
+        while (r < 1024 && (e / vec) % (2 * r) == 0 && e / (2 * r) >= (int64_t)block * vec * v) r *= 2;
+        rows = r;
+        row_len = e / r;
+        per = row_len;
+        chan = 1;
+    }
+    if (row_len % vec != 0) return p;
+    if (row_len >= (int64_t)1 << 31) return p;
+    p.rows = rows;
+    p.row_len = row_len;
+    p.hw = per;
+    p.channels = (int32_t)chan;
+    p.span = block * vec * v;
+    p.col_tiles = (int32_t)ceil_div(row_len, p.span);
+    int64_t want = ceil_div(GRANQ_TARGET_BLOCKS, p.col_tiles);
+    int64_t most = rows / GRANQ_MIN_ROWS > 0 ? rows / GRANQ_MIN_ROWS : 1;
+    int64_t groups = want < most ? want : most;
+    if (groups < 1) groups = 1;
+    p.rows_per_group = (int32_t)ceil_div(rows, groups);
+    p.row_groups = (int32_t)ceil_div(rows, p.rows_per_group);
+    if ((int64_t)p.col_tiles * p.row_groups >= (int64_t)1 << 31) return p;
+    int64_t k = (p.span - 1) / per + 2;
+    p.kmax = (int32_t)(k < chan ? k : chan);
+    p.uniform = (per % vec) == 0;
+    p.ok = true;
+    return p;
+}
+
+// Fallback ("row") plan: one channel per block, P groups of rows.
+struct RowPlan {
+    int32_t row_groups;
+    int32_t rows_per_group;
+};
+
+inline RowPlan make_row_plan(int64_t n, int64_t c, int64_t hw) {
+    RowPlan p{};
+    int64_t want = ceil_div(GRANQ_TARGET_BLOCKS, c);
+    // keep at least ~4096 elements per block where the tensor allows it
+    int64_t min_rows = ceil_div(4096, hw);
+    int64_t most = n / min_rows > 0 ? n / min_rows : 1;
+    int64_t groups = want < most ? want : most;
+    if (groups < 1) groups = 1;
+    p.rows_per_group = (int32_t)ceil_div(n, groups);
+    p.row_groups = (int32_t)ceil_div(n, p.rows_per_group);
+    return p;
+}
+
+}  // namespace granq

@@ -1,0 +1,61 @@
+"""Buffer management for one activation tensor: the four calls in sequence.
+
+Holds the caller-side buffers (ranges, scale, zero-point, workspace) that the
+C ABI expects the caller to own, and issues range_reduce -> prescale -> forward
+(and backward) on the current stream.  No arithmetic happens here.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as B
+
+
+class ActivationQuantizer:
+    """Per-channel fake-quantizer for tensors of one fixed shape and dtype."""
+
+    def __init__(self, shape, dtype: torch.dtype, bits: int, device="cuda", view: str = "channel"):
+        n, c = int(shape[0]), int(shape[1])
+        hw = 1
+        for d in shape[2:]:
+            hw *= int(d)
+        h = int(shape[2]) if len(shape) > 2 else 1
+        w = hw // h
+        code = B.GRANQ_F32 if dtype == torch.float32 else B.GRANQ_BF16
+        if view == "channel":            # one range per channel over (n,h,w)
+            self.desc = B.make_desc(n, c, h, w, code)
+        elif view == "layer":            # one range for the whole tensor
+            self.desc = B.make_desc(1, 1, 1, n * c * hw, code)
+        elif view == "sample_channel":   # one range per (n,c)
+            self.desc = B.make_desc(1, n * c, h, w, code)
+        else:
+            raise ValueError("unknown view %r" % view)
+        self.bits = int(bits)
+        self.shape = tuple(shape)
+        self.dtype = dtype
+        cc = self.desc.c
+        f32 = dict(dtype=torch.float32, device=device)
+        self.ch_min = torch.empty(cc, **f32)
+        self.ch_max = torch.empty(cc, **f32)
+        self.scale = torch.empty(cc, **f32)
+        self.zero_point = torch.empty(cc, **f32)
+        self.workspace = torch.empty(max(16, B.granq_workspace_bytes(self.desc)), dtype=torch.uint8,
+                                     device=device)
+
+    def calibrate(self, x: torch.Tensor, stream=None) -> None:
+        """range_reduce + prescale: refresh scale / zero-point from x."""
+        B.granq_range_reduce(x, self.ch_min, self.ch_max, self.workspace, stream, self.desc)
+        B.granq_prescale(self.ch_min, self.ch_max, self.bits, self.scale, self.zero_point, stream)
+
+    def forward(self, x: torch.Tensor, x_hat: torch.Tensor, codes: Optional[torch.Tensor] = None,
+                stream=None, recalibrate: bool = True) -> torch.Tensor:
+        if recalibrate:
+            self.calibrate(x, stream)
+        B.granq_fakequant_fwd(x, self.scale, self.zero_point, self.bits, x_hat, codes, stream, self.desc)
+        return x_hat
+
+    def backward(self, x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, stream=None) -> torch.Tensor:
+        B.granq_fakequant_bwd(x, dy, self.scale, self.zero_point, self.bits, dx, stream, self.desc)
+        return dx

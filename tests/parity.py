@@ -1,0 +1,154 @@
+"""Helpers for the GPU-vs-oracle parity tests: run the HIP library through its
+C ABI, run the oracle on the same bits, compare element by element."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2503_18339_amd as G
+
+WORKERS = 8
+
+
+def to_numpy(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> host array the oracle takes (bf16 as uint16 bit patterns)."""
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def bits_view(a: np.ndarray) -> np.ndarray:
+    if a.dtype == np.float32:
+        return a.view(np.uint32)
+    return a
+
+
+def values(a: np.ndarray) -> np.ndarray:
+    if a.dtype == np.uint16:
+        return oracle.f32_from_bf16_bits(a)
+    return a
+
+
+def _chunks(n, parts):
+    step = max(1, -(-n // parts))
+    return [(i, min(n, i + step)) for i in range(0, n, step)]
+
+
+def oracle_fwd(x, s, z, bits, workers=WORKERS):
+    """Oracle forward; large tensors are split over the batch across threads
+    (the forward is element-wise once scale and zero-point are given)."""
+    if x.size < (1 << 22) or x.shape[0] < 2:
+        return oracle.fakequant_fwd(x, s, z, bits)
+    xhat = np.empty_like(x)
+    codes = np.empty(x.shape, np.uint8)
+
+    def work(rng):
+        a, b = rng
+        xhat[a:b], codes[a:b] = oracle.fakequant_fwd(x[a:b], s, z, bits)
+
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(work, _chunks(x.shape[0], workers * 2)))
+    return xhat, codes
+
+
+def oracle_bwd(x, dy, s, z, bits, workers=WORKERS):
+    if x.size < (1 << 22) or x.shape[0] < 2:
+        return oracle.fakequant_bwd(x, dy, s, z, bits)
+    dx = np.empty_like(x)
+
+    def work(rng):
+        a, b = rng
+        dx[a:b] = oracle.fakequant_bwd(x[a:b], dy[a:b], s, z, bits)
+
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(work, _chunks(x.shape[0], workers * 2)))
+    return dx
+
+
+def gpu_path(x: torch.Tensor, bits: int, dy: torch.Tensor = None, want_codes=True, desc=None,
+             scale=None, zero_point=None):
+    """range_reduce -> prescale -> fwd (-> bwd) through the C ABI.  Returns host arrays."""
+    d = desc or G.desc_of(x)
+    c = d.c
+    dev = x.device
+    out = {}
+    f32 = dict(dtype=torch.float32, device=dev)
+    if scale is None:
+        ch_min = torch.full((c,), float("nan"), **f32)
+        ch_max = torch.full((c,), float("nan"), **f32)
+        ws = torch.empty(max(16, G.granq_workspace_bytes(d)), dtype=torch.uint8, device=dev)
+        s = torch.full((c,), float("nan"), **f32)
+        z = torch.full((c,), float("nan"), **f32)
+        G.granq_range_reduce(x, ch_min, ch_max, ws, desc=d)
+        G.granq_prescale(ch_min, ch_max, bits, s, z)
+        out["min"], out["max"] = ch_min.cpu().numpy(), ch_max.cpu().numpy()
+    else:
+        s = torch.as_tensor(scale, **f32)
+        z = torch.as_tensor(zero_point, **f32)
+    x_hat = torch.empty_like(x)
+    codes = torch.full(x.shape, 255, dtype=torch.uint8, device=dev) if want_codes else None
+    G.granq_fakequant_fwd(x, s, z, bits, x_hat, codes, desc=d)
+    out["scale"], out["zero_point"] = s.cpu().numpy(), z.cpu().numpy()
+    out["xhat"] = to_numpy(x_hat)
+    if want_codes:
+        out["codes"] = codes.cpu().numpy()
+    if dy is not None:
+        dx = torch.empty_like(x)
+        G.granq_fakequant_bwd(x, dy, s, z, bits, dx, desc=d)
+        out["dx"] = to_numpy(dx)
+    torch.cuda.synchronize()
+    return out
+
+
+def oracle_path(x_np: np.ndarray, bits: int, dy_np: np.ndarray = None, view_shape=None,
+                scale=None, zero_point=None):
+    xv = x_np.reshape(view_shape) if view_shape else x_np
+    out = {}
+    if scale is None:
+        mn, mx = oracle.range_reduce(xv)
+        s, z = oracle.prescale(mn, mx, bits)
+        out["min"], out["max"] = mn, mx
+    else:
+        s, z = np.asarray(scale, np.float32), np.asarray(zero_point, np.float32)
+    out["scale"], out["zero_point"] = s, z
+    xhat, codes = oracle_fwd(xv, s, z, bits)
+    out["xhat"], out["codes"] = xhat.reshape(x_np.shape), codes.reshape(x_np.shape)
+    if dy_np is not None:
+        dyv = dy_np.reshape(view_shape) if view_shape else dy_np
+        out["dx"] = oracle_bwd(xv, dyv, s, z, bits).reshape(x_np.shape)
+    return out
+
+
+def first_mismatch(a, b):
+    bad = np.nonzero(a.ravel() != b.ravel())[0]
+    return None if bad.size == 0 else (int(bad[0]), bad.size)
+
+
+def assert_parity(got: dict, want: dict, what=""):
+    """The bar: ranges equal as values (+0 == -0), scale / zero-point bit-exact, codes
+    bit-exact, x_hat equal as values and within 1e-6 relative, dx bit-exact."""
+    for key in ("min", "max"):
+        if key in want and key in got:
+            assert np.array_equal(got[key], want[key]), "%s %s differs: %r" % (
+                what, key, first_mismatch(got[key], want[key]))
+    for key in ("scale", "zero_point"):
+        assert np.array_equal(bits_view(got[key]), bits_view(want[key])), "%s %s not bit-exact: %r" % (
+            what, key, first_mismatch(bits_view(got[key]), bits_view(want[key])))
+    if "codes" in got:
+        mm = first_mismatch(got["codes"], want["codes"])
+        assert mm is None, "%s codes differ at flat index %d (%d in total)" % ((what,) + mm)
+    gv, wv = values(got["xhat"]), values(want["xhat"])
+    # tolerance for floating-point outputs: 1e-6 relative
+    tol = 1e-6 * np.abs(wv)
+    assert np.all(np.abs(gv.astype(np.float64) - wv.astype(np.float64)) <= tol), what + " xhat beyond 1e-6 relative"
+    mm = first_mismatch(gv, wv)              # expectation: identical values (only +-0 may differ in bits)
+    assert mm is None, "%s xhat differs at flat index %d (%d in total)" % ((what,) + mm)
+    if got["xhat"].dtype == np.uint16:
+        nz = wv != 0
+        assert np.array_equal(got["xhat"][nz], want["xhat"][nz]), what + " bf16 xhat bits differ"
+    if "dx" in want and "dx" in got:
+        g, w = got["dx"], want["dx"]
+        mm = first_mismatch(bits_view(g), bits_view(w))
+        assert mm is None, "%s dx not bit-exact at flat index %d (%d in total)" % ((what,) + mm)

@@ -1,0 +1,197 @@
+"""The C ABI without a GPU: the library loads, exports what include/granq.h
+declares, validates its arguments before touching the device, and plans tilings
+whose index arithmetic stays inside the tensor and the workspace."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2503_18339_amd as G
+from paper_2503_18339_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "granq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(granq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = G.load()
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_status_strings():
+    assert "gfx950" in G.version()
+    seen = set()
+    for code in range(5):
+        s = G.status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in G.status_string(99)
+
+
+def _call_fwd(lib, desc, x=16, s=16, z=16, bits=4, out=16, codes=0):
+    return lib.granq_fakequant_fwd(x, ctypes.byref(desc), s, z, bits, out, codes, 0)
+
+
+def test_argument_validation_happens_before_any_gpu_work():
+    """Bad arguments are refused on the host (these calls run with no GPU present)."""
+    lib = G.load()
+    good = G.make_desc(2, 3, 4, 4, G.GRANQ_F32)
+    # bits outside 1..8
+    for bits in (0, 9, -1):
+        assert _call_fwd(lib, good, bits=bits) == G.GRANQ_ERR_INVALID_ARG
+        assert lib.granq_fakequant_bwd(16, 16, ctypes.byref(good), 16, 16, bits, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+        assert lib.granq_prescale(16, 16, 3, bits, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+    # null pointers
+    assert _call_fwd(lib, good, x=0) == G.GRANQ_ERR_INVALID_ARG
+    assert _call_fwd(lib, good, s=0) == G.GRANQ_ERR_INVALID_ARG
+    assert _call_fwd(lib, good, out=0) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_fakequant_bwd(16, 0, ctypes.byref(good), 16, 16, 4, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_prescale(0, 16, 3, 4, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_range_reduce(0, ctypes.byref(good), 16, 16, 16, 1 << 20, 0) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_fakequant_fwd(16, None, 16, 16, 4, 16, 0, 0) == G.GRANQ_ERR_INVALID_ARG
+    # non-positive dims, channel count
+    for bad in [(0, 3, 4, 4), (2, 0, 4, 4), (2, 3, -1, 4), (2, 3, 4, 0)]:
+        assert _call_fwd(lib, G.make_desc(*bad, G.GRANQ_F32)) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_prescale(16, 16, 0, 4, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+    # unknown dtype, absurd size, misaligned element pointers
+    assert _call_fwd(lib, G.make_desc(2, 3, 4, 4, 7)) == G.GRANQ_ERR_UNSUPPORTED
+    assert _call_fwd(lib, G.make_desc(1 << 30, 1 << 20, 1 << 10, 1 << 10, 0)) == G.GRANQ_ERR_UNSUPPORTED
+    assert _call_fwd(lib, good, x=18) == G.GRANQ_ERR_UNSUPPORTED            # float32 at 2 mod 4
+    assert _call_fwd(lib, G.make_desc(2, 3, 4, 4, G.GRANQ_BF16), x=17) == G.GRANQ_ERR_UNSUPPORTED
+    assert _call_fwd(lib, good, s=18) == G.GRANQ_ERR_UNSUPPORTED
+    # workspace: missing, too small, misaligned
+    need = G.granq_workspace_bytes(good)
+    assert need > 0
+    assert lib.granq_range_reduce(16, ctypes.byref(good), 16, 16, 0, need, 0) == G.GRANQ_ERR_WORKSPACE
+    assert lib.granq_range_reduce(16, ctypes.byref(good), 16, 16, 16, need - 1, 0) == G.GRANQ_ERR_WORKSPACE
+    assert lib.granq_range_reduce(16, ctypes.byref(good), 16, 16, 20, need, 0) == G.GRANQ_ERR_WORKSPACE
+    out = ctypes.c_size_t()
+    assert lib.granq_workspace_bytes(ctypes.byref(good), None) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_workspace_bytes(None, ctypes.byref(out)) == G.GRANQ_ERR_INVALID_ARG
+
+
+def test_binding_refuses_cpu_tensors_and_wrong_shapes():
+    import torch
+    x = torch.zeros(2, 3, 4, 4)
+    v = torch.zeros(3)
+    with pytest.raises(ValueError, match="GPU"):
+        G.granq_fakequant_fwd(x, v, v, 4, torch.empty_like(x))
+    with pytest.raises(TypeError):
+        G.desc_of(x.double())
+    with pytest.raises(ValueError):
+        G.desc_of(x.permute(0, 2, 3, 1))
+    with pytest.raises(G.GranqError) as ei:
+        G.granq_workspace_bytes(G.make_desc(0, 1, 1, 1, 0))
+    assert ei.value.status == G.GRANQ_ERR_INVALID_ARG
+
+
+SHAPES = [
+    (8, 16, 32, 32), (256, 64, 112, 112), (256, 64, 56, 56), (256, 128, 28, 28), (256, 256, 14, 14),
+    (256, 512, 7, 7), (256, 2048, 7, 7), (256, 960, 7, 7), (256, 24, 56, 56), (1, 1, 1, 205520896),
+    (1, 1, 1, 4096), (1, 2048, 7, 7), (3, 40, 1, 1), (5, 37, 9, 8), (2, 3, 7, 7), (4, 8, 7, 7),
+    (1, 64, 1, 1152), (7, 12, 14, 14), (1, 1, 1, 131072 * 3), (2, 1, 5, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", [G.GRANQ_F32, G.GRANQ_BF16])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_plan_invariants(shape, dtype):
+    n, c, h, w = shape
+    d = G.make_desc(n, c, h, w, dtype)
+    pl = G.granq_plan_describe(d)
+    need = G.granq_workspace_bytes(d)
+    vec = 4 if dtype == G.GRANQ_F32 else 8
+    e = n * c * h * w
+    assert need >= 8 and need % 8 == 0
+    if not pl["vector_path"]:
+        assert (c * h * w) % vec != 0 or (c == 1 and e % vec != 0)
+        return
+    assert pl["rows"] * pl["row_len"] == e
+    assert pl["row_len"] % vec == 0 and pl["row_len"] < 2 ** 31
+    if c == 1:
+        assert pl["hw"] == pl["row_len"]
+    else:
+        assert pl["hw"] == h * w and pl["rows"] == n and pl["row_len"] == c * h * w
+    assert pl["span"] % (256 * vec) == 0
+    assert (pl["col_tiles"] - 1) * pl["span"] < pl["row_len"] <= pl["col_tiles"] * pl["span"]
+    assert (pl["row_groups"] - 1) * pl["rows_per_group"] < pl["rows"] <= pl["row_groups"] * pl["rows_per_group"]
+    assert pl["uniform"] == (1 if pl["hw"] % vec == 0 else 0)
+    assert 2 * 4 * pl["row_groups"] * pl["col_tiles"] * pl["kmax"] <= need
+    # every column tile touches at most kmax channels
+    j = np.arange(pl["col_tiles"], dtype=np.int64)
+    first = (j * pl["span"]) // pl["hw"]
+    last = (np.minimum((j + 1) * pl["span"], pl["row_len"]) - 1) // pl["hw"]
+    assert int((last - first).max()) + 1 <= pl["kmax"]
+    assert int(last.max()) == pl["row_len"] // pl["hw"] - 1
+
+
+def _emulate_range_cols(x2d, pl, vec):
+    """Index arithmetic of the two reduction passes, replayed with numpy: returns
+    (ch_min, ch_max) and checks every partial slot that pass 2 reads was written."""
+    rows, row_len = x2d.shape
+    span, hw, kmax = pl["span"], pl["hw"], pl["kmax"]
+    J, P, rpg = pl["col_tiles"], pl["row_groups"], pl["rows_per_group"]
+    channels = row_len // hw
+    v_per_lane = span // (256 * vec)
+    ws_min = np.full(P * J * kmax, np.nan, np.float32)
+    ws_max = np.full(P * J * kmax, np.nan, np.float32)
+    for p in range(P):
+        r0, r1 = p * rpg, min(rows, (p + 1) * rpg)
+        assert r0 < r1
+        for j in range(J):
+            lds_min = np.full(kmax, np.inf, np.float32)
+            lds_max = np.full(kmax, -np.inf, np.float32)
+            ch_first = (j * span) // hw
+            for v in range(v_per_lane):
+                cols = j * span + (np.arange(256) + v * 256) * vec
+                for col in cols[cols < row_len]:
+                    for e in range(vec):
+                        k = (col + e) // hw - ch_first
+                        assert 0 <= k < kmax
+                        seg = x2d[r0:r1, col + e]
+                        lds_min[k] = min(lds_min[k], seg.min())
+                        lds_max[k] = max(lds_max[k], seg.max())
+            slot = (p * J + j) * kmax
+            ws_min[slot:slot + kmax] = lds_min
+            ws_max[slot:slot + kmax] = lds_max
+    mn = np.empty(channels, np.float32)
+    mx = np.empty(channels, np.float32)
+    for c in range(channels):
+        j_lo, j_hi = (c * hw) // span, ((c + 1) * hw - 1) // span
+        vals_min, vals_max = [], []
+        for p in range(P):
+            for jj in range(j_lo, j_hi + 1):
+                k = c - (jj * span) // hw
+                at = (p * J + jj) * kmax + k
+                assert 0 <= k < kmax and not np.isnan(ws_min[at])
+                vals_min.append(ws_min[at])
+                vals_max.append(ws_max[at])
+        mn[c], mx[c] = min(vals_min), max(vals_max)
+    return mn, mx
+
+
+@pytest.mark.parametrize("shape,dtype", [((5, 37, 9, 8), G.GRANQ_F32), ((6, 100, 7, 7), G.GRANQ_F32),
+                                         ((3, 40, 1, 1), G.GRANQ_F32), ((9, 24, 14, 14), G.GRANQ_BF16),
+                                         ((4, 3000, 1, 1), G.GRANQ_BF16), ((1, 1, 1, 16384), G.GRANQ_F32)])
+def test_two_pass_reduction_indexing(shape, dtype):
+    n, c, h, w = shape
+    pl = G.granq_plan_describe(G.make_desc(n, c, h, w, dtype))
+    assert pl["vector_path"]
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(shape).astype(np.float32)
+    vec = 4 if dtype == G.GRANQ_F32 else 8
+    mn, mx = _emulate_range_cols(x.reshape(pl["rows"], pl["row_len"]), pl, vec)
+    if c == 1:
+        assert mn[0] == x.min() and mx[0] == x.max() and mn.size == 1
+    else:
+        assert np.array_equal(mn, x.min(axis=(0, 2, 3))) and np.array_equal(mx, x.max(axis=(0, 2, 3)))

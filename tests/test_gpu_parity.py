@@ -1,0 +1,189 @@
+"""HIP library vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_18339_amd as G
+import workloads
+from golden_cases import load_cases
+from parity import assert_parity, gpu_path, oracle_path, to_numpy
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def _loaded_native_library():
+    with open("/proc/self/maps") as fh:
+        return any("libgranq.so" in line for line in fh)
+
+
+def test_native_library_is_what_runs():
+    G.load()
+    assert _loaded_native_library(), "libgranq.so is not mapped into this process"
+    assert torch.cuda.is_available()
+
+
+def _check(x, bits, seed=0, desc=None, view_shape=None, what=""):
+    dy = workloads.make_grad(x.shape, seed, x.device, x.dtype)
+    got = gpu_path(x, bits, dy, desc=desc)
+    want = oracle_path(to_numpy(x), bits, to_numpy(dy), view_shape=view_shape)
+    assert_parity(got, want, what)
+    return got, want
+
+
+def test_config1_resnet20_first_layer():
+    wl = workloads.resnet20_first_layer()
+    a = wl.acts[0]
+    x = workloads.make_activation(a.shape(wl.batch), a.law, wl.sigma, 0, DEV)
+    got, want = _check(x, 3, 0, what="config1")
+    assert np.all(got["min"] >= 0)
+    assert got["codes"].max() == 7
+
+
+# Shapes chosen to span several column tiles (2048 elements per tile), ragged
+# last tiles, channels straddling tiles and vectors, tiny and unit dimensions.
+SMALL = [
+    (8, 16, 32, 32), (5, 37, 9, 8), (6, 100, 7, 7), (3, 40, 1, 1), (9, 24, 14, 14), (4, 3000, 1, 1),
+    (1, 1, 1, 16384), (2, 1, 5, 4), (1, 64, 1, 1152), (7, 12, 14, 14), (1, 2048, 7, 7), (13, 8, 7, 7),
+    (17, 520, 2, 2), (4, 4, 64, 65), (1, 1, 1, 4), (1, 4, 1, 1), (31, 8, 1, 3),
+    # no 16-byte structure: element-wise kernels
+    (2, 3, 7, 7), (5, 7, 3, 3), (1, 1, 1, 5), (3, 1, 7, 3), (1, 1, 1, 1), (2, 5, 1, 1), (4, 9, 5, 5),
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "x".join(map(str, s)))
+def test_small_shapes(shape, dtype):
+    for i, (law, bits) in enumerate([("relu", 3), ("linear", 4), ("laplace", 8), ("relu6", 1)]):
+        x = workloads.make_activation(shape, law, (0.05, 20.0), seed=i, device=DEV, dtype=dtype)
+        _check(x, bits, i, what="%s %s b%d" % (shape, law, bits))
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_every_bit_width(bits):
+    x = workloads.make_activation((6, 20, 12, 12), "linear", (0.05, 20.0), seed=bits, device=DEV)
+    got, _ = _check(x, bits, bits, what="bits=%d" % bits)
+    assert got["codes"].max() == 2 ** bits - 1 and got["codes"].min() == 0
+
+
+def test_golden_examples_on_gpu():
+    """The hand-derived worked examples, through the HIP library."""
+    for cs in load_cases():
+        shape = cs["shape"]
+        dt = torch.float32 if cs["dtype"] == "f32" else torch.bfloat16
+        x = torch.tensor(cs["x"], dtype=torch.float32).reshape(shape).to(dt).to(DEV)
+        dyv = 1.0 + np.arange(x.numel()) / 8.0
+        dy = torch.tensor(dyv, dtype=torch.float32).reshape(shape).to(dt).to(DEV)
+        kw = {}
+        if "given_scale" in cs:
+            kw = dict(scale=cs["given_scale"].astype(np.float32), zero_point=cs["given_zero_point"].astype(np.float32))
+        got = gpu_path(x, cs["bits"], dy, **kw)
+        name = cs["name"]
+        if not kw:
+            assert np.array_equal(got["min"], cs["min"].astype(np.float32)), name
+            assert np.array_equal(got["max"], cs["max"].astype(np.float32)), name
+            assert np.array_equal(got["scale"], cs["scale"].astype(np.float32)), name
+            assert np.array_equal(got["zero_point"], cs["zero_point"].astype(np.float32)), name
+            assert not np.any(np.signbit(got["zero_point"]) & (got["zero_point"] == 0)), name
+        assert np.array_equal(got["codes"].ravel(), cs["codes"].astype(np.uint8)), name
+        from parity import values
+        assert np.array_equal(values(got["xhat"]).ravel(), cs["xhat"].astype(np.float32)), name
+        assert np.array_equal(values(got["dx"]).ravel(), (dyv * cs["mask"]).astype(np.float32)), name
+
+
+def test_stale_ranges_clamp_both_sides():
+    """Scale / zero-point from another tensor: both clamp sides and the gate are exercised."""
+    for dtype in (torch.float32, torch.bfloat16):
+        ref = workloads.make_activation((4, 24, 14, 14), "linear", (0.5, 2.0), seed=1, device=DEV, dtype=dtype)
+        x = workloads.make_activation((4, 24, 14, 14), "linear", (0.5, 6.0), seed=2, device=DEV, dtype=dtype)
+        dy = workloads.make_grad(x.shape, 3, DEV, dtype)
+        base = gpu_path(ref, 4)
+        got = gpu_path(x, 4, dy, scale=base["scale"], zero_point=base["zero_point"])
+        want = oracle_path(to_numpy(x), 4, to_numpy(dy), scale=base["scale"], zero_point=base["zero_point"])
+        assert_parity(got, want, "stale ranges")
+        from parity import values
+        gated = (values(got["dx"]) == 0) & (values(to_numpy(dy)) != 0)
+        assert 0.01 < gated.mean() < 0.9
+        assert (got["codes"] == 0).any() and (got["codes"] == 15).any()
+
+
+def test_dead_and_constant_channels():
+    x = workloads.make_activation((4, 8, 7, 8), "relu", (0.05, 20.0), seed=5, device=DEV)
+    x[:, 2] = 0.0
+    x[:, 5] = 2.5
+    x[:, 6] = -1e-30
+    got, want = _check(x, 4, 5, what="degenerate")
+    assert got["scale"][2] == 1.0 and got["zero_point"][2] == 0.0
+    assert np.all(got["xhat"][:, 2] == 0) and np.all(got["codes"][:, 2] == 0)
+    assert got["scale"][5] == 1.0 and np.all(got["xhat"][:, 5] == 2.0)
+
+
+def test_subnormal_and_huge_values():
+    x = torch.empty(2, 4, 4, 4, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(0)
+    x[:, 0] = torch.rand(2, 4, 4, generator=g, device=DEV) * 1e-38          # subnormal range
+    x[:, 1] = torch.rand(2, 4, 4, generator=g, device=DEV) * 1e-36
+    x[:, 2] = (torch.rand(2, 4, 4, generator=g, device=DEV) - 0.5) * 1e37   # range near overflow
+    x[:, 3] = torch.rand(2, 4, 4, generator=g, device=DEV) * 1e-44
+    _check(x, 4, 0, what="extreme magnitudes")
+
+
+def test_layerwise_and_per_sample_views():
+    x = workloads.make_activation((6, 12, 16, 16), "relu", (0.05, 20.0), seed=9, device=DEV)
+    e = x.numel()
+    _check(x, 3, 1, desc=G.make_desc(1, 1, 1, e, G.GRANQ_F32), view_shape=(1, 1, 1, e), what="layer-wise view")
+    _check(x, 3, 2, desc=G.make_desc(1, 6 * 12, 16, 16, G.GRANQ_F32), view_shape=(1, 72, 16, 16), what="per-sample view")
+    w = workloads.make_activation((1, 64, 1, 32 * 9), "linear", (0.01, 0.2), seed=4, device=DEV)
+    _check(w, 4, 3, what="weight view")
+
+
+def test_in_place_forward_and_gradient():
+    x = workloads.make_activation((4, 16, 14, 14), "linear", (0.05, 20.0), seed=3, device=DEV)
+    dy = workloads.make_grad(x.shape, 3, DEV)
+    ref = gpu_path(x, 4, dy)
+    s = torch.tensor(ref["scale"], device=DEV)
+    z = torch.tensor(ref["zero_point"], device=DEV)
+    x2, dy2 = x.clone(), dy.clone()
+    G.granq_fakequant_bwd(x2, dy2, s, z, 4, dy2)       # dx aliases dy
+    G.granq_fakequant_fwd(x2, s, z, 4, x2)             # x_hat aliases x
+    torch.cuda.synchronize()
+    assert np.array_equal(x2.cpu().numpy(), ref["xhat"])
+    assert np.array_equal(dy2.cpu().numpy(), ref["dx"])
+
+
+def test_misaligned_pointers_take_the_elementwise_path():
+    """A tensor that starts 4 bytes into an allocation: same results, no fault."""
+    for dtype in (torch.float32, torch.bfloat16):
+        shape = (3, 8, 8, 8)
+        n = 3 * 8 * 8 * 8
+        off = 1 if dtype == torch.float32 else 2
+        xbuf = torch.zeros(n + 8, dtype=dtype, device=DEV)
+        x = xbuf[off:off + n].view(shape)
+        x.copy_(workloads.make_activation(shape, "linear", (0.05, 20.0), seed=6, device=DEV, dtype=dtype))
+        assert x.data_ptr() % 16 != 0
+        dybuf = torch.zeros(n + 8, dtype=dtype, device=DEV)
+        dy = dybuf[off:off + n].view(shape)
+        dy.copy_(workloads.make_grad(shape, 6, DEV, dtype))
+        got = gpu_path(x, 4, dy)
+        want = oracle_path(to_numpy(x), 4, to_numpy(dy))
+        assert_parity(got, want, "misaligned %s" % dtype)
+
+
+def test_non_default_stream_and_reuse_of_workspace():
+    st = torch.cuda.Stream()
+    x1 = workloads.make_activation((8, 32, 14, 14), "relu", (0.05, 20.0), seed=1, device=DEV)
+    x2 = workloads.make_activation((8, 32, 14, 14), "linear", (0.05, 20.0), seed=2, device=DEV)
+    q = G.ActivationQuantizer(x1.shape, x1.dtype, 4, DEV)
+    outs = []
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        for x in (x1, x2, x1):
+            xh = torch.empty_like(x)
+            q.forward(x, xh)
+            outs.append(xh)
+    st.synchronize()
+    for x, xh in zip((x1, x2, x1), outs):
+        want = oracle_path(to_numpy(x), 4)
+        assert np.array_equal(xh.cpu().numpy(), want["xhat"])

@@ -1,0 +1,71 @@
+"""Full-size parity on the five workloads, in the launch configuration the
+benchmark times, every element compared with the oracle (needs an MI355X).
+
+Tensors are the synthetic stand-ins described in workloads/__init__.py.  One
+tensor is resident at a time; the oracle's element-wise passes are split over
+the batch across host threads."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_18339_amd as G
+import workloads
+from parity import assert_parity, gpu_path, oracle_path, to_numpy
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _distinct(wl):
+    seen, out = set(), []
+    for a in wl.acts:
+        key = (a.c, a.hw, a.law)
+        if key not in seen:
+            seen.add(key)
+            out.append(a)
+    return out
+
+
+def _run(wl, act, bits, dtype, seed):
+    shape = act.shape(wl.batch)
+    x = workloads.make_activation(shape, act.law, wl.sigma, seed, DEV, workloads.torch_dtype(dtype))
+    dy = workloads.make_grad(shape, seed, DEV, x.dtype)
+    got = gpu_path(x, bits, dy)
+    x_np, dy_np = to_numpy(x), to_numpy(dy)
+    del x, dy
+    torch.cuda.empty_cache()
+    want = oracle_path(x_np, bits, dy_np)
+    assert_parity(got, want, "%s %s b%d %s" % (wl.name, act.name, bits, dtype))
+    return got
+
+
+CFG2 = workloads.resnet20_cifar()
+CFG3 = workloads.resnet18_imagenet()
+CFG4 = workloads.mobilenetv2_imagenet()
+CFG5 = workloads.resnet50_imagenet()
+
+
+@pytest.mark.parametrize("bits", CFG2.bits)
+@pytest.mark.parametrize("idx", range(len(CFG2.tensors())))
+def test_config2_resnet20_cifar(idx, bits):
+    _run(CFG2, CFG2.tensors()[idx], bits, "f32", seed=idx)
+
+
+@pytest.mark.parametrize("dtype,bits", [("f32", 4), ("bf16", 4), ("f32", 5), ("bf16", 5)])
+@pytest.mark.parametrize("idx", range(len(CFG3.acts)))
+def test_config3_resnet18_imagenet(idx, dtype, bits):
+    got = _run(CFG3, CFG3.acts[idx], bits, dtype, seed=idx)
+    assert np.all(got["zero_point"] == 0)          # post-ReLU: min 0
+    assert got["codes"].max() == 2 ** bits - 1
+
+
+@pytest.mark.parametrize("idx", range(len(CFG4.acts)))
+def test_config4_mobilenetv2(idx):
+    got = _run(CFG4, CFG4.acts[idx], 4, "f32", seed=idx)
+    if CFG4.acts[idx].law == "linear":
+        assert np.any(got["zero_point"] != 0)      # signed data: non-zero zero-points
+
+
+@pytest.mark.parametrize("idx", range(len(_distinct(CFG5))))
+def test_config5_resnet50_distinct_shapes(idx):
+    _run(CFG5, _distinct(CFG5)[idx], 3, "f32", seed=idx)
