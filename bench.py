@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the GranQ activation fake-quantizer on one MI355X.
+
+One step = one pass of the whole quantizer path over the batch-256 ResNet-18
+ImageNet activation set (five tensors, synthetic stand-ins, resident in HBM):
+for every tensor range_reduce -> prescale -> fakequant_fwd in network order,
+then fakequant_bwd for every tensor in reverse order, all on one stream with no
+host synchronisation in between.  Throughput is algorithmic bytes per second:
+24 bytes per float32 element and step (x read by the reduction, x read and
+x_hat written by the forward, x and dy read and dx written by the backward).
+
+Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2503_18339_amd as G  # noqa: E402
+import workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+# algorithmic bytes per element: (reduce, forward, backward) x element size
+BYTES_PER_ELEM = {"reduce": 1, "fwd": 2, "bwd": 3}
+
+
+class Layer:
+    """Device buffers of one activation tensor and its quantizer state."""
+
+    def __init__(self, act, batch, sigma, dtype, bits, seed, device):
+        shape = act.shape(batch)
+        self.name = act.name
+        self.shape = shape
+        self.numel = act.numel(batch)
+        self.esize = 4 if dtype == torch.float32 else 2
+        self.x = workloads.make_activation(shape, act.law, sigma, seed, device, dtype)
+        self.dy = workloads.make_grad(shape, seed, device, dtype)
+        self.x_hat = torch.empty_like(self.x)
+        self.dx = torch.empty_like(self.x)
+        self.q = G.ActivationQuantizer(shape, dtype, bits, device)
+        # the dominant kernel is the backward on tensors whose 16-byte vectors stay inside
+        # one channel (a separate template instance handles the others)
+        self.dominant = bool(G.granq_plan_describe(self.q.desc)["uniform"])
+
+    def bytes(self, kind):
+        return self.numel * self.esize * BYTES_PER_ELEM[kind]
+
+
+def build_layers(wl, dtype, bits, device):
+    return [Layer(a, wl.batch, wl.sigma, dtype, bits, i, device) for i, a in enumerate(wl.tensors())]
+
+
+def run_step(layers, stream, ev=None):
+    """One pass of the hot path.  `ev`, if given, collects one (start, end, bytes,
+    launches) record per step around the consecutive backward launches of the
+    dominant kernel (the layers are ordered so that those launches are adjacent)."""
+    for L in layers:
+        L.q.calibrate(L.x, stream)
+        G.granq_fakequant_fwd(L.x, L.q.scale, L.q.zero_point, L.q.bits, L.x_hat, None, stream, L.q.desc)
+    rev = list(reversed(layers))
+    first = next((i for i, L in enumerate(rev) if L.dominant), None)
+    last = max((i for i, L in enumerate(rev) if L.dominant), default=None)
+    a = b = None
+    for i, L in enumerate(rev):
+        if ev is not None and i == first:
+            a = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+        G.granq_fakequant_bwd(L.x, L.dy, L.q.scale, L.q.zero_point, L.q.bits, L.dx, stream, L.q.desc)
+        if ev is not None and i == last:
+            b = torch.cuda.Event(enable_timing=True)
+            b.record(stream)
+            doms = [M for M in rev[first:last + 1]]
+            assert all(M.dominant for M in doms)
+            ev.append((a, b, sum(M.bytes("bwd") for M in doms), len(doms)))
+
+
+def time_steps(layers, steps, warmup, with_events):
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        run_step(layers, stream)
+    ev = [] if with_events else None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_step(layers, stream, ev)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt, ev
+
+
+def kernel_breakdown(layers, reps=10):
+    """Per tensor and kernel: average device time over `reps` launches (HIP events)."""
+    stream = torch.cuda.current_stream()
+    rows = []
+    for L in layers:
+        calls = {
+            "reduce": lambda: G.granq_range_reduce(L.x, L.q.ch_min, L.q.ch_max, L.q.workspace, stream, L.q.desc),
+            "prescale": lambda: G.granq_prescale(L.q.ch_min, L.q.ch_max, L.q.bits, L.q.scale, L.q.zero_point, stream),
+            "fwd": lambda: G.granq_fakequant_fwd(L.x, L.q.scale, L.q.zero_point, L.q.bits, L.x_hat, None, stream, L.q.desc),
+            "bwd": lambda: G.granq_fakequant_bwd(L.x, L.dy, L.q.scale, L.q.zero_point, L.q.bits, L.dx, stream, L.q.desc),
+        }
+        row = {"tensor": "%s %s" % (L.name, "x".join(map(str, L.shape)))}
+        for kind, fn in calls.items():
+            fn()
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            b.record(stream)
+            b.synchronize()
+            us = a.elapsed_time(b) * 1e3 / reps
+            row[kind + "_us"] = round(us, 2)
+            if kind != "prescale":
+                row[kind + "_GBs"] = round(L.bytes(kind) / us / 1e3, 1)
+        rows.append(row)
+    return rows
+
+
+def cpu_baseline(wl, bits, sample_batch):
+    """The CPU oracle, as it stands, on a batch-`sample_batch` sample of the same
+    tensors (float32), single thread; returns GB/s on the same algorithmic bytes."""
+    import oracle
+    total_bytes = 0
+    total_s = 0.0
+    for i, a in enumerate(wl.tensors()):
+        shape = a.shape(sample_batch)
+        x = workloads.make_activation(shape, a.law, wl.sigma, i, "cpu").numpy()
+        dy = workloads.make_grad(shape, i, "cpu").numpy()
+        t0 = time.perf_counter()
+        mn, mx = oracle.range_reduce(x)
+        s, z = oracle.prescale(mn, mx, bits)
+        oracle.fakequant_fwd(x, s, z, bits)
+        oracle.fakequant_bwd(x, dy, s, z, bits)
+        total_s += time.perf_counter() - t0
+        total_bytes += x.size * 4 * 6
+    return total_bytes / total_s / 1e9, total_s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--cpu-sample-batch", type=int, default=128,
+                    help="batch size of the sample the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true", help="skip breakdown and other dtypes")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this library is a single-GPU kernel library; it has no collectives and "
+              "no multi-GPU path.  Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    G.load()
+
+    device = "cuda"
+    wl = workloads.resnet18_imagenet()
+    dtype = workloads.torch_dtype(args.dtype)
+    layers = build_layers(wl, dtype, args.bits, device)
+    bwd_rows = G.granq_plan_describe(layers[0].q.desc)["bwd_rows"]
+    esize = layers[0].esize
+    elems = sum(L.numel for L in layers)
+    step_bytes = elems * esize * 6
+
+    dt, ev = time_steps(layers, args.steps, args.warmup, with_events=True)
+    ms_per_step = dt * 1e3 / args.steps
+    value = step_bytes / (dt / args.steps) / 1e9
+
+    k_bytes = sum(e[2] for e in ev)
+    k_launches = sum(e[3] for e in ev)
+    k_ms = sum(e[0].elapsed_time(e[1]) for e in ev)
+    achieved = k_bytes / (k_ms * 1e-3) / 1e9
+    roofline = {
+        "kernel": "granq::fq_bwd_cols<granq::%s, 1, %d, true>" % ("F32" if args.dtype == "f32" else "BF16", bwd_rows),
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "launches": k_launches, "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),
+        "bytes_per_launch": k_bytes // max(1, k_launches),
+        "note": "one HIP event pair per step around the adjacent launches of this kernel "
+                "(tensors 4..1 of the backward sweep); average = span / launches",
+    }
+
+    out = {
+        "metric": "fake-quant fwd+bwd GB/s and % of HBM peak, ResNet-18 ImageNet activations",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %s, %d-bit, range_reduce+prescale+fwd per tensor then bwd in reverse"
+                   % (wl.name, ", ".join("%d@%dx%d" % (a.c, a.hw, a.hw) for a in wl.acts), args.bits),
+                   "batch": wl.batch, "elements_per_step": elems, "bytes_per_step": step_bytes},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "elements_per_s": round(elems / (dt / args.steps), 0),
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        extra = {"per_kernel": kernel_breakdown(layers)}
+        fb_us = sum(r["fwd_us"] + r["bwd_us"] for r in extra["per_kernel"])
+        extra["fwd_bwd_kernels_only_GBs"] = round(elems * esize * 5 / fb_us / 1e3, 1)
+        # same step without the per-launch events: what the events cost
+        dt2, _ = time_steps(layers, args.steps, 2, with_events=False)
+        extra["value_without_kernel_events_GBs"] = round(step_bytes / (dt2 / args.steps) / 1e9, 1)
+        del layers
+        torch.cuda.empty_cache()
+        others = {}
+        for dname, bits in [("f32", 4), ("f32", 5), ("bf16", 4), ("bf16", 5)]:
+            if dname == args.dtype and bits == args.bits:
+                continue
+            ls = build_layers(wl, workloads.torch_dtype(dname), bits, device)
+            d, _ = time_steps(ls, args.steps, args.warmup, with_events=False)
+            b = elems * ls[0].esize * 6
+            others["%s_b%d" % (dname, bits)] = {"GBs": round(b / (d / args.steps) / 1e9, 1),
+                                                "ms_per_step": round(d * 1e3 / args.steps, 4),
+                                                "elements_per_s": round(elems / (d / args.steps), 0)}
+            del ls
+            torch.cuda.empty_cache()
+        extra["other_dtypes_bits"] = others
+        out["extra"] = extra
+
+    if args.cpu_sample_batch > 0:
+        gbs, secs = cpu_baseline(wl, args.bits, args.cpu_sample_batch)
+        out["cpu_baseline"] = {
+            "value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "the same five tensors at batch %d of 256, float32, %d-bit, one pass "
+                      "(range_reduce+prescale+fwd+bwd), %.1f s" % (args.cpu_sample_batch, args.bits, secs),
+        }
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

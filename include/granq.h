@@ -83,14 +83,17 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
 
 /*
  * Host-only introspection (no GPU call): how the vectorised kernels would tile
- * this descriptor.  Fills out[0..9] with
+ * this descriptor.  Fills out[0..15] with
  *   [0] 1 if the shape is eligible for the 128-bit column kernels, else 0
  *   [1] rows  [2] row length  [3] elements per channel within a row
  *   [4] columns per block  [5] column tiles  [6] row groups  [7] rows per group
  *   [8] partial slots per column tile  [9] 1 if no 16-byte vector straddles channels
- * of the matrix view (rows x row length) the kernels walk.  For tests and tuning.
+ *   [10..12] multiplier and the two shifts of the column -> channel division
+ *   [13] rows per block of the forward  [14] of the backward  [15] their columns per block
+ * of the matrix view (rows x row length) the kernels walk; [4]..[8] describe the
+ * reduction.  For tests and tuning.
  */
-granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[10]);
+granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[16]);
 
 /*
  * Activation decomposition (Eq. 4; Alg. 1's min/max step; Sec. 5.1: channel-wise

@@ -21,22 +21,41 @@
 #include "granq.h"
 #include "granq_device.h"
 #include "granq_plan.h"
+#include "granq_quotient.h"
 
 namespace granq {
 
-// Vectors per lane and row in the column kernels, and rows in flight per lane.
-#ifndef GRANQ_V_F32
-#define GRANQ_V_F32 2
+// Vectors per lane and row for the element-wise (E: forward, backward) and the
+// reduction (R) column kernels, and rows in flight per lane in the reduction.
+// (Forward and backward keep GRANQ_F_ROWS / GRANQ_B_ROWS rows in flight.)
+#ifndef GRANQ_E_V_F32
+#define GRANQ_E_V_F32 1
 #endif
-#ifndef GRANQ_V_BF16
-#define GRANQ_V_BF16 1
+#ifndef GRANQ_E_V_BF16
+#define GRANQ_E_V_BF16 1
 #endif
-#ifndef GRANQ_UNROLL
-#define GRANQ_UNROLL 4
+#ifndef GRANQ_R_V_F32
+#define GRANQ_R_V_F32 4
+#endif
+#ifndef GRANQ_R_V_BF16
+#define GRANQ_R_V_BF16 2
+#endif
+#ifndef GRANQ_R_UNROLL
+#define GRANQ_R_UNROLL 8
+#endif
+// The forward walks the tensor from its end towards its start: it usually runs
+// right after the reduction, whose most recently read (last) rows are the ones
+// still held by the memory-side cache.
+#ifndef GRANQ_FWD_REVERSE
+#define GRANQ_FWD_REVERSE 1
 #endif
 // Non-temporal stores for outputs nobody re-reads soon (x_hat, dx, codes).
 #ifndef GRANQ_NT_STORE
 #define GRANQ_NT_STORE 1
+#endif
+// Five-operation exact quotient (granq_quotient.h) instead of the general division.
+#ifndef GRANQ_FAST_QUOTIENT
+#define GRANQ_FAST_QUOTIENT 1
 #endif
 
 template <typename V>
@@ -51,159 +70,192 @@ __device__ inline void store_vec(V *p, const V &v) {
 #endif
 }
 
-// Per-lane channel parameters for the NS elements (1 if the vector lies inside
-// one channel, else VEC) of a vector starting at column `col`.
+// Channels of the NS elements (1 if the vector lies inside one channel, else
+// VEC) of a vector starting at column `col`.
 template <int NS>
-__device__ inline void lane_channels(int64_t col, int64_t hw, int32_t (&ch)[NS]) {
-    int64_t c0 = col / hw;
-    int64_t rem = col - c0 * hw;
+__device__ inline void lane_channels(uint32_t col, const ColPlan &plan, int32_t (&ch)[NS]) {
+    uint32_t c0 = fastdiv(col, plan.hw_div);
+    uint32_t rem = col - c0 * plan.hw_div.d;
     ch[0] = (int32_t)c0;
 #pragma unroll
     for (int e = 1; e < NS; ++e) {
         rem += 1;
-        if (rem == hw) { rem = 0; c0 += 1; }
+        if (rem == plan.hw_div.d) { rem = 0; c0 += 1; }
         ch[e] = (int32_t)c0;
     }
 }
 
+// What a lane keeps per channel while it walks down its rows.
+struct ChanRegs {
+    float s, z, r;       // scale, zero-point, RN(1/scale)
+};
+
+// Rounded, unclamped code of Eq. 1.  FAST: x / s through the per-channel
+// reciprocal, bit-identical where it matters (see granq_quotient.h).
+template <bool FAST>
+__device__ inline float code_of(float x, const ChanRegs &c) {
+    float t;
+    if (FAST) t = quotient_fast(quotient_clamp(x), c.s, c.r);
+    else t = x / c.s;
+    float v = t + c.z;
+    return __builtin_rintf(v);
+}
+
 // ---------------------------------------------------------------------------
-// fake-quant forward, column kernel
+// fake-quant forward and straight-through backward, column kernels
 // ---------------------------------------------------------------------------
 
-template <typename T, int V, bool UNIFORM, bool CODES>
+// Shared prologue: this lane's vectors within a row and their channels' registers.
+// Returns true when every channel this lane touches admits the fast quotient.
+template <typename T, int V, bool UNIFORM>
+__device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *__restrict__ scale,
+                                  const float *__restrict__ zero_point,
+                                  ChanRegs (&cr)[V][UNIFORM ? 1 : T::VEC], uint32_t (&cv)[V],
+                                  bool (&active)[V]) {
+    constexpr int VEC = T::VEC;
+    constexpr int NS = UNIFORM ? 1 : VEC;
+    bool fast = GRANQ_FAST_QUOTIENT != 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kBlock) * VEC;
+        active[v] = col < (uint32_t)plan.row_len;
+        cv[v] = col / VEC;
+        int32_t ch[NS];
+        lane_channels<NS>(active[v] ? col : 0u, plan, ch);
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            const float s = scale[ch[e]], z = zero_point[ch[e]];
+            cr[v][e].s = s;
+            cr[v][e].z = z;
+            cr[v][e].r = 1.0f / s;
+            fast = fast && quotient_fast_ok(s, z);
+        }
+    }
+    return fast;
+}
+
+template <typename T, int V, int U, bool UNIFORM, bool CODES, bool FAST>
+__device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
+                                typename T::vec_t *__restrict__ x_hat,
+                                typename T::code_t *__restrict__ codes, float qmax, int64_t row_vecs,
+                                int64_t r, int nrows, const ChanRegs (&cr)[V][UNIFORM ? 1 : T::VEC],
+                                const uint32_t (&cv)[V], const bool (&active)[V]) {
+    constexpr int VEC = T::VEC;
+    typename T::vec_t in[U][V];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            if (u < nrows && active[v]) in[u][v] = load_vec(x + (r + u) * row_vecs + cv[v]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            if (u < nrows && active[v]) {
+                float f[VEC], q[VEC];
+                T::unpack(in[u][v], f);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const ChanRegs &c = cr[v][UNIFORM ? 0 : e];
+                    q[e] = clamp_code(code_of<FAST>(f[e], c), qmax);
+                    f[e] = dequant(q[e], c.s, c.z);
+                }
+                const int64_t at = (r + u) * row_vecs + cv[v];
+                store_vec(x_hat + at, T::pack(f));
+                if (CODES) store_vec(codes + at, T::pack_codes(q));
+            }
+}
+
+template <typename T, int V, int U, bool UNIFORM, bool CODES>
 __global__ __launch_bounds__(kBlock) void fq_fwd_cols(
     const typename T::vec_t *__restrict__ x, typename T::vec_t *__restrict__ x_hat,
     typename T::code_t *__restrict__ codes, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
-    constexpr int VEC = T::VEC;
-    constexpr int NS = UNIFORM ? 1 : VEC;
-    constexpr int U = GRANQ_UNROLL;
-    using vec_t = typename T::vec_t;
+    constexpr int NS = UNIFORM ? 1 : T::VEC;
+    const uint32_t j = GRANQ_FWD_REVERSE ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    const uint32_t p = GRANQ_FWD_REVERSE ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
+    const int64_t row_vecs = plan.row_len / T::VEC;
 
-    const int32_t j = blockIdx.x % plan.col_tiles;
-    const int32_t p = blockIdx.x / plan.col_tiles;
-    const int64_t row_vecs = plan.row_len / VEC;
-
-    float s[V][NS], z[V][NS];
-    int64_t cv[V];           // vector index of this lane's v-th vector within a row
+    ChanRegs cr[V][NS];
+    uint32_t cv[V];
     bool active[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        int64_t col = (int64_t)j * plan.span + (int64_t)(threadIdx.x + v * kBlock) * VEC;
-        active[v] = col < plan.row_len;
-        cv[v] = col / VEC;
-        int32_t ch[NS];
-        lane_channels<NS>(active[v] ? col : 0, plan.hw, ch);
-#pragma unroll
-        for (int e = 0; e < NS; ++e) {
-            s[v][e] = scale[ch[e]];
-            z[v][e] = zero_point[ch[e]];
-        }
-    }
+    const bool fast = lane_setup<T, V, UNIFORM>(plan, j, scale, zero_point, cr, cv, active);
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
-
-    auto body = [&](int64_t r, const int nrows) {
-        vec_t in[U][V];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-                if (u < nrows && active[v]) in[u][v] = load_vec(x + (r + u) * row_vecs + cv[v]);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-                if (u < nrows && active[v]) {
-                    float f[VEC], q[VEC];
-                    T::unpack(in[u][v], f);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        const float se = s[v][UNIFORM ? 0 : e], ze = z[v][UNIFORM ? 0 : e];
-                        q[e] = clamp_code(raw_code(f[e], se, ze), qmax);
-                        f[e] = dequant(q[e], se, ze);
-                    }
-                    const int64_t at = (r + u) * row_vecs + cv[v];
-                    store_vec(x_hat + at, T::pack(f));
-                    if (CODES) store_vec(codes + at, T::pack_codes(q));
-                }
-    };
-
     int64_t r = r0;
-    for (; r + U <= r1; r += U) body(r, U);
-    if (r < r1) body(r, (int)(r1 - r));
+    if (fast) {
+        for (; r + U <= r1; r += U)
+            fwd_rows<T, V, U, UNIFORM, CODES, true>(x, x_hat, codes, qmax, row_vecs, r, U, cr, cv, active);
+        if (r < r1)
+            fwd_rows<T, V, U, UNIFORM, CODES, true>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+    } else {
+        for (; r < r1; ++r)
+            fwd_rows<T, V, 1, UNIFORM, CODES, false>(x, x_hat, codes, qmax, row_vecs, r, 1, cr, cv, active);
+    }
 }
 
-// ---------------------------------------------------------------------------
-// straight-through backward, column kernel
-// ---------------------------------------------------------------------------
+template <typename T, int V, int U, bool UNIFORM, bool FAST>
+__device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
+                                const typename T::vec_t *__restrict__ dy,
+                                typename T::vec_t *__restrict__ dx, float qmax, int64_t row_vecs,
+                                int64_t r, int nrows, const ChanRegs (&cr)[V][UNIFORM ? 1 : T::VEC],
+                                const uint32_t (&cv)[V], const bool (&active)[V]) {
+    constexpr int VEC = T::VEC;
+    typename T::vec_t in[U][V], g[U][V];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            if (u < nrows && active[v]) {
+                const int64_t at = (r + u) * row_vecs + cv[v];
+                in[u][v] = load_vec(x + at);
+                g[u][v] = load_vec(dy + at);
+            }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            if (u < nrows && active[v]) {
+                float f[VEC];
+                bool keep[VEC];
+                T::unpack(in[u][v], f);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    keep[e] = in_range(code_of<FAST>(f[e], cr[v][UNIFORM ? 0 : e]), qmax);
+                store_vec(dx + (r + u) * row_vecs + cv[v], T::gate(g[u][v], keep));
+            }
+}
 
-template <typename T, int V, bool UNIFORM>
+template <typename T, int V, int U, bool UNIFORM>
 __global__ __launch_bounds__(kBlock) void fq_bwd_cols(
     const typename T::vec_t *__restrict__ x, const typename T::vec_t *__restrict__ dy,
     typename T::vec_t *__restrict__ dx, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
-    constexpr int VEC = T::VEC;
-    constexpr int NS = UNIFORM ? 1 : VEC;
-    constexpr int U = GRANQ_UNROLL;
-    using vec_t = typename T::vec_t;
+    constexpr int NS = UNIFORM ? 1 : T::VEC;
+    const uint32_t j = blockIdx.x;
+    const uint32_t p = blockIdx.y;
+    const int64_t row_vecs = plan.row_len / T::VEC;
 
-    const int32_t j = blockIdx.x % plan.col_tiles;
-    const int32_t p = blockIdx.x / plan.col_tiles;
-    const int64_t row_vecs = plan.row_len / VEC;
-
-    float s[V][NS], z[V][NS];
-    int64_t cv[V];
+    ChanRegs cr[V][NS];
+    uint32_t cv[V];
     bool active[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        int64_t col = (int64_t)j * plan.span + (int64_t)(threadIdx.x + v * kBlock) * VEC;
-        active[v] = col < plan.row_len;
-        cv[v] = col / VEC;
-        int32_t ch[NS];
-        lane_channels<NS>(active[v] ? col : 0, plan.hw, ch);
-#pragma unroll
-        for (int e = 0; e < NS; ++e) {
-            s[v][e] = scale[ch[e]];
-            z[v][e] = zero_point[ch[e]];
-        }
-    }
+    const bool fast = lane_setup<T, V, UNIFORM>(plan, j, scale, zero_point, cr, cv, active);
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
-
-    auto body = [&](int64_t r, const int nrows) {
-        vec_t in[U][V], g[U][V];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-                if (u < nrows && active[v]) {
-                    const int64_t at = (r + u) * row_vecs + cv[v];
-                    in[u][v] = load_vec(x + at);
-                    g[u][v] = load_vec(dy + at);
-                }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-                if (u < nrows && active[v]) {
-                    float f[VEC];
-                    bool keep[VEC];
-                    T::unpack(in[u][v], f);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e)
-                        keep[e] = in_range(raw_code(f[e], s[v][UNIFORM ? 0 : e], z[v][UNIFORM ? 0 : e]), qmax);
-                    store_vec(dx + (r + u) * row_vecs + cv[v], T::gate(g[u][v], keep));
-                }
-    };
-
     int64_t r = r0;
-    for (; r + U <= r1; r += U) body(r, U);
-    if (r < r1) body(r, (int)(r1 - r));
+    if (fast) {
+        for (; r + U <= r1; r += U)
+            bwd_rows<T, V, U, UNIFORM, true>(x, dy, dx, qmax, row_vecs, r, U, cr, cv, active);
+        if (r < r1)
+            bwd_rows<T, V, U, UNIFORM, true>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+    } else {
+        for (; r < r1; ++r)
+            bwd_rows<T, V, 1, UNIFORM, false>(x, dy, dx, qmax, row_vecs, r, 1, cr, cv, active);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -226,12 +278,12 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
 {
     constexpr int VEC = T::VEC;
     constexpr int NS = UNIFORM ? 1 : VEC;
-    constexpr int U = GRANQ_UNROLL;
+    constexpr int U = GRANQ_R_UNROLL;
     using vec_t = typename T::vec_t;
     extern __shared__ uint32_t lds_keys[];          // [kmax] min keys, then [kmax] max keys
 
-    const int32_t j = blockIdx.x % plan.col_tiles;
-    const int32_t p = blockIdx.x / plan.col_tiles;
+    const uint32_t j = blockIdx.x;
+    const uint32_t p = blockIdx.y;
     const int64_t row_vecs = plan.row_len / VEC;
     const int32_t kmax = plan.kmax;
 
@@ -241,12 +293,12 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
     }
 
     float mn[V][NS], mx[V][NS];
-    int64_t cv[V];
+    uint32_t cv[V];
     bool active[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        int64_t col = (int64_t)j * plan.span + (int64_t)(threadIdx.x + v * kBlock) * VEC;
-        active[v] = col < plan.row_len;
+        const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kBlock) * VEC;
+        active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
 #pragma unroll
         for (int e = 0; e < NS; ++e) {
@@ -286,13 +338,13 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
 
     __syncthreads();                                   // LDS slots initialised
 
-    const int32_t ch_first = (int32_t)(((int64_t)j * plan.span) / plan.hw);
+    const int32_t ch_first = (int32_t)fastdiv(j * (uint32_t)plan.span, plan.hw_div);
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         // inactive lanes hold the identities and point at the tile's first channel
-        int64_t col = active[v] ? cv[v] * VEC : (int64_t)j * plan.span;
+        const uint32_t col = active[v] ? cv[v] * VEC : j * (uint32_t)plan.span;
         int32_t ch[NS];
-        lane_channels<NS>(col, plan.hw, ch);
+        lane_channels<NS>(col, plan, ch);
 #pragma unroll
         for (int e = 0; e < NS; ++e) {
             const int32_t k = ch[e] - ch_first;
@@ -313,7 +365,7 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
 
     __syncthreads();
 
-    const int64_t slot = ((int64_t)p * plan.col_tiles + j) * kmax;
+    const int64_t slot = ((int64_t)p * plan.col_tiles + (int64_t)j) * kmax;
     for (int i = threadIdx.x; i < kmax; i += kBlock) {
         ws_min[slot + i] = key_float(lds_keys[i]);
         ws_max[slot + i] = key_float(lds_keys[kmax + i]);
@@ -492,10 +544,24 @@ static bool aligned_elem(const void *p, granq_dtype_t dt) {
 }
 
 static int vec_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? F32::VEC : BF16::VEC; }
-static int v_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? GRANQ_V_F32 : GRANQ_V_BF16; }
 
-static ColPlan col_plan(const granq_desc_t *d) {
-    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), v_of(d->dtype), kBlock);
+// Plans of the element-wise kernels: rows per block = rows in flight per lane.
+static ColPlan fwd_plan(const granq_desc_t *d) {
+    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                         d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kBlock,
+                         (int64_t)1 << 40, GRANQ_F_ROWS);
+}
+static ColPlan bwd_plan(const granq_desc_t *d) {
+    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                         d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kBlock,
+                         (int64_t)1 << 40, GRANQ_B_ROWS);
+}
+
+// Plan of the reduction; it also fixes the workspace layout.
+static ColPlan range_plan(const granq_desc_t *d) {
+    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                         d->dtype == GRANQ_F32 ? GRANQ_R_V_F32 : GRANQ_R_V_BF16, kBlock,
+                         GRANQ_R_TARGET_BLOCKS, GRANQ_R_MIN_ROWS);
 }
 
 static granq_status_t launched() {
@@ -505,7 +571,7 @@ static granq_status_t launched() {
 // Grid of the row kernels: enough wavefronts to fill the chip, no more than slabs.
 static uint32_t row_grid(int64_t slabs) {
     int64_t blocks = ceil_div(slabs, kBlock / kWave);
-    int64_t cap = (int64_t)GRANQ_TARGET_BLOCKS * 4;
+    int64_t cap = (int64_t)GRANQ_ROW_TARGET_BLOCKS * 4;
     return (uint32_t)(blocks < cap ? blocks : cap);
 }
 
@@ -514,16 +580,16 @@ static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
     using code_t = typename T::code_t;
-    dim3 grid((uint32_t)(pl.col_tiles * pl.row_groups)), block(kBlock);
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kBlock);
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
     auto cv = (code_t *)codes;
     if (pl.uniform) {
-        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, true, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-        else hipLaunchKernelGGL((fq_fwd_cols<T, V, true, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, true, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+        else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, true, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
     } else {
-        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, false, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-        else hipLaunchKernelGGL((fq_fwd_cols<T, V, false, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, false, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+        else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, false, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
     }
 }
 
@@ -531,18 +597,18 @@ template <typename T, int V>
 static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, void *dx,
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
-    dim3 grid((uint32_t)(pl.col_tiles * pl.row_groups)), block(kBlock);
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kBlock);
     if (pl.uniform)
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, true>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
     else
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, false>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
 }
 
 template <typename T, int V>
 static void launch_range_cols(const ColPlan &pl, const void *x, float *ws_min, float *ws_max,
                               hipStream_t st) {
     using vec_t = typename T::vec_t;
-    dim3 grid((uint32_t)(pl.col_tiles * pl.row_groups)), block(kBlock);
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kBlock);
     size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
     if (pl.uniform)
         hipLaunchKernelGGL((range_cols_pass1<T, V, true>), grid, block, lds, st, (const vec_t *)x, ws_min, ws_max, pl);
@@ -580,17 +646,17 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
     const int64_t hw = desc->h * desc->w;
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);
     size_t floats = (size_t)rp.row_groups * (size_t)desc->c;
-    ColPlan cp = col_plan(desc);
+    ColPlan cp = range_plan(desc);
     if (cp.ok && col_ws_floats(cp) > floats) floats = col_ws_floats(cp);
     *bytes_out = 2 * floats * sizeof(float);
     return GRANQ_OK;
 }
 
-granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[10]) {
+granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[16]) {
     if (!out) return GRANQ_ERR_INVALID_ARG;
     granq_status_t st = check_desc(desc);
     if (st != GRANQ_OK) return st;
-    ColPlan cp = col_plan(desc);
+    ColPlan cp = range_plan(desc);
     out[0] = cp.ok ? 1 : 0;
     out[1] = cp.rows;
     out[2] = cp.row_len;
@@ -601,6 +667,13 @@ granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[10]) {
     out[7] = cp.rows_per_group;
     out[8] = cp.kmax;
     out[9] = cp.uniform ? 1 : 0;
+    out[10] = cp.hw_div.m;
+    out[11] = cp.hw_div.s1;
+    out[12] = cp.hw_div.s2;
+    ColPlan fp = fwd_plan(desc), bp = bwd_plan(desc);
+    out[13] = fp.rows_per_group;
+    out[14] = bp.rows_per_group;
+    out[15] = fp.span;
     return GRANQ_OK;
 }
 
@@ -617,13 +690,13 @@ granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return GRANQ_ERR_WORKSPACE;
     hipStream_t hs = (hipStream_t)stream;
     const int64_t hw = desc->h * desc->w;
-    ColPlan cp = col_plan(desc);
+    ColPlan cp = range_plan(desc);
     if (cp.ok && aligned16(x)) {
         const size_t floats = col_ws_floats(cp);
         float *ws_min = (float *)workspace;
         float *ws_max = ws_min + floats;
-        if (desc->dtype == GRANQ_F32) launch_range_cols<F32, GRANQ_V_F32>(cp, x, ws_min, ws_max, hs);
-        else launch_range_cols<BF16, GRANQ_V_BF16>(cp, x, ws_min, ws_max, hs);
+        if (desc->dtype == GRANQ_F32) launch_range_cols<F32, GRANQ_R_V_F32>(cp, x, ws_min, ws_max, hs);
+        else launch_range_cols<BF16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
         st = launched();
         if (st != GRANQ_OK) return st;
         dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave)), block(kBlock);
@@ -672,12 +745,12 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
         return GRANQ_ERR_UNSUPPORTED;
     const float qmax = (float)((1 << bits) - 1);
     hipStream_t hs = (hipStream_t)stream;
-    ColPlan cp = col_plan(desc);
+    ColPlan cp = fwd_plan(desc);
     // packed codes are stored VEC bytes at a time
     const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
     if (cp.ok && aligned16(x) && aligned16(x_hat) && codes_ok) {
-        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_V_F32>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
-        else launch_fwd_cols<BF16, GRANQ_V_BF16>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
+        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
         return launched();
     }
     const int64_t hw = desc->h * desc->w;
@@ -702,10 +775,10 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
         return GRANQ_ERR_UNSUPPORTED;
     const float qmax = (float)((1 << bits) - 1);
     hipStream_t hs = (hipStream_t)stream;
-    ColPlan cp = col_plan(desc);
+    ColPlan cp = bwd_plan(desc);
     if (cp.ok && aligned16(x) && aligned16(dy) && aligned16(dx)) {
-        if (desc->dtype == GRANQ_F32) launch_bwd_cols<F32, GRANQ_V_F32>(cp, x, dy, dx, scale, zero_point, qmax, hs);
-        else launch_bwd_cols<BF16, GRANQ_V_BF16>(cp, x, dy, dx, scale, zero_point, qmax, hs);
+        if (desc->dtype == GRANQ_F32) launch_bwd_cols<F32, GRANQ_E_V_F32>(cp, x, dy, dx, scale, zero_point, qmax, hs);
+        else launch_bwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, dy, dx, scale, zero_point, qmax, hs);
         return launched();
     }
     const int64_t hw = desc->h * desc->w;

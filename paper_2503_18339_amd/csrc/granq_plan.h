@@ -11,7 +11,7 @@
 //   columns:  J tiles of `span` = kBlock * VEC * V elements (VEC = 16 bytes'
 //             worth of elements, V vectors per lane and row)
 //   rows:     P groups of `rows_per_group` consecutive rows
-//   grid:     J * P blocks, column tile fastest, so that blocks that are
+//   grid:     (J, P) blocks, column tile fastest, so that blocks that are
 //             resident together read neighbouring spans of the same rows.
 //
 // A tensor with a single channel (the layer-wise view {1,1,1,E}) has only one
@@ -24,14 +24,63 @@
 
 namespace granq {
 
-// Resident blocks the plan aims for: 256 compute units x 8 blocks of 4 waves.
-#ifndef GRANQ_TARGET_BLOCKS
-#define GRANQ_TARGET_BLOCKS 2048
+// Tuning (defaults from sweeps on MI355X; -D overrides).
+// Element-wise kernels (forward, backward) run best as very many short blocks:
+// a block that issues all its loads at once and retires keeps the memory system
+// busier than long-lived blocks marching in lockstep.  A block of the forward
+// handles GRANQ_F_ROWS rows of its column tile, one of the backward
+// GRANQ_B_ROWS.  The reduction prefers fatter blocks (fewer partials, cheaper
+// epilogue): at least GRANQ_R_MIN_ROWS rows per block.
+#ifndef GRANQ_F_ROWS
+#define GRANQ_F_ROWS 2
 #endif
-// Fewest rows a block should walk before the plan stops splitting the rows.
-#ifndef GRANQ_MIN_ROWS
-#define GRANQ_MIN_ROWS 4
+#ifndef GRANQ_B_ROWS
+#define GRANQ_B_ROWS 1
 #endif
+#ifndef GRANQ_R_TARGET_BLOCKS
+#define GRANQ_R_TARGET_BLOCKS 1000000
+#endif
+#ifndef GRANQ_R_MIN_ROWS
+#define GRANQ_R_MIN_ROWS 8
+#endif
+// Blocks the fallback (row) kernels aim for: 256 compute units x 8 blocks.
+#ifndef GRANQ_ROW_TARGET_BLOCKS
+#define GRANQ_ROW_TARGET_BLOCKS 2048
+#endif
+
+#if defined(__HIPCC__)
+#define GRANQ_PLAN_HD __host__ __device__
+#else
+#define GRANQ_PLAN_HD
+#endif
+
+// Division of a 32-bit unsigned number by a constant chosen at run time
+// (Granlund & Montgomery, "Division by invariant integers using
+// multiplication", 1994): with l = ceil(log2 d) and
+// m = floor(2^32 * (2^l - d) / d) + 1,
+//     n / d = (t + ((n - t) >> min(l,1))) >> max(l-1,0),   t = mulhi(m, n),
+// exact for every 32-bit n.  Five integer instructions instead of the ~30 of a
+// general division.
+struct FastDiv {
+    uint32_t d, m, s1, s2;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    uint64_t m = (((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1;
+    FastDiv f;
+    f.d = d;
+    f.m = (uint32_t)m;
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l > 0 ? l - 1 : 0;
+    return f;
+}
+
+GRANQ_PLAN_HD inline uint32_t fastdiv(uint32_t n, const FastDiv &f) {
+    uint32_t t = (uint32_t)(((uint64_t)f.m * n) >> 32);
+    return (t + ((n - t) >> f.s1)) >> f.s2;
+}
 
 struct ColPlan {
     int64_t rows;            // rows of the (possibly folded) matrix
@@ -43,6 +92,7 @@ struct ColPlan {
     int32_t row_groups;      // P
     int32_t rows_per_group;
     int32_t kmax;            // most channels any column tile touches
+    FastDiv hw_div;          // column -> channel
     bool uniform;            // every 16-byte vector lies inside one channel
     bool ok;                 // false: shape not eligible for the vector kernels
 };
@@ -50,7 +100,8 @@ struct ColPlan {
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // vec = elements per 16 bytes, v = vectors per lane and row, block = threads.
-inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, int block) {
+inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, int block,
+                             int64_t target_blocks, int64_t min_rows) {
     ColPlan p{};
     p.ok = false;
     int64_t rows = n, row_len = c * hw, chan = c, per = hw;
@@ -74,13 +125,14 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
     p.channels = (int32_t)chan;
     p.span = block * vec * v;
     p.col_tiles = (int32_t)ceil_div(row_len, p.span);
-    int64_t want = ceil_div(GRANQ_TARGET_BLOCKS, p.col_tiles);
-    int64_t most = rows / GRANQ_MIN_ROWS > 0 ? rows / GRANQ_MIN_ROWS : 1;
+    int64_t want = ceil_div(target_blocks, p.col_tiles);
+    int64_t most = rows / min_rows > 0 ? rows / min_rows : 1;
     int64_t groups = want < most ? want : most;
     if (groups < 1) groups = 1;
+    if (groups > 65535) groups = 65535;              // row groups ride on gridDim.y
     p.rows_per_group = (int32_t)ceil_div(rows, groups);
     p.row_groups = (int32_t)ceil_div(rows, p.rows_per_group);
-    if ((int64_t)p.col_tiles * p.row_groups >= (int64_t)1 << 31) return p;
+    p.hw_div = make_fastdiv((uint32_t)per);
     int64_t k = (p.span - 1) / per + 2;
     p.kmax = (int32_t)(k < chan ? k : chan);
     p.uniform = (per % vec) == 0;
@@ -96,7 +148,7 @@ struct RowPlan {
 
 inline RowPlan make_row_plan(int64_t n, int64_t c, int64_t hw) {
     RowPlan p{};
-    int64_t want = ceil_div(GRANQ_TARGET_BLOCKS, c);
+    int64_t want = ceil_div(GRANQ_ROW_TARGET_BLOCKS, c);
     // keep at least ~4096 elements per block where the tensor allows it
     int64_t min_rows = ceil_div(4096, hw);
     int64_t most = n / min_rows > 0 ? n / min_rows : 1;

@@ -135,6 +135,25 @@ def test_plan_invariants(shape, dtype):
     assert int(last.max()) == pl["row_len"] // pl["hw"] - 1
 
 
+@pytest.mark.parametrize("hw", [1, 2, 3, 4, 7, 49, 64, 196, 784, 1000, 3136, 12544, 65535, 65536, 65537,
+                                (1 << 20) + 7, (1 << 28) + 4])
+def test_column_to_channel_division_is_exact(hw):
+    """The multiply-shift division the kernels use for column -> channel, replayed
+    with the constants the library computed, against integer division."""
+    pl = G.granq_plan_describe(G.make_desc(3, 4, 1, hw, G.GRANQ_F32))
+    assert pl["vector_path"] and pl["hw"] == hw
+    m, s1, s2 = pl["div_m"], pl["div_s1"], pl["div_s2"]
+    rng = np.random.default_rng(hw)
+    n = np.concatenate([rng.integers(0, 2 ** 32, size=200000, dtype=np.uint64),
+                        np.arange(0, 70000, dtype=np.uint64),
+                        np.arange(1, 3000, dtype=np.uint64) * np.uint64(hw) % np.uint64(2 ** 32),
+                        (np.arange(1, 3000, dtype=np.uint64) * np.uint64(hw) - np.uint64(1)) % np.uint64(2 ** 32),
+                        np.array([2 ** 32 - 1, 2 ** 31, 2 ** 31 - 1], dtype=np.uint64)])
+    t = (np.uint64(m) * n) >> np.uint64(32)
+    q = ((t + ((n - t) >> np.uint64(s1))) & np.uint64(0xFFFFFFFF)) >> np.uint64(s2)
+    assert np.array_equal(q, n // np.uint64(hw))
+
+
 def _emulate_range_cols(x2d, pl, vec):
     """Index arithmetic of the two reduction passes, replayed with numpy: returns
     (ch_min, ch_max) and checks every partial slot that pass 2 reads was written."""

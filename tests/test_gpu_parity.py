@@ -187,3 +187,52 @@ def test_non_default_stream_and_reuse_of_workspace():
     for x, xh in zip((x1, x2, x1), outs):
         want = oracle_path(to_numpy(x), 4)
         assert np.array_equal(xh.cpu().numpy(), want["xhat"])
+
+
+def test_near_ties_at_scale():
+    """Millions of inputs sitting on or next to a rounding tie of Eq. 1
+    (x ~ s * (k + 1/2) and its neighbouring floats): the quotient must be the
+    correctly rounded one for the codes to agree."""
+    g = torch.Generator(device=DEV).manual_seed(11)
+    c, n, hw = 96, 16, 1024
+    for bits in (4, 5, 8):
+        qmax = 2 ** bits - 1
+        s_true = torch.exp(torch.rand(c, generator=g, device=DEV) * 12 - 6)          # 2.5e-3 .. 400
+        k = torch.randint(0, qmax, (n, c, hw), generator=g, device=DEV).float()
+        x = (s_true.view(1, c, 1) * (k + 0.5)).contiguous()
+        bump = torch.randint(-2, 3, (n, c, hw), generator=g, device=DEV, dtype=torch.int32)
+        x = (x.view(torch.int32) + bump).view(torch.float32)
+        x[0, :, 0] = 0.0
+        x[0, :, 1] = s_true * qmax                                                   # range [0, s*qmax]
+        x = torch.minimum(x, (s_true * qmax).view(1, c, 1)).view(n, c, 32, 32).contiguous()
+        got, want = _check(x, bits, bits, what="near ties b%d" % bits)
+        # the scales the library derived are close to the planted ones, so the inputs are near ties
+        frac = np.abs((to_numpy(x).astype(np.float64) / want["scale"].reshape(1, c, 1, 1)) % 1.0 - 0.5)
+        assert np.median(frac) < 1e-5
+
+
+def test_channels_outside_the_fast_quotient_window():
+    """Scales below 2^-30, above 2^60, huge zero-points and ordinary channels mixed
+    in one tensor: lanes fall back to the general division per channel."""
+    g = torch.Generator(device=DEV).manual_seed(12)
+    for shape in [(4, 12, 8, 8), (3, 12, 7, 7), (2, 12, 1, 2048)]:
+        c = shape[1]
+        mag = torch.tensor([1e-12, 1e-11, 1.0, 1e20, 1e25, 3e-10, 1e-3, 1e19, 5.0, 1e-9, 1e30, 2.0], device=DEV)
+        x = torch.rand(shape, generator=g, device=DEV) * mag.view(1, c, 1, 1)
+        x[:, 8] += 3e8                       # offset range: zero-point ~ -1e9 (beyond 2^26)
+        for bits in (3, 8):
+            got, want = _check(x, bits, 1, what="window %s b%d" % (shape, bits))
+        assert (want["scale"] < 2.0 ** -30).any() and (want["scale"] > 2.0 ** 60).any()
+        assert (np.abs(want["zero_point"]) > 2.0 ** 26).any()
+        # stale parameters too: huge inputs against small scales, tiny inputs against large ones
+        s = np.array([2.0 ** -30, 2.0 ** 60, 1.0, 2.0 ** -29, 2.0 ** 59, 1e-5, 1e5, 3.0, 0.1, 7.0, 2.0 ** -31, 2.0 ** 61], np.float32)
+        z = np.array([0, 3, -5, 2.0 ** 26, -2.0 ** 26, 2.0 ** 27, 1, 0.3, 0.49999997, 100, 0, 1], np.float32)
+        xs = (torch.randn(shape, generator=g, device=DEV) * torch.exp(torch.randn(shape, generator=g, device=DEV) * 30)).clamp(-3e38, 3e38).contiguous()
+        xs[0, :, 0, 0] = 3.0e38
+        xs[0, :, 0, 1] = -3.0e38
+        xs[0, :, 0, 2] = 1e-45
+        xs[0, :, 0, 3] = 0.0
+        dy = workloads.make_grad(shape, 2, DEV)
+        got = gpu_path(xs, 4, dy, scale=s, zero_point=z)
+        want = oracle_path(to_numpy(xs), 4, to_numpy(dy), scale=s, zero_point=z)
+        assert_parity(got, want, "stale extreme %s" % (shape,))
