@@ -97,6 +97,27 @@ def time_steps(layers, steps, warmup, with_events):
     return dt, ev
 
 
+def time_graph_steps(layers, steps, warmup):
+    """The same step captured once into a HIP graph and replayed (no per-kernel events)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_step(layers, side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_step(layers, torch.cuda.current_stream())
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
 def kernel_breakdown(layers, reps=10):
     """Per tensor and kernel: average device time over `reps` launches (HIP events)."""
     stream = torch.cuda.current_stream()
@@ -156,6 +177,9 @@ def main():
     ap.add_argument("--cpu-sample-batch", type=int, default=128,
                     help="batch size of the sample the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="skip breakdown and other dtypes")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain device copy of known size (torch copy_ of the largest "
+                         "tensor, 3 launches) so that a counter run has a reference kernel")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -180,6 +204,9 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     value = step_bytes / (dt / args.steps) / 1e9
 
+    from paper_2503_18339_amd import profiling
+    rec = profiling.load_record() if (args.dtype == "f32") else None
+    traffic = round(rec["traffic_bytes_per_launch"]) if rec else None
     k_bytes = sum(e[2] for e in ev)
     k_launches = sum(e[3] for e in ev)
     k_ms = sum(e[0].elapsed_time(e[1]) for e in ev)
@@ -187,7 +214,7 @@ def main():
     roofline = {
         "kernel": "granq::fq_bwd_cols<granq::%s, 1, %d, true>" % ("F32" if args.dtype == "f32" else "BF16", bwd_rows),
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "launches": k_launches, "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),
         "bytes_per_launch": k_bytes // max(1, k_launches),
         "note": "one HIP event pair per step around the adjacent launches of this kernel "
@@ -207,6 +234,14 @@ def main():
         "roofline": roofline,
     }
 
+    if args.pmc_calibration:
+        big = max(layers, key=lambda L: L.numel)
+        for _ in range(3):
+            big.dx.copy_(big.x)
+        torch.cuda.synchronize()
+        out["pmc_calibration"] = {"kernel": "torch copy_ (elementwise copy)", "launches": 3,
+                                  "bytes_read": big.numel * esize, "bytes_written": big.numel * esize}
+
     if not args.no_extras:
         extra = {"per_kernel": kernel_breakdown(layers)}
         fb_us = sum(r["fwd_us"] + r["bwd_us"] for r in extra["per_kernel"])
@@ -214,6 +249,8 @@ def main():
         # same step without the per-launch events: what the events cost
         dt2, _ = time_steps(layers, args.steps, 2, with_events=False)
         extra["value_without_kernel_events_GBs"] = round(step_bytes / (dt2 / args.steps) / 1e9, 1)
+        dt3 = time_graph_steps(layers, args.steps, 2)
+        extra["value_hip_graph_replay_GBs"] = round(step_bytes / (dt3 / args.steps) / 1e9, 1)
         del layers
         torch.cuda.empty_cache()
         others = {}

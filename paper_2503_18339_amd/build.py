@@ -12,7 +12,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libgranq.so")
 SOURCES = [os.path.join(CSRC, "granq_kernels.hip")]
 HEADERS = [os.path.join(CSRC, "granq_device.h"), os.path.join(CSRC, "granq_plan.h"),
-           os.path.join(INCLUDE, "granq.h")]
+           os.path.join(CSRC, "granq_quotient.h"), os.path.join(INCLUDE, "granq.h")]
 
 # -ffp-contract=off: one rounding per source operation (no FMA contraction);
 # correctly rounded float division is HIP's default and is stated explicitly;

@@ -14,7 +14,10 @@
 
 namespace granq {
 
-constexpr int kBlock = 256;   // threads per block: four wavefronts
+#ifndef GRANQ_BLOCK
+#define GRANQ_BLOCK 256
+#endif
+constexpr int kBlock = GRANQ_BLOCK;   // threads per block: four wavefronts
 constexpr int kWave = 64;     // CDNA wavefront width
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));

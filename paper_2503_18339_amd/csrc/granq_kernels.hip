@@ -16,6 +16,7 @@
 // one wavefront per (n,c) slab, scale and zero-point wave-uniform).
 #include <hip/hip_runtime.h>
 #include <float.h>
+#include <type_traits>
 #include <stdint.h>
 
 #include "granq.h"
@@ -58,8 +59,43 @@ namespace granq {
 #define GRANQ_FAST_QUOTIENT 1
 #endif
 
-template <typename V>
-__device__ inline V load_vec(const V *p) { return *p; }
+// Threads per block of the element-wise column kernels (the reduction and the
+// row kernels use kBlock).
+#ifndef GRANQ_E_BLOCK
+#define GRANQ_E_BLOCK 64
+#endif
+constexpr int kEBlock = GRANQ_E_BLOCK;
+// Threads per block of the reduction's first pass.
+#ifndef GRANQ_R_BLOCK
+#define GRANQ_R_BLOCK 256
+#endif
+constexpr int kRBlock = GRANQ_R_BLOCK;
+
+// Streaming policy.  Data that cannot survive in the caches until it is needed
+// again is loaded with non-temporal loads, which on MI355X stream markedly
+// faster than ordinary loads; data that the next kernel re-reads is loaded
+// normally so that it stays resident.
+//   - a tensor of at least GRANQ_STREAM_BYTES is "large": the reduction and the
+//     forward stream all of it except its last GRANQ_KEEP_BYTES, which the
+//     reduction leaves in the memory-side cache and the (reverse-order) forward
+//     picks up from there;
+//   - the backward streams x and dy of any tensor of at least
+//     GRANQ_BWD_STREAM_BYTES.
+#ifndef GRANQ_STREAM_BYTES
+#define GRANQ_STREAM_BYTES ((int64_t)384 << 20)
+#endif
+#ifndef GRANQ_KEEP_BYTES
+#define GRANQ_KEEP_BYTES ((int64_t)160 << 20)
+#endif
+#ifndef GRANQ_BWD_STREAM_BYTES
+#define GRANQ_BWD_STREAM_BYTES ((int64_t)96 << 20)
+#endif
+
+template <bool NT, typename V>
+__device__ inline V load_vec(const V *p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
 
 template <typename V>
 __device__ inline void store_vec(V *p, const V &v) {
@@ -117,7 +153,7 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
     bool fast = GRANQ_FAST_QUOTIENT != 0;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kBlock) * VEC;
+        const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kEBlock) * VEC;
         active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
         int32_t ch[NS];
@@ -134,7 +170,7 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
     return fast;
 }
 
-template <typename T, int V, int U, bool UNIFORM, bool CODES, bool FAST>
+template <typename T, int V, int U, bool UNIFORM, bool CODES, bool FAST, bool NT>
 __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
                                 typename T::vec_t *__restrict__ x_hat,
                                 typename T::code_t *__restrict__ codes, float qmax, int64_t row_vecs,
@@ -146,7 +182,7 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int v = 0; v < V; ++v)
-            if (u < nrows && active[v]) in[u][v] = load_vec(x + (r + u) * row_vecs + cv[v]);
+            if (u < nrows && active[v]) in[u][v] = load_vec<NT>(x + (r + u) * row_vecs + cv[v]);
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -167,7 +203,7 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
 }
 
 template <typename T, int V, int U, bool UNIFORM, bool CODES>
-__global__ __launch_bounds__(kBlock) void fq_fwd_cols(
+__global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const typename T::vec_t *__restrict__ x, typename T::vec_t *__restrict__ x_hat,
     typename T::code_t *__restrict__ codes, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
@@ -185,18 +221,24 @@ __global__ __launch_bounds__(kBlock) void fq_fwd_cols(
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
     int64_t r = r0;
-    if (fast) {
-        for (; r + U <= r1; r += U)
-            fwd_rows<T, V, U, UNIFORM, CODES, true>(x, x_hat, codes, qmax, row_vecs, r, U, cr, cv, active);
-        if (r < r1)
-            fwd_rows<T, V, U, UNIFORM, CODES, true>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
-    } else {
+    const bool nt = r0 < plan.nt_row_end;              // block-uniform
+    if (!fast) {
         for (; r < r1; ++r)
-            fwd_rows<T, V, 1, UNIFORM, CODES, false>(x, x_hat, codes, qmax, row_vecs, r, 1, cr, cv, active);
+            fwd_rows<T, V, 1, UNIFORM, CODES, false, false>(x, x_hat, codes, qmax, row_vecs, r, 1, cr, cv, active);
+    } else if (nt) {
+        for (; r + U <= r1; r += U)
+            fwd_rows<T, V, U, UNIFORM, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, U, cr, cv, active);
+        if (r < r1)
+            fwd_rows<T, V, U, UNIFORM, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+    } else {
+        for (; r + U <= r1; r += U)
+            fwd_rows<T, V, U, UNIFORM, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, U, cr, cv, active);
+        if (r < r1)
+            fwd_rows<T, V, U, UNIFORM, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
     }
 }
 
-template <typename T, int V, int U, bool UNIFORM, bool FAST>
+template <typename T, int V, int U, bool UNIFORM, bool FAST, bool NT>
 __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
                                 const typename T::vec_t *__restrict__ dy,
                                 typename T::vec_t *__restrict__ dx, float qmax, int64_t row_vecs,
@@ -210,8 +252,8 @@ __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
         for (int v = 0; v < V; ++v)
             if (u < nrows && active[v]) {
                 const int64_t at = (r + u) * row_vecs + cv[v];
-                in[u][v] = load_vec(x + at);
-                g[u][v] = load_vec(dy + at);
+                in[u][v] = load_vec<NT>(x + at);
+                g[u][v] = load_vec<NT>(dy + at);
             }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -229,7 +271,7 @@ __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
 }
 
 template <typename T, int V, int U, bool UNIFORM>
-__global__ __launch_bounds__(kBlock) void fq_bwd_cols(
+__global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
     const typename T::vec_t *__restrict__ x, const typename T::vec_t *__restrict__ dy,
     typename T::vec_t *__restrict__ dx, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
@@ -247,14 +289,20 @@ __global__ __launch_bounds__(kBlock) void fq_bwd_cols(
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
     int64_t r = r0;
-    if (fast) {
-        for (; r + U <= r1; r += U)
-            bwd_rows<T, V, U, UNIFORM, true>(x, dy, dx, qmax, row_vecs, r, U, cr, cv, active);
-        if (r < r1)
-            bwd_rows<T, V, U, UNIFORM, true>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
-    } else {
+    const bool nt = r0 < plan.nt_row_end;              // block-uniform
+    if (!fast) {
         for (; r < r1; ++r)
-            bwd_rows<T, V, 1, UNIFORM, false>(x, dy, dx, qmax, row_vecs, r, 1, cr, cv, active);
+            bwd_rows<T, V, 1, UNIFORM, false, false>(x, dy, dx, qmax, row_vecs, r, 1, cr, cv, active);
+    } else if (nt) {
+        for (; r + U <= r1; r += U)
+            bwd_rows<T, V, U, UNIFORM, true, true>(x, dy, dx, qmax, row_vecs, r, U, cr, cv, active);
+        if (r < r1)
+            bwd_rows<T, V, U, UNIFORM, true, true>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+    } else {
+        for (; r + U <= r1; r += U)
+            bwd_rows<T, V, U, UNIFORM, true, false>(x, dy, dx, qmax, row_vecs, r, U, cr, cv, active);
+        if (r < r1)
+            bwd_rows<T, V, U, UNIFORM, true, false>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
     }
 }
 
@@ -272,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void fq_bwd_cols(
 // that overlap the channel and of all row groups.
 
 template <typename T, int V, bool UNIFORM>
-__global__ __launch_bounds__(kBlock) void range_cols_pass1(
+__global__ __launch_bounds__(kRBlock) void range_cols_pass1(
     const typename T::vec_t *__restrict__ x, float *__restrict__ ws_min,
     float *__restrict__ ws_max, ColPlan plan)
 {
@@ -287,7 +335,7 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
     const int64_t row_vecs = plan.row_len / VEC;
     const int32_t kmax = plan.kmax;
 
-    for (int i = threadIdx.x; i < kmax; i += kBlock) {
+    for (int i = threadIdx.x; i < kmax; i += kRBlock) {
         lds_keys[i] = kKeyPosInf;
         lds_keys[kmax + i] = kKeyNegInf;
     }
@@ -297,7 +345,7 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
     bool active[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kBlock) * VEC;
+        const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kRBlock) * VEC;
         active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
 #pragma unroll
@@ -310,13 +358,14 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
 
-    auto body = [&](int64_t r, const int nrows) {
+    auto body = [&](int64_t r, const int nrows, auto nt_tag) {
+        constexpr bool NT = decltype(nt_tag)::value;
         vec_t in[U][V];
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int v = 0; v < V; ++v)
-                if (u < nrows && active[v]) in[u][v] = load_vec(x + (r + u) * row_vecs + cv[v]);
+                if (u < nrows && active[v]) in[u][v] = load_vec<NT>(x + (r + u) * row_vecs + cv[v]);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -333,8 +382,13 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
     };
 
     int64_t r = r0;
-    for (; r + U <= r1; r += U) body(r, U);
-    if (r < r1) body(r, (int)(r1 - r));
+    if (r0 < plan.nt_row_end) {                        // block-uniform
+        for (; r + U <= r1; r += U) body(r, U, std::true_type{});
+        if (r < r1) body(r, (int)(r1 - r), std::true_type{});
+    } else {
+        for (; r + U <= r1; r += U) body(r, U, std::false_type{});
+        if (r < r1) body(r, (int)(r1 - r), std::false_type{});
+    }
 
     __syncthreads();                                   // LDS slots initialised
 
@@ -366,7 +420,7 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass1(
     __syncthreads();
 
     const int64_t slot = ((int64_t)p * plan.col_tiles + (int64_t)j) * kmax;
-    for (int i = threadIdx.x; i < kmax; i += kBlock) {
+    for (int i = threadIdx.x; i < kmax; i += kRBlock) {
         ws_min[slot + i] = key_float(lds_keys[i]);
         ws_max[slot + i] = key_float(lds_keys[kmax + i]);
     }
@@ -545,23 +599,42 @@ static bool aligned_elem(const void *p, granq_dtype_t dt) {
 
 static int vec_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? F32::VEC : BF16::VEC; }
 
+static int64_t tensor_bytes(const granq_desc_t *d) {
+    return d->n * d->c * d->h * d->w * (d->dtype == GRANQ_F32 ? 4 : 2);
+}
+
+// Rows [0, nt_row_end) of a large tensor are streamed, the last GRANQ_KEEP_BYTES stay cached.
+static void split_large(ColPlan &p, const granq_desc_t *d) {
+    p.nt_row_end = 0;
+    if (!p.ok || tensor_bytes(d) < GRANQ_STREAM_BYTES) return;
+    const int64_t row_bytes = tensor_bytes(d) / p.rows;
+    const int64_t keep_rows = GRANQ_KEEP_BYTES / row_bytes;
+    p.nt_row_end = p.rows > keep_rows ? p.rows - keep_rows : 0;
+}
+
 // Plans of the element-wise kernels: rows per block = rows in flight per lane.
 static ColPlan fwd_plan(const granq_desc_t *d) {
-    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                         d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kBlock,
-                         (int64_t)1 << 40, GRANQ_F_ROWS);
+    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                              d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kEBlock,
+                              (int64_t)1 << 40, GRANQ_F_ROWS);
+    split_large(p, d);
+    return p;
 }
 static ColPlan bwd_plan(const granq_desc_t *d) {
-    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                         d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kBlock,
-                         (int64_t)1 << 40, GRANQ_B_ROWS);
+    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                              d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kEBlock,
+                              (int64_t)1 << 40, GRANQ_B_ROWS);
+    p.nt_row_end = (p.ok && tensor_bytes(d) >= GRANQ_BWD_STREAM_BYTES) ? p.rows : 0;
+    return p;
 }
 
 // Plan of the reduction; it also fixes the workspace layout.
 static ColPlan range_plan(const granq_desc_t *d) {
-    return make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                         d->dtype == GRANQ_F32 ? GRANQ_R_V_F32 : GRANQ_R_V_BF16, kBlock,
-                         GRANQ_R_TARGET_BLOCKS, GRANQ_R_MIN_ROWS);
+    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                              d->dtype == GRANQ_F32 ? GRANQ_R_V_F32 : GRANQ_R_V_BF16, kRBlock,
+                              GRANQ_R_TARGET_BLOCKS, GRANQ_R_MIN_ROWS);
+    split_large(p, d);
+    return p;
 }
 
 static granq_status_t launched() {
@@ -580,7 +653,7 @@ static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
     using code_t = typename T::code_t;
-    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kBlock);
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
     auto cv = (code_t *)codes;
@@ -597,7 +670,7 @@ template <typename T, int V>
 static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, void *dx,
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
-    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kBlock);
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
     if (pl.uniform)
         hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
     else
@@ -608,7 +681,7 @@ template <typename T, int V>
 static void launch_range_cols(const ColPlan &pl, const void *x, float *ws_min, float *ws_max,
                               hipStream_t st) {
     using vec_t = typename T::vec_t;
-    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kBlock);
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kRBlock);
     size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
     if (pl.uniform)
         hipLaunchKernelGGL((range_cols_pass1<T, V, true>), grid, block, lds, st, (const vec_t *)x, ws_min, ws_max, pl);

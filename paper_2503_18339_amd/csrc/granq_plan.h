@@ -92,6 +92,7 @@ struct ColPlan {
     int32_t row_groups;      // P
     int32_t rows_per_group;
     int32_t kmax;            // most channels any column tile touches
+    int64_t nt_row_end;      // rows below this are loaded non-temporally (streamed)
     FastDiv hw_div;          // column -> channel
     bool uniform;            // every 16-byte vector lies inside one channel
     bool ok;                 // false: shape not eligible for the vector kernels

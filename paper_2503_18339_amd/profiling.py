@@ -1,0 +1,139 @@
+"""Turn rocprofv3 output of `bench.py` into the short summaries kept under
+profiles/ and into the measured-traffic record that bench.py reports.
+
+    python -m paper_2503_18339_amd.profiling trace  <bench_kernel_stats.csv>
+    python -m paper_2503_18339_amd.profiling counters <fetch_counter_collection.csv> \
+            <write_counter_collection.csv> --copy-bytes N [--write-record]
+
+`counters` expects two `rocprofv3 --pmc` runs of `bench.py --pmc-calibration`
+(FETCH_SIZE in one, WRITE_SIZE in the other; both counters are in KiB per
+dispatch).  The calibration launches are plain device copies of N bytes; what
+the counters read for them gives the factor that converts counter units into
+bytes.  `--write-record` stores the per-launch traffic of the dominant kernel,
+together with a hash of the kernel sources, in traffic_record.json next to this
+file; bench.py reports it as `roofline.traffic` only while that hash still
+matches the sources it runs.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import hashlib
+import json
+import os
+import sys
+
+from . import build as _build
+
+RECORD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "traffic_record.json")
+COPY_KERNEL = "__amd_rocclr_copyBuffer"
+
+
+def source_hash() -> str:
+    """Hash of everything that determines the kernels' code: sources, headers, flags."""
+    h = hashlib.sha256()
+    for path in sorted(_build.SOURCES + _build.HEADERS):
+        with open(path, "rb") as fh:
+            h.update(os.path.basename(path).encode())
+            h.update(fh.read())
+    h.update(" ".join(_build.HIPCC_FLAGS).encode())
+    return h.hexdigest()[:16]
+
+
+def _short(name: str) -> str:
+    name = name.replace("granq::", "").replace("void ", "")
+    cut = name.find("(")
+    return name[:cut] if cut > 0 else name
+
+
+def summarise_trace(stats_csv: str) -> str:
+    rows = list(csv.DictReader(open(stats_csv)))
+    out = ["%-58s %7s %12s %10s %7s" % ("kernel", "calls", "avg_us", "total_ms", "%")]
+    for r in rows:
+        if float(r["Percentage"]) < 0.05:
+            continue
+        out.append("%-58s %7d %12.2f %10.2f %7.2f" % (
+            _short(r["Name"])[:58], int(r["Calls"]), float(r["AverageNs"]) / 1e3,
+            float(r["TotalDurationNs"]) / 1e6, float(r["Percentage"])))
+    return "\n".join(out)
+
+
+def _per_kernel(counter_csv: str):
+    agg = collections.defaultdict(list)
+    for r in csv.DictReader(open(counter_csv)):
+        agg[(r["Kernel_Name"], int(r["Grid_Size"]))].append(float(r["Counter_Value"]))
+    return agg
+
+
+def summarise_counters(fetch_csv: str, write_csv: str, copy_bytes: int, dominant: str = "fq_bwd_cols"):
+    fetch, write = _per_kernel(fetch_csv), _per_kernel(write_csv)
+
+    def copy_reading(agg):
+        vals = [max(v) for (k, _), v in agg.items() if k.startswith(COPY_KERNEL)]
+        if not vals:
+            raise SystemExit("no calibration copy kernel in the counter file")
+        return max(vals)
+
+    f_scale = copy_bytes / 1024.0 / copy_reading(fetch)
+    w_scale = copy_bytes / 1024.0 / copy_reading(write)
+    lines = ["calibration: plain device copy of %d bytes reads FETCH_SIZE %.1f KiB, WRITE_SIZE %.1f KiB"
+             % (copy_bytes, copy_reading(fetch), copy_reading(write)),
+             "             -> bytes = FETCH_SIZE * 1024 * %.4f,  bytes = WRITE_SIZE * 1024 * %.4f" % (f_scale, w_scale),
+             "", "%-50s %12s %14s %14s" % ("kernel", "grid", "fetched MB", "written MB")]
+    per_kernel = collections.defaultdict(lambda: [0.0, 0.0, 0])
+    for (k, g), v in sorted(fetch.items(), key=lambda kv: -max(kv[1])):
+        if "granq::" not in k:
+            continue
+        fb = sum(v) / len(v) * 1024 * f_scale
+        wv = write.get((k, g), [0.0])
+        wb = sum(wv) / len(wv) * 1024 * w_scale
+        lines.append("%-50s %12d %14.2f %14.2f" % (_short(k)[:50], g, fb / 1e6, wb / 1e6))
+        rec = per_kernel[_short(k)]
+        rec[0] += fb
+        rec[1] += wb
+        rec[2] += 1
+    dom = [(k, r) for k, r in per_kernel.items() if dominant in k and k.rstrip(">").endswith("true")]
+    if not dom:
+        raise SystemExit("dominant kernel %r not found" % dominant)
+    name, (fb, wb, shapes) = max(dom, key=lambda kr: kr[1][0] + kr[1][1])
+    record = {"kernel": name, "launch_shapes": shapes, "fetch_bytes_per_launch": fb / shapes,
+              "write_bytes_per_launch": wb / shapes, "traffic_bytes_per_launch": (fb + wb) / shapes,
+              "fetch_scale": f_scale, "write_scale": w_scale, "source_hash": source_hash()}
+    lines += ["", "dominant kernel %s: %.2f MB fetched + %.2f MB written per launch (mean over its %d launch shapes)"
+              % (name, fb / shapes / 1e6, wb / shapes / 1e6, shapes)]
+    return "\n".join(lines), record
+
+
+def load_record():
+    """The stored traffic figure, or None when it was taken from other kernel sources."""
+    try:
+        rec = json.load(open(RECORD))
+    except (OSError, ValueError):
+        return None
+    return rec if rec.get("source_hash") == source_hash() else None
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    t = sub.add_parser("trace")
+    t.add_argument("stats_csv")
+    c = sub.add_parser("counters")
+    c.add_argument("fetch_csv")
+    c.add_argument("write_csv")
+    c.add_argument("--copy-bytes", type=int, required=True)
+    c.add_argument("--write-record", action="store_true")
+    args = ap.parse_args(argv)
+    if args.cmd == "trace":
+        print(summarise_trace(args.stats_csv))
+    else:
+        text, record = summarise_counters(args.fetch_csv, args.write_csv, args.copy_bytes)
+        print(text)
+        if args.write_record:
+            json.dump(record, open(RECORD, "w"), indent=1)
+            print("\nwrote", RECORD, file=sys.stderr)
+
+
+if __name__ == "__main__":
+    main()
