@@ -28,6 +28,8 @@ GRANQ_BF16 = 1
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
            "granq_range_reduce",
            "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd")
+COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
+                   "granq_cmp_accumulate_prescaled")
 
 
 class granq_desc_t(ctypes.Structure):
@@ -69,7 +71,11 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_prescale.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_fwd.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_bwd.argtypes = [_vp, _vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp]
-    for name in EXPORTS[2:]:
+    lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
+                                               ctypes.c_size_t, _vp]
+    lib.granq_cmp_accumulate_inloop.argtypes = [_vp, dp, _vp, _vp, _vp, _vp, _vp]
+    lib.granq_cmp_accumulate_prescaled.argtypes = [_vp, dp, _vp, _vp, _vp]
+    for name in EXPORTS[2:] + COMPARE_EXPORTS:
         getattr(lib, name).restype = ctypes.c_int
     if path is None:
         _lib = lib
@@ -195,3 +201,38 @@ def granq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, scale: torch.Tensor,
                                       _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"),
                                       int(bits), _dev(dx, "dx"), _stream(stream)),
            "granq_fakequant_bwd")
+
+
+# --- comparison points for the benchmark (include/granq_compare.h) ---------------------------
+
+def granq_cmp_channel_loop_fwd(x: torch.Tensor, bits: int, ch_min: torch.Tensor, ch_max: torch.Tensor,
+                               scale: torch.Tensor, zero_point: torch.Tensor, x_hat: torch.Tensor,
+                               workspace: torch.Tensor, stream=None,
+                               desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    _check(load().granq_cmp_channel_loop_fwd(
+        _dev(x, "x"), ctypes.byref(d), int(bits), _vec(ch_min, d.c, "ch_min"), _vec(ch_max, d.c, "ch_max"),
+        _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"), _dev(x_hat, "x_hat"),
+        _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream(stream)),
+        "granq_cmp_channel_loop_fwd")
+
+
+def granq_cmp_accumulate_inloop(codes: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor,
+                                weight: torch.Tensor, y: torch.Tensor, stream=None,
+                                desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or make_desc(codes.shape[0], codes.shape[1], codes.shape[2], codes.shape[3], GRANQ_F32)
+    if codes.dtype != torch.uint8 or y.dtype != torch.float32 or y.numel() != d.n * d.h * d.w:
+        raise ValueError("codes must be uint8 and y float32 with N*H*W entries")
+    _check(load().granq_cmp_accumulate_inloop(
+        _dev(codes, "codes"), ctypes.byref(d), _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"),
+        _vec(weight, d.c, "weight"), _dev(y, "y"), _stream(stream)), "granq_cmp_accumulate_inloop")
+
+
+def granq_cmp_accumulate_prescaled(x_hat: torch.Tensor, weight: torch.Tensor, y: torch.Tensor, stream=None,
+                                   desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x_hat)
+    if x_hat.dtype != torch.float32 or y.dtype != torch.float32 or y.numel() != d.n * d.h * d.w:
+        raise ValueError("x_hat and y must be float32, y with N*H*W entries")
+    _check(load().granq_cmp_accumulate_prescaled(
+        _dev(x_hat, "x_hat"), ctypes.byref(d), _vec(weight, d.c, "weight"), _dev(y, "y"), _stream(stream)),
+        "granq_cmp_accumulate_prescaled")

@@ -10,9 +10,10 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libgranq.so")
-SOURCES = [os.path.join(CSRC, "granq_kernels.hip")]
+SOURCES = [os.path.join(CSRC, "granq_kernels.hip"), os.path.join(CSRC, "granq_compare.hip")]
 HEADERS = [os.path.join(CSRC, "granq_device.h"), os.path.join(CSRC, "granq_plan.h"),
-           os.path.join(CSRC, "granq_quotient.h"), os.path.join(INCLUDE, "granq.h")]
+           os.path.join(CSRC, "granq_quotient.h"), os.path.join(INCLUDE, "granq.h"),
+           os.path.join(INCLUDE, "granq_compare.h")]
 
 # -ffp-contract=off: one rounding per source operation (no FMA contraction);
 # correctly rounded float division is HIP's default and is stated explicitly;

@@ -31,9 +31,11 @@ COPY_KERNEL = "__amd_rocclr_copyBuffer"
 
 
 def source_hash() -> str:
-    """Hash of everything that determines the kernels' code: sources, headers, flags."""
+    """Hash of everything that determines the quantizer kernels' code: sources, headers, flags
+    (the benchmark-only comparison kernels are left out)."""
     h = hashlib.sha256()
-    for path in sorted(_build.SOURCES + _build.HEADERS):
+    paths = [p for p in _build.SOURCES + _build.HEADERS if "compare" not in os.path.basename(p)]
+    for path in sorted(paths):
         with open(path, "rb") as fh:
             h.update(os.path.basename(path).encode())
             h.update(fh.read())

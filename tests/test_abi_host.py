@@ -14,8 +14,8 @@ from paper_2503_18339_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "granq.h")).read()
+def _declared_functions(header="granq.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(granq_[a-z_]+)\s*\(", text)))
 
@@ -25,6 +25,10 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
     for name in names:
+        assert getattr(lib, name) is not None
+    cmp_names = _declared_functions("granq_compare.h")
+    assert set(cmp_names) == set(B.COMPARE_EXPORTS), (cmp_names, B.COMPARE_EXPORTS)
+    for name in cmp_names:
         assert getattr(lib, name) is not None
 
 
