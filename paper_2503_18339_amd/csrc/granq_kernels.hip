@@ -106,21 +106,6 @@ __device__ inline void store_vec(V *p, const V &v) {
 #endif
 }
 
-// Channels of the NS elements (1 if the vector lies inside one channel, else
-// VEC) of a vector starting at column `col`.
-template <int NS>
-__device__ inline void lane_channels(uint32_t col, const ColPlan &plan, int32_t (&ch)[NS]) {
-    uint32_t c0 = fastdiv(col, plan.hw_div);
-    uint32_t rem = col - c0 * plan.hw_div.d;
-    ch[0] = (int32_t)c0;
-#pragma unroll
-    for (int e = 1; e < NS; ++e) {
-        rem += 1;
-        if (rem == plan.hw_div.d) { rem = 0; c0 += 1; }
-        ch[e] = (int32_t)c0;
-    }
-}
-
 // What a lane keeps per channel while it walks down its rows.
 struct ChanRegs {
     float s, z, r;       // scale, zero-point, RN(1/scale)
@@ -141,15 +126,60 @@ __device__ inline float code_of(float x, const ChanRegs &c) {
 // fake-quant forward and straight-through backward, column kernels
 // ---------------------------------------------------------------------------
 
+// How the elements of one 16-byte vector map to channels (template parameter MODE):
+//   kOne   H*W is a multiple of the vector width: the whole vector is one channel
+//   kTwo   H*W >= vector width: at most two channels, elements [0, split) and [split, VEC)
+//   kEach  H*W < vector width: every element may have its own channel
+constexpr int kOne = 0, kTwo = 1, kEach = 2;
+template <int MODE, int VEC>
+struct Slots { static constexpr int N = MODE == kOne ? 1 : (MODE == kTwo ? 2 : VEC); };
+
+template <int MODE, int NS>
+__device__ inline ChanRegs pick_chan(const ChanRegs (&c)[NS], int e, uint32_t split) {
+    if (MODE == kOne) return c[0];
+    if (MODE == kEach) return c[e < NS ? e : 0];
+    ChanRegs r;
+    const bool first = (uint32_t)e < split;
+    r.s = first ? c[0].s : c[NS > 1 ? 1 : 0].s;
+    r.z = first ? c[0].z : c[NS > 1 ? 1 : 0].z;
+    r.r = first ? c[0].r : c[NS > 1 ? 1 : 0].r;
+    return r;
+}
+
+// Channels of this lane's vector starting at column `col`: ch[] per slot, and the
+// number of leading elements that belong to the first channel.
+template <int MODE, int VEC, int NS>
+__device__ inline uint32_t vector_channels(uint32_t col, const ColPlan &plan, int32_t (&ch)[NS]) {
+    const uint32_t c0 = fastdiv(col, plan.hw_div);
+    const uint32_t rem = col - c0 * plan.hw_div.d;
+    if (MODE == kEach) {
+        uint32_t c = c0, r = rem;
+        ch[0] = (int32_t)c;
+#pragma unroll
+        for (int e = 1; e < NS; ++e) {
+            r += 1;
+            if (r == plan.hw_div.d) { r = 0; c += 1; }
+            ch[e] = (int32_t)c;
+        }
+        return VEC;
+    }
+    ch[0] = (int32_t)c0;
+    if (MODE == kOne) return VEC;
+    const uint32_t left = plan.hw_div.d - rem;           // elements of channel c0 from col on
+    const uint32_t split = left < (uint32_t)VEC ? left : (uint32_t)VEC;
+    ch[NS > 1 ? 1 : 0] = (int32_t)(split < (uint32_t)VEC ? c0 + 1 : c0);
+    return split;
+}
+
 // Shared prologue: this lane's vectors within a row and their channels' registers.
 // Returns true when every channel this lane touches admits the fast quotient.
-template <typename T, int V, bool UNIFORM>
+template <typename T, int V, int MODE>
 __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *__restrict__ scale,
                                   const float *__restrict__ zero_point,
-                                  ChanRegs (&cr)[V][UNIFORM ? 1 : T::VEC], uint32_t (&cv)[V],
-                                  bool (&active)[V]) {
+                                  ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N], uint32_t (&split)[V],
+                                  uint32_t (&cv)[V], bool (&active)[V]) {
     constexpr int VEC = T::VEC;
-    constexpr int NS = UNIFORM ? 1 : VEC;
+    constexpr int NS = Slots<MODE, VEC>::N;
     bool fast = GRANQ_FAST_QUOTIENT != 0;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
@@ -157,7 +187,7 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
         active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
         int32_t ch[NS];
-        lane_channels<NS>(active[v] ? col : 0u, plan, ch);
+        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? col : 0u, plan, ch);
 #pragma unroll
         for (int e = 0; e < NS; ++e) {
             const float s = scale[ch[e]], z = zero_point[ch[e]];
@@ -170,12 +200,13 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
     return fast;
 }
 
-template <typename T, int V, int U, bool UNIFORM, bool CODES, bool FAST, bool NT>
+template <typename T, int V, int U, int MODE, bool CODES, bool FAST, bool NT>
 __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
                                 typename T::vec_t *__restrict__ x_hat,
                                 typename T::code_t *__restrict__ codes, float qmax, int64_t row_vecs,
-                                int64_t r, int nrows, const ChanRegs (&cr)[V][UNIFORM ? 1 : T::VEC],
-                                const uint32_t (&cv)[V], const bool (&active)[V]) {
+                                int64_t r, int nrows, const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
+                                const uint32_t (&split)[V], const uint32_t (&cv)[V],
+                                const bool (&active)[V]) {
     constexpr int VEC = T::VEC;
     typename T::vec_t in[U][V];
 #pragma unroll
@@ -192,7 +223,7 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
                 T::unpack(in[u][v], f);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const ChanRegs &c = cr[v][UNIFORM ? 0 : e];
+                    const ChanRegs c = pick_chan<MODE>(cr[v], e, split[v]);
                     q[e] = clamp_code(code_of<FAST>(f[e], c), qmax);
                     f[e] = dequant(q[e], c.s, c.z);
                 }
@@ -202,21 +233,21 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
             }
 }
 
-template <typename T, int V, int U, bool UNIFORM, bool CODES>
+template <typename T, int V, int U, int MODE, bool CODES>
 __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const typename T::vec_t *__restrict__ x, typename T::vec_t *__restrict__ x_hat,
     typename T::code_t *__restrict__ codes, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
-    constexpr int NS = UNIFORM ? 1 : T::VEC;
+    constexpr int NS = Slots<MODE, T::VEC>::N;
     const uint32_t j = GRANQ_FWD_REVERSE ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
     const uint32_t p = GRANQ_FWD_REVERSE ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
     const int64_t row_vecs = plan.row_len / T::VEC;
 
     ChanRegs cr[V][NS];
-    uint32_t cv[V];
+    uint32_t split[V], cv[V];
     bool active[V];
-    const bool fast = lane_setup<T, V, UNIFORM>(plan, j, scale, zero_point, cr, cv, active);
+    const bool fast = lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active);
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
@@ -224,26 +255,27 @@ __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const bool nt = r0 < plan.nt_row_end;              // block-uniform
     if (!fast) {
         for (; r < r1; ++r)
-            fwd_rows<T, V, 1, UNIFORM, CODES, false, false>(x, x_hat, codes, qmax, row_vecs, r, 1, cr, cv, active);
+            fwd_rows<T, V, 1, MODE, CODES, false, false>(x, x_hat, codes, qmax, row_vecs, r, 1, cr, split, cv, active);
     } else if (nt) {
         for (; r + U <= r1; r += U)
-            fwd_rows<T, V, U, UNIFORM, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, U, cr, cv, active);
+            fwd_rows<T, V, U, MODE, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
-            fwd_rows<T, V, U, UNIFORM, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+            fwd_rows<T, V, U, MODE, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
     } else {
         for (; r + U <= r1; r += U)
-            fwd_rows<T, V, U, UNIFORM, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, U, cr, cv, active);
+            fwd_rows<T, V, U, MODE, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
-            fwd_rows<T, V, U, UNIFORM, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+            fwd_rows<T, V, U, MODE, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
     }
 }
 
-template <typename T, int V, int U, bool UNIFORM, bool FAST, bool NT>
+template <typename T, int V, int U, int MODE, bool FAST, bool NT>
 __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
                                 const typename T::vec_t *__restrict__ dy,
                                 typename T::vec_t *__restrict__ dx, float qmax, int64_t row_vecs,
-                                int64_t r, int nrows, const ChanRegs (&cr)[V][UNIFORM ? 1 : T::VEC],
-                                const uint32_t (&cv)[V], const bool (&active)[V]) {
+                                int64_t r, int nrows, const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
+                                const uint32_t (&split)[V], const uint32_t (&cv)[V],
+                                const bool (&active)[V]) {
     constexpr int VEC = T::VEC;
     typename T::vec_t in[U][V], g[U][V];
 #pragma unroll
@@ -265,26 +297,26 @@ __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
                 T::unpack(in[u][v], f);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e)
-                    keep[e] = in_range(code_of<FAST>(f[e], cr[v][UNIFORM ? 0 : e]), qmax);
+                    keep[e] = in_range(code_of<FAST>(f[e], pick_chan<MODE>(cr[v], e, split[v])), qmax);
                 store_vec(dx + (r + u) * row_vecs + cv[v], T::gate(g[u][v], keep));
             }
 }
 
-template <typename T, int V, int U, bool UNIFORM>
+template <typename T, int V, int U, int MODE>
 __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
     const typename T::vec_t *__restrict__ x, const typename T::vec_t *__restrict__ dy,
     typename T::vec_t *__restrict__ dx, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
-    constexpr int NS = UNIFORM ? 1 : T::VEC;
+    constexpr int NS = Slots<MODE, T::VEC>::N;
     const uint32_t j = blockIdx.x;
     const uint32_t p = blockIdx.y;
     const int64_t row_vecs = plan.row_len / T::VEC;
 
     ChanRegs cr[V][NS];
-    uint32_t cv[V];
+    uint32_t split[V], cv[V];
     bool active[V];
-    const bool fast = lane_setup<T, V, UNIFORM>(plan, j, scale, zero_point, cr, cv, active);
+    const bool fast = lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active);
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
@@ -292,17 +324,17 @@ __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
     const bool nt = r0 < plan.nt_row_end;              // block-uniform
     if (!fast) {
         for (; r < r1; ++r)
-            bwd_rows<T, V, 1, UNIFORM, false, false>(x, dy, dx, qmax, row_vecs, r, 1, cr, cv, active);
+            bwd_rows<T, V, 1, MODE, false, false>(x, dy, dx, qmax, row_vecs, r, 1, cr, split, cv, active);
     } else if (nt) {
         for (; r + U <= r1; r += U)
-            bwd_rows<T, V, U, UNIFORM, true, true>(x, dy, dx, qmax, row_vecs, r, U, cr, cv, active);
+            bwd_rows<T, V, U, MODE, true, true>(x, dy, dx, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
-            bwd_rows<T, V, U, UNIFORM, true, true>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+            bwd_rows<T, V, U, MODE, true, true>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
     } else {
         for (; r + U <= r1; r += U)
-            bwd_rows<T, V, U, UNIFORM, true, false>(x, dy, dx, qmax, row_vecs, r, U, cr, cv, active);
+            bwd_rows<T, V, U, MODE, true, false>(x, dy, dx, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
-            bwd_rows<T, V, U, UNIFORM, true, false>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, cv, active);
+            bwd_rows<T, V, U, MODE, true, false>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
     }
 }
 
@@ -319,13 +351,13 @@ __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
 // Pass 2: one wavefront per channel gathers the partials of all column tiles
 // that overlap the channel and of all row groups.
 
-template <typename T, int V, bool UNIFORM>
+template <typename T, int V, int MODE>
 __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
     const typename T::vec_t *__restrict__ x, float *__restrict__ ws_min,
     float *__restrict__ ws_max, ColPlan plan)
 {
     constexpr int VEC = T::VEC;
-    constexpr int NS = UNIFORM ? 1 : VEC;
+    constexpr int NS = MODE == kOne ? 1 : VEC;           // running min/max per element position
     constexpr int U = GRANQ_R_UNROLL;
     using vec_t = typename T::vec_t;
     extern __shared__ uint32_t lds_keys[];          // [kmax] min keys, then [kmax] max keys
@@ -375,8 +407,8 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
                     T::unpack(in[u][v], f);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
-                        mn[v][UNIFORM ? 0 : e] = __builtin_fminf(mn[v][UNIFORM ? 0 : e], f[e]);
-                        mx[v][UNIFORM ? 0 : e] = __builtin_fmaxf(mx[v][UNIFORM ? 0 : e], f[e]);
+                        mn[v][MODE == kOne ? 0 : e] = __builtin_fminf(mn[v][MODE == kOne ? 0 : e], f[e]);
+                        mx[v][MODE == kOne ? 0 : e] = __builtin_fmaxf(mx[v][MODE == kOne ? 0 : e], f[e]);
                     }
                 }
     };
@@ -393,26 +425,48 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
     __syncthreads();                                   // LDS slots initialised
 
     const int32_t ch_first = (int32_t)fastdiv(j * (uint32_t)plan.span, plan.hw_div);
+    constexpr int NG = Slots<MODE, VEC>::N;             // channel groups per vector
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         // inactive lanes hold the identities and point at the tile's first channel
         const uint32_t col = active[v] ? cv[v] * VEC : j * (uint32_t)plan.span;
-        int32_t ch[NS];
-        lane_channels<NS>(col, plan, ch);
+        int32_t ch[NG];
+        const uint32_t split = vector_channels<MODE, VEC, NG>(col, plan, ch);
+        float gmn[NG], gmx[NG];
+        if (MODE == kTwo) {
+            // fold the element positions into the (at most) two channels of the vector
+            gmn[0] = gmn[NG - 1] = __builtin_inff();
+            gmx[0] = gmx[NG - 1] = -__builtin_inff();
 #pragma unroll
-        for (int e = 0; e < NS; ++e) {
+            for (int e = 0; e < VEC; ++e) {
+                const bool first = (uint32_t)e < split;
+                const float a = mn[v][e < NS ? e : 0], b = mx[v][e < NS ? e : 0];
+                gmn[0] = __builtin_fminf(gmn[0], first ? a : __builtin_inff());
+                gmx[0] = __builtin_fmaxf(gmx[0], first ? b : -__builtin_inff());
+                gmn[NG - 1] = __builtin_fminf(gmn[NG - 1], first ? __builtin_inff() : a);
+                gmx[NG - 1] = __builtin_fmaxf(gmx[NG - 1], first ? -__builtin_inff() : b);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < NG; ++e) {
+                gmn[e] = mn[v][e < NS ? e : 0];
+                gmx[e] = mx[v][e < NS ? e : 0];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < NG; ++e) {
             const int32_t k = ch[e] - ch_first;
             const int32_t k_lead = __builtin_amdgcn_readfirstlane(k);
             if (__all(k == k_lead)) {
-                float wmn = wave_min(mn[v][e]);
-                float wmx = wave_max(mx[v][e]);
+                float wmn = wave_min(gmn[e]);
+                float wmx = wave_max(gmx[e]);
                 if ((threadIdx.x & (kWave - 1)) == 0) {
                     atomicMin(&lds_keys[k_lead], float_key(wmn));
                     atomicMax(&lds_keys[kmax + k_lead], float_key(wmx));
                 }
             } else {
-                atomicMin(&lds_keys[k], float_key(mn[v][e]));
-                atomicMax(&lds_keys[kmax + k], float_key(mx[v][e]));
+                atomicMin(&lds_keys[k], float_key(gmn[e]));
+                atomicMax(&lds_keys[kmax + k], float_key(gmx[e]));
             }
         }
     }
@@ -648,8 +702,8 @@ static uint32_t row_grid(int64_t slabs) {
     return (uint32_t)(blocks < cap ? blocks : cap);
 }
 
-template <typename T, int V>
-static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8_t *codes,
+template <typename T, int V, int MODE>
+static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, uint8_t *codes,
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
     using code_t = typename T::code_t;
@@ -657,13 +711,16 @@ static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
     auto cv = (code_t *)codes;
-    if (pl.uniform) {
-        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, true, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-        else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, true, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-    } else {
-        if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, false, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-        else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, false, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-    }
+    if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+    else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+}
+
+template <typename T, int V>
+static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8_t *codes,
+                            const float *s, const float *z, float qmax, hipStream_t st) {
+    if (pl.mode == kOne) launch_fwd_mode<T, V, kOne>(pl, x, x_hat, codes, s, z, qmax, st);
+    else if (pl.mode == kTwo) launch_fwd_mode<T, V, kTwo>(pl, x, x_hat, codes, s, z, qmax, st);
+    else launch_fwd_mode<T, V, kEach>(pl, x, x_hat, codes, s, z, qmax, st);
 }
 
 template <typename T, int V>
@@ -671,10 +728,15 @@ static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, vo
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
     dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
-    if (pl.uniform)
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
+    auto xv = (const vec_t *)x;
+    auto gv = (const vec_t *)dy;
+    auto ov = (vec_t *)dx;
+    if (pl.mode == kOne)
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+    else if (pl.mode == kTwo)
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
     else
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false>), grid, block, 0, st, (const vec_t *)x, (const vec_t *)dy, (vec_t *)dx, s, z, qmax, pl);
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
 }
 
 template <typename T, int V>
@@ -683,10 +745,13 @@ static void launch_range_cols(const ColPlan &pl, const void *x, float *ws_min, f
     using vec_t = typename T::vec_t;
     dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kRBlock);
     size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
-    if (pl.uniform)
-        hipLaunchKernelGGL((range_cols_pass1<T, V, true>), grid, block, lds, st, (const vec_t *)x, ws_min, ws_max, pl);
+    auto xv = (const vec_t *)x;
+    if (pl.mode == kOne)
+        hipLaunchKernelGGL((range_cols_pass1<T, V, kOne>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+    else if (pl.mode == kTwo)
+        hipLaunchKernelGGL((range_cols_pass1<T, V, kTwo>), grid, block, lds, st, xv, ws_min, ws_max, pl);
     else
-        hipLaunchKernelGGL((range_cols_pass1<T, V, false>), grid, block, lds, st, (const vec_t *)x, ws_min, ws_max, pl);
+        hipLaunchKernelGGL((range_cols_pass1<T, V, kEach>), grid, block, lds, st, xv, ws_min, ws_max, pl);
 }
 
 static size_t col_ws_floats(const ColPlan &pl) {

@@ -95,6 +95,7 @@ struct ColPlan {
     int64_t nt_row_end;      // rows below this are loaded non-temporally (streamed)
     FastDiv hw_div;          // column -> channel
     bool uniform;            // every 16-byte vector lies inside one channel
+    int32_t mode;            // 0: one channel per vector, 1: at most two, 2: up to one per element
     bool ok;                 // false: shape not eligible for the vector kernels
 };
 
@@ -137,6 +138,7 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
     int64_t k = (p.span - 1) / per + 2;
     p.kmax = (int32_t)(k < chan ? k : chan);
     p.uniform = (per % vec) == 0;
+    p.mode = p.uniform ? 0 : (per >= vec ? 1 : 2);
     p.ok = true;
     return p;
 }
