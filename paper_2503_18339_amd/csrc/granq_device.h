@@ -23,6 +23,8 @@ constexpr int kWave = 64;     // CDNA wavefront width
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------
 // storage traits: one 16-byte vector per lane and per load
@@ -77,12 +79,21 @@ struct BF16 {
         f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
         f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
     }
+    // v_cvt_pk_bf16_f32 rounds to nearest even; checked against bf16_round on every
+    // finite binary32 pattern, subnormals included.
+    __device__ static inline uint32_t pack2(float lo, float hi) {
+        f32x2 v = {lo, hi};
+        bf16x2 b = __builtin_convertvector(v, bf16x2);
+        uint32_t u;
+        __builtin_memcpy(&u, &b, sizeof u);
+        return u;
+    }
     __device__ static inline vec_t pack(const float (&f)[VEC]) {
         vec_t v;
-        v.x = bf16_round(f[0]) | (bf16_round(f[1]) << 16);
-        v.y = bf16_round(f[2]) | (bf16_round(f[3]) << 16);
-        v.z = bf16_round(f[4]) | (bf16_round(f[5]) << 16);
-        v.w = bf16_round(f[6]) | (bf16_round(f[7]) << 16);
+        v.x = pack2(f[0], f[1]);
+        v.y = pack2(f[2], f[3]);
+        v.z = pack2(f[4], f[5]);
+        v.w = pack2(f[6], f[7]);
         return v;
     }
     __device__ static inline code_t pack_codes(const float (&q)[VEC]) {
@@ -122,8 +133,9 @@ __device__ inline float raw_code(float x, float s, float z) {
     return __builtin_rintf(v);
 }
 
+// Clamp to [0, qmax]: the median of (u, 0, qmax), one instruction.
 __device__ inline float clamp_code(float u, float qmax) {
-    return __builtin_fminf(__builtin_fmaxf(u, 0.0f), qmax);
+    return __builtin_amdgcn_fmed3f(u, 0.0f, qmax);
 }
 
 // Dequantization of Eq. 6: s * (q - z).
