@@ -235,6 +235,38 @@ def comparison_points(wl, bits, device):
     return out
 
 
+def gate_bit_variant(wl, dtype, bits, device, steps, warmup):
+    """The same step with the forward emitting one gate bit per element and the backward reading
+    dy + bits instead of x + dy (granq_fakequant_fwd_mask / granq_fakequant_bwd_mask)."""
+    layers = build_layers(wl, dtype, bits, device)
+    for L in layers:
+        L.mask = torch.empty(G.granq_mask_bytes(L.q.desc), dtype=torch.uint8, device=device)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for L in layers:
+            L.q.calibrate(L.x, stream)
+            G.granq_fakequant_fwd_mask(L.x, L.q.scale, L.q.zero_point, L.q.bits, L.x_hat, L.mask, stream, L.q.desc)
+        for L in reversed(layers):
+            G.granq_fakequant_bwd_mask(L.dy, L.mask, L.dx, stream, L.q.desc)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    elems = sum(L.numel for L in layers)
+    e = layers[0].esize
+    moved = elems * (5 * e + 0.25)          # reduce e, fwd 2e + 1/8, bwd 2e + 1/8
+    return {"ms_per_step": round(dt * 1e3, 4), "bytes_moved_per_step": int(moved),
+            "GBs_on_bytes_moved": round(moved / dt / 1e9, 1),
+            "speedup_vs_x_based_step": None,
+            "note": "same results as the four-call step; %.3f instead of %d bytes per element" % (5 * e + 0.25, 6 * e)}
+
+
 def cpu_baseline(wl, bits, sample_batch, min_seconds=10.0, max_passes=8):
     """The CPU oracle, as it stands, single thread, on the same tensors at batch
     `sample_batch` (float32): whole passes (range_reduce+prescale+fwd+bwd) are
@@ -362,6 +394,9 @@ def main():
             torch.cuda.empty_cache()
         extra["other_dtypes_bits"] = others
         extra["comparison_points"] = comparison_points(wl, args.bits, device)
+        extra["gate_bit_variant"] = gate_bit_variant(wl, dtype, args.bits, device, args.steps, args.warmup)
+        extra["gate_bit_variant"]["speedup_vs_x_based_step"] = round(
+            ms_per_step / extra["gate_bit_variant"]["ms_per_step"], 3)
         out["extra"] = extra
 
     if args.cpu_sample_batch > 0:

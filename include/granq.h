@@ -156,6 +156,28 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy,
                                    const float *scale, const float *zero_point,
                                    int bits, void *dx, void *stream);
 
+/*
+ * Gate-bit variant of the forward / backward pair.  The forward already decides,
+ * per element, whether the clamp was inactive; stored as one bit per element it
+ * lets the backward read dy and E/8 bytes instead of dy and x (8.125 instead of
+ * 12 bytes per float32 element), with identical results:
+ *     granq_fakequant_fwd_mask  = granq_fakequant_fwd, plus mask
+ *     granq_fakequant_bwd_mask(dy, mask) == granq_fakequant_bwd(x, dy, scale, zero_point)
+ * for the x, scale, zero_point and bits the mask was made with.
+ * mask layout: bit (i & 7) of byte (i >> 3) is 1 where 0 <= u <= 2^bits - 1 for the
+ * element with flat NCHW index i; unused high bits of the last byte are 0.
+ * granq_mask_bytes (host-only) returns ceil(N*C*H*W / 8).
+ * x_hat may alias x; dx may alias dy.
+ */
+granq_status_t granq_mask_bytes(const granq_desc_t *desc, size_t *bytes_out);
+
+granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc,
+                                        const float *scale, const float *zero_point,
+                                        int bits, void *x_hat, uint8_t *mask, void *stream);
+
+granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask,
+                                        const granq_desc_t *desc, void *dx, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

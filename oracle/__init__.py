@@ -62,9 +62,11 @@ def load(path: str | None = None) -> ctypes.CDLL:
                                                _int, _ptr, _ptr]
     lib.granq_oracle_fakequant_bwd.argtypes = [_ptr, _ptr, _int, _i64, _i64, _i64, _ptr, _ptr,
                                                _int, _ptr]
+    lib.granq_oracle_gate_mask.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr]
+    lib.granq_oracle_bwd_from_mask.argtypes = [_ptr, _ptr, _int, _i64, _ptr]
     lib.granq_oracle_accumulate_inloop.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_prescaled.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr]
-    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd",
+    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask",
                  "accumulate_inloop", "accumulate_prescaled"):
         getattr(lib, "granq_oracle_" + name).restype = None
     if path is None:
@@ -150,6 +152,27 @@ def fakequant_bwd(x: np.ndarray, dy: np.ndarray, scale, zero_point, bits: int, l
     dx = np.empty_like(x)
     lib.granq_oracle_fakequant_bwd(_p(x), _p(dy), _dtype_code(x), n, c, hw, _p(s), _p(z),
                                    int(bits), _p(dx))
+    return dx
+
+
+def gate_mask(x: np.ndarray, scale, zero_point, bits: int, lib=None) -> np.ndarray:
+    """Packed straight-through gate: bit (i & 7) of byte (i >> 3), 1 = clamp inactive."""
+    lib = lib or load()
+    n, c, hw = _nchw(x)
+    s = _f32vec(scale, c)
+    z = _f32vec(zero_point, c)
+    mask = np.empty((x.size + 7) // 8, np.uint8)
+    lib.granq_oracle_gate_mask(_p(x), _dtype_code(x), n, c, hw, _p(s), _p(z), int(bits), _p(mask))
+    return mask
+
+
+def bwd_from_mask(dy: np.ndarray, mask: np.ndarray, lib=None) -> np.ndarray:
+    """dx = dy where the gate bit is set, else 0."""
+    lib = lib or load()
+    if not dy.flags["C_CONTIGUOUS"] or mask.dtype != np.uint8 or mask.size < (dy.size + 7) // 8:
+        raise ValueError("dy must be contiguous and mask uint8 with ceil(size / 8) bytes")
+    dx = np.empty_like(dy)
+    lib.granq_oracle_bwd_from_mask(_p(dy), _p(np.ascontiguousarray(mask)), _dtype_code(dy), dy.size, _p(dx))
     return dx
 
 

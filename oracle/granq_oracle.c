@@ -204,6 +204,44 @@ void granq_oracle_fakequant_bwd(const void *x, const void *dy, int dtype,
 }
 
 /*
+ * The straight-through gate on its own, one bit per element: bit (i & 7) of byte
+ * (i >> 3) is 1 where 0 <= u <= 2^b - 1 for the element with flat index i (u the
+ * rounded, unclamped code of Eq. 1).  mask has (n*c*hw + 7) / 8 bytes; unused
+ * high bits of the last byte are 0.
+ */
+void granq_oracle_gate_mask(const void *x, int dtype, int64_t n, int64_t c, int64_t hw,
+                            const float *scale, const float *zero_point, int bits,
+                            uint8_t *mask)
+{
+    float qmax = code_max(bits);
+    int64_t total = n * c * hw;
+    for (int64_t b = 0; b < (total + 7) / 8; ++b)
+        mask[b] = 0;
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t ic = 0; ic < c; ++ic) {
+            for (int64_t k = 0; k < hw; ++k) {
+                int64_t i = (in * c + ic) * hw + k;
+                float u = raw_code(load_elem(x, i, dtype), scale[ic], zero_point[ic]);
+                if (u >= 0.0f && u <= qmax)
+                    mask[i >> 3] |= (uint8_t)(1u << (i & 7));
+            }
+        }
+    }
+}
+
+/* Backward from the gate bits: dx = dy where the bit is set, else 0. */
+void granq_oracle_bwd_from_mask(const void *dy, const uint8_t *mask, int dtype,
+                                int64_t total, void *dx)
+{
+    for (int64_t i = 0; i < total; ++i) {
+        float g = load_elem(dy, i, dtype);
+        if (!((mask[i >> 3] >> (i & 7)) & 1u))
+            g = 0.0f;
+        store_elem(dx, i, dtype, g);
+    }
+}
+
+/*
  * The two accumulation forms the paper contrasts, on a 1x1 weighted channel
  * sum with one weight per channel (fp32 storage only; accumulation in channel
  * order c = 0, 1, ...):

@@ -27,7 +27,8 @@ GRANQ_BF16 = 1
 
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
            "granq_range_reduce",
-           "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd")
+           "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
+           "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -71,6 +72,9 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_prescale.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_fwd.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_bwd.argtypes = [_vp, _vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp]
+    lib.granq_mask_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.granq_fakequant_fwd_mask.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
+    lib.granq_fakequant_bwd_mask.argtypes = [_vp, _vp, dp, _vp, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
                                                ctypes.c_size_t, _vp]
     lib.granq_cmp_accumulate_inloop.argtypes = [_vp, dp, _vp, _vp, _vp, _vp, _vp]
@@ -201,6 +205,37 @@ def granq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, scale: torch.Tensor,
                                       _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"),
                                       int(bits), _dev(dx, "dx"), _stream(stream)),
            "granq_fakequant_bwd")
+
+
+def granq_mask_bytes(desc: granq_desc_t) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().granq_mask_bytes(ctypes.byref(desc), ctypes.byref(out)), "granq_mask_bytes")
+    return int(out.value)
+
+
+def granq_fakequant_fwd_mask(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
+                             x_hat: torch.Tensor, mask: torch.Tensor, stream=None,
+                             desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    if x_hat.dtype != x.dtype or x_hat.numel() != x.numel():
+        raise ValueError("x_hat must match x")
+    if mask.dtype != torch.uint8 or mask.numel() < (x.numel() + 7) // 8:
+        raise ValueError("mask must be uint8 with at least ceil(numel / 8) entries")
+    _check(load().granq_fakequant_fwd_mask(_dev(x, "x"), ctypes.byref(d), _vec(scale, d.c, "scale"),
+                                           _vec(zero_point, d.c, "zero_point"), int(bits),
+                                           _dev(x_hat, "x_hat"), _dev(mask, "mask"), _stream(stream)),
+           "granq_fakequant_fwd_mask")
+
+
+def granq_fakequant_bwd_mask(dy: torch.Tensor, mask: torch.Tensor, dx: torch.Tensor, stream=None,
+                             desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(dy)
+    if dx.dtype != dy.dtype or dx.numel() != dy.numel():
+        raise ValueError("dx must match dy")
+    if mask.dtype != torch.uint8 or mask.numel() < (dy.numel() + 7) // 8:
+        raise ValueError("mask must be uint8 with at least ceil(numel / 8) entries")
+    _check(load().granq_fakequant_bwd_mask(_dev(dy, "dy"), _dev(mask, "mask"), ctypes.byref(d),
+                                           _dev(dx, "dx"), _stream(stream)), "granq_fakequant_bwd_mask")
 
 
 # --- comparison points for the benchmark (include/granq_compare.h) ---------------------------

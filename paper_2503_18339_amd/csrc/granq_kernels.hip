@@ -200,11 +200,18 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
     return fast;
 }
 
-template <typename T, int V, int U, int MODE, bool CODES, bool FAST, bool NT>
+// What the forward writes besides x_hat.
+constexpr int kNoExtra = 0;   // nothing
+constexpr int kCodes = 1;     // one byte per element: the clamped code q
+constexpr int kMask = 2;      // one bit per element: 1 where the clamp was inactive (the
+                              // straight-through gate), bit (i & 7) of byte (i >> 3), i the
+                              // flat NCHW index
+
+template <typename T, int V, int U, int MODE, int EXTRA, bool FAST, bool NT>
 __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
-                                typename T::vec_t *__restrict__ x_hat,
-                                typename T::code_t *__restrict__ codes, float qmax, int64_t row_vecs,
-                                int64_t r, int nrows, const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
+                                typename T::vec_t *__restrict__ x_hat, void *__restrict__ extra,
+                                float qmax, int64_t row_vecs, int64_t r, int nrows,
+                                const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
                                 const uint32_t (&split)[V], const uint32_t (&cv)[V],
                                 const bool (&active)[V]) {
     constexpr int VEC = T::VEC;
@@ -217,26 +224,45 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int v = 0; v < V; ++v)
+        for (int v = 0; v < V; ++v) {
+            uint32_t gate_bits = 0;                    // bit e: element e passes the gate
             if (u < nrows && active[v]) {
                 float f[VEC], q[VEC];
                 T::unpack(in[u][v], f);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
                     const ChanRegs c = pick_chan<MODE>(cr[v], e, split[v]);
-                    q[e] = clamp_code(code_of<FAST>(f[e], c), qmax);
+                    const float code = code_of<FAST>(f[e], c);
+                    q[e] = clamp_code(code, qmax);
+                    // the clamp left the code alone <=> 0 <= code <= qmax (-0 == +0; NaN fails)
+                    if (EXTRA == kMask) gate_bits |= (code == q[e] ? 1u : 0u) << e;
                     f[e] = dequant(q[e], c.s, c.z);
                 }
                 const int64_t at = (r + u) * row_vecs + cv[v];
                 store_vec(x_hat + at, T::pack(f));
-                if (CODES) store_vec(codes + at, T::pack_codes(q));
+                if (EXTRA == kCodes) store_vec((typename T::code_t *)extra + at, T::pack_codes(q));
             }
+            if (EXTRA == kMask && u < nrows) {         // wave-uniform condition: all lanes take part
+                // byte index of this lane's vector; VEC == 8: one byte per lane, VEC == 4: two
+                // neighbouring lanes share a byte (the row length is a multiple of 8 on this path,
+                // so a pair is active or inactive together and starts on a byte boundary)
+                const int64_t byte_at = ((r + u) * row_vecs + cv[v]) * VEC / 8;
+                uint8_t *mask = (uint8_t *)extra;
+                if (VEC == 8) {
+                    if (active[v]) mask[byte_at] = (uint8_t)gate_bits;
+                } else {
+                    const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(
+                        0, (int)gate_bits, kDppQuadSwap1, 0xF, 0xF, false);   // lane ^ 1
+                    if (active[v] && (threadIdx.x & 1u) == 0) mask[byte_at] = (uint8_t)(gate_bits | (other << 4));
+                }
+            }
+        }
 }
 
-template <typename T, int V, int U, int MODE, bool CODES>
+template <typename T, int V, int U, int MODE, int EXTRA>
 __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const typename T::vec_t *__restrict__ x, typename T::vec_t *__restrict__ x_hat,
-    typename T::code_t *__restrict__ codes, const float *__restrict__ scale,
+    void *__restrict__ extra, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
     constexpr int NS = Slots<MODE, T::VEC>::N;
@@ -247,7 +273,8 @@ __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     ChanRegs cr[V][NS];
     uint32_t split[V], cv[V];
     bool active[V];
-    const bool fast = lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active);
+    // wave-uniform: if any lane's channel needs the general division, the whole wavefront takes it
+    const bool fast = __all(lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active));
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
@@ -255,17 +282,17 @@ __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const bool nt = r0 < plan.nt_row_end;              // block-uniform
     if (!fast) {
         for (; r < r1; ++r)
-            fwd_rows<T, V, 1, MODE, CODES, false, false>(x, x_hat, codes, qmax, row_vecs, r, 1, cr, split, cv, active);
+            fwd_rows<T, V, 1, MODE, EXTRA, false, false>(x, x_hat, extra, qmax, row_vecs, r, 1, cr, split, cv, active);
     } else if (nt) {
         for (; r + U <= r1; r += U)
-            fwd_rows<T, V, U, MODE, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, U, cr, split, cv, active);
+            fwd_rows<T, V, U, MODE, EXTRA, true, true>(x, x_hat, extra, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
-            fwd_rows<T, V, U, MODE, CODES, true, true>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
+            fwd_rows<T, V, U, MODE, EXTRA, true, true>(x, x_hat, extra, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
     } else {
         for (; r + U <= r1; r += U)
-            fwd_rows<T, V, U, MODE, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, U, cr, split, cv, active);
+            fwd_rows<T, V, U, MODE, EXTRA, true, false>(x, x_hat, extra, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
-            fwd_rows<T, V, U, MODE, CODES, true, false>(x, x_hat, codes, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
+            fwd_rows<T, V, U, MODE, EXTRA, true, false>(x, x_hat, extra, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
     }
 }
 
@@ -316,7 +343,8 @@ __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
     ChanRegs cr[V][NS];
     uint32_t split[V], cv[V];
     bool active[V];
-    const bool fast = lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active);
+    // wave-uniform: if any lane's channel needs the general division, the whole wavefront takes it
+    const bool fast = __all(lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active));
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
@@ -335,6 +363,77 @@ __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
             bwd_rows<T, V, U, MODE, true, false>(x, dy, dx, qmax, row_vecs, r, U, cr, split, cv, active);
         if (r < r1)
             bwd_rows<T, V, U, MODE, true, false>(x, dy, dx, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
+    }
+}
+
+// Backward from the forward's gate bits: dx = dy where the bit is set, else 0.
+// Reads dy and one bit per element instead of x and dy.
+template <typename T, int U, bool NT>
+__global__ __launch_bounds__(kEBlock) void fq_bwd_mask_cols(
+    const typename T::vec_t *__restrict__ dy, const uint8_t *__restrict__ mask,
+    typename T::vec_t *__restrict__ dx, ColPlan plan)
+{
+    constexpr int VEC = T::VEC;
+    const int64_t row_vecs = plan.row_len / VEC;
+    const uint32_t col = blockIdx.x * (uint32_t)plan.span + threadIdx.x * VEC;
+    if (col >= (uint32_t)plan.row_len) return;
+    const uint32_t cv = col / VEC;
+    const int64_t r0 = (int64_t)blockIdx.y * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
+    for (int64_t r = r0; r < r1; r += U) {
+        typename T::vec_t g[U];
+        uint32_t bits[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (r + u < r1) {
+                const int64_t at = (r + u) * row_vecs + cv;
+                g[u] = load_vec<NT>(dy + at);
+                bits[u] = mask[at * VEC / 8];
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (r + u < r1) {
+                const uint32_t b = VEC == 8 ? bits[u] : (bits[u] >> (4 * (threadIdx.x & 1u)));
+                bool keep[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) keep[e] = (b >> e) & 1u;
+                store_vec(dx + (r + u) * row_vecs + cv, T::gate(g[u], keep));
+            }
+    }
+}
+
+// Any shape: one thread per mask byte (eight consecutive elements).
+template <typename T>
+__global__ __launch_bounds__(kBlock) void mask_from_x_bytes(
+    const void *__restrict__ x, const float *__restrict__ scale, const float *__restrict__ zero_point,
+    float qmax, int64_t c, int64_t hw, int64_t total, uint8_t *__restrict__ mask)
+{
+    const int64_t nbytes = (total + 7) / 8;
+    for (int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x; b < nbytes; b += (int64_t)gridDim.x * kBlock) {
+        uint32_t bits = 0;
+        for (int k = 0; k < 8; ++k) {
+            const int64_t i = b * 8 + k;
+            if (i < total) {
+                const int64_t ic = (i / hw) % c;
+                const float u = raw_code(T::load1(x, i), scale[ic], zero_point[ic]);
+                bits |= (in_range(u, qmax) ? 1u : 0u) << k;
+            }
+        }
+        mask[b] = (uint8_t)bits;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void bwd_mask_bytes(
+    const void *__restrict__ dy, const uint8_t *__restrict__ mask, int64_t total, void *__restrict__ dx)
+{
+    const int64_t nbytes = (total + 7) / 8;
+    for (int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x; b < nbytes; b += (int64_t)gridDim.x * kBlock) {
+        const uint32_t bits = mask[b];
+        for (int k = 0; k < 8; ++k) {
+            const int64_t i = b * 8 + k;
+            if (i < total) T::store_gated1(dx, dy, i, (bits >> k) & 1u);
+        }
     }
 }
 
@@ -703,24 +802,24 @@ static uint32_t row_grid(int64_t slabs) {
 }
 
 template <typename T, int V, int MODE>
-static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, uint8_t *codes,
+static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, void *extra, int kind,
                             const float *s, const float *z, float qmax, hipStream_t st) {
     using vec_t = typename T::vec_t;
-    using code_t = typename T::code_t;
     dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
-    auto cv = (code_t *)codes;
-    if (codes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, true>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
-    else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, false>), grid, block, 0, st, xv, yv, cv, s, z, qmax, pl);
+    if (kind == kCodes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else if (kind == kMask) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kMask>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
 }
 
+// kind: kNoExtra, kCodes (extra = codes) or kMask (extra = gate bits)
 template <typename T, int V>
-static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, uint8_t *codes,
+static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, void *extra, int kind,
                             const float *s, const float *z, float qmax, hipStream_t st) {
-    if (pl.mode == kOne) launch_fwd_mode<T, V, kOne>(pl, x, x_hat, codes, s, z, qmax, st);
-    else if (pl.mode == kTwo) launch_fwd_mode<T, V, kTwo>(pl, x, x_hat, codes, s, z, qmax, st);
-    else launch_fwd_mode<T, V, kEach>(pl, x, x_hat, codes, s, z, qmax, st);
+    if (pl.mode == kOne) launch_fwd_mode<T, V, kOne>(pl, x, x_hat, extra, kind, s, z, qmax, st);
+    else if (pl.mode == kTwo) launch_fwd_mode<T, V, kTwo>(pl, x, x_hat, extra, kind, s, z, qmax, st);
+    else launch_fwd_mode<T, V, kEach>(pl, x, x_hat, extra, kind, s, z, qmax, st);
 }
 
 template <typename T, int V>
@@ -887,8 +986,8 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
     // packed codes are stored VEC bytes at a time
     const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
     if (cp.ok && aligned16(x) && aligned16(x_hat) && codes_ok) {
-        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
-        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, scale, zero_point, qmax, hs);
+        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, codes_or_null ? kCodes : kNoExtra, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, codes_or_null ? kCodes : kNoExtra, scale, zero_point, qmax, hs);
         return launched();
     }
     const int64_t hw = desc->h * desc->w;
@@ -926,6 +1025,80 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
         hipLaunchKernelGGL(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
     else
         hipLaunchKernelGGL(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+    return launched();
+}
+
+// The vectorised mask kernels need whole bytes per lane pair: rows that are a multiple of
+// eight elements (and, as everywhere, 16-byte vectors).
+static bool mask_vector_ok(const ColPlan &cp) {
+    return cp.ok && cp.row_len % 8 == 0 && GRANQ_E_V_F32 == 1 && GRANQ_E_V_BF16 == 1;
+}
+
+granq_status_t granq_mask_bytes(const granq_desc_t *desc, size_t *bytes_out) {
+    if (!bytes_out) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    *bytes_out = (size_t)((desc->n * desc->c * desc->h * desc->w + 7) / 8);
+    return GRANQ_OK;
+}
+
+granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc, const float *scale,
+                                        const float *zero_point, int bits, void *x_hat,
+                                        uint8_t *mask, void *stream) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!x || !x_hat || !scale || !zero_point || !mask) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(x, desc->dtype) || !aligned_elem(x_hat, desc->dtype) ||
+        !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
+        return GRANQ_ERR_UNSUPPORTED;
+    const float qmax = (float)((1 << bits) - 1);
+    hipStream_t hs = (hipStream_t)stream;
+    ColPlan cp = fwd_plan(desc);
+    if (mask_vector_ok(cp) && aligned16(x) && aligned16(x_hat)) {
+        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, mask, kMask, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, mask, kMask, scale, zero_point, qmax, hs);
+        return launched();
+    }
+    // any other shape or alignment: gate bits from x first (x_hat may alias x), then the forward
+    const int64_t hw = desc->h * desc->w;
+    const int64_t total = desc->n * desc->c * hw;
+    const int64_t want = ceil_div(ceil_div(total, 8), kBlock);
+    dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
+    if (desc->dtype == GRANQ_F32)
+        hipLaunchKernelGGL(mask_from_x_bytes<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
+    else
+        hipLaunchKernelGGL(mask_from_x_bytes<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
+    st = launched();
+    if (st != GRANQ_OK) return st;
+    return granq_fakequant_fwd(x, desc, scale, zero_point, bits, x_hat, nullptr, stream);
+}
+
+granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask, const granq_desc_t *desc,
+                                        void *dx, void *stream) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!dy || !mask || !dx) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(dy, desc->dtype) || !aligned_elem(dx, desc->dtype)) return GRANQ_ERR_UNSUPPORTED;
+    hipStream_t hs = (hipStream_t)stream;
+    ColPlan cp = bwd_plan(desc);
+    if (mask_vector_ok(cp) && aligned16(dy) && aligned16(dx)) {
+        dim3 grid((uint32_t)cp.col_tiles, (uint32_t)cp.row_groups), block(kEBlock);
+        const bool nt = cp.nt_row_end > 0;
+        if (desc->dtype == GRANQ_F32) {
+            if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
+            else hipLaunchKernelGGL((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
+        } else {
+            if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<BF16, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const BF16::vec_t *)dy, mask, (BF16::vec_t *)dx, cp);
+            else hipLaunchKernelGGL((fq_bwd_mask_cols<BF16, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const BF16::vec_t *)dy, mask, (BF16::vec_t *)dx, cp);
+        }
+        return launched();
+    }
+    const int64_t total = desc->n * desc->c * desc->h * desc->w;
+    const int64_t want = ceil_div(ceil_div(total, 8), kBlock);
+    dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
+    if (desc->dtype == GRANQ_F32) hipLaunchKernelGGL(bwd_mask_bytes<F32>, grid, block, 0, hs, dy, mask, total, dx);
+    else hipLaunchKernelGGL(bwd_mask_bytes<BF16>, grid, block, 0, hs, dy, mask, total, dx);
     return launched();
 }
 

@@ -65,6 +65,11 @@ def check_golden(lib=None):
         dy = to_storage(dyv, dt).reshape(cs["shape"])
         dx = oracle.fakequant_bwd(x, dy, s, z, bits, lib)
         _eq(from_storage(dx).ravel(), (dyv * cs["mask"]).astype(np.float32), name + ": dx")
+        # the packed gate bits: numpy's little-endian bit packing of the fixture's mask row
+        packed = oracle.gate_mask(x, s, z, bits, lib)
+        _eq(packed, np.packbits(cs["mask"].astype(np.uint8), bitorder="little"), name + ": packed gate bits")
+        _eq(from_storage(oracle.bwd_from_mask(dy, packed, lib)).ravel(),
+            (dyv * cs["mask"]).astype(np.float32), name + ": dx from gate bits")
 
 
 # ---------------------------------------------------------------------------
@@ -336,11 +341,15 @@ def check_invariants(lib=None):
             _eq(codes_k, codes, "pow2 codes")
             _eq(xh_k, xhat * np.float32(2.0 ** k), "pow2 xhat")
             _eq(z_k, z, "pow2 zero-point")
+        # the packed gate bits are the same gate (numpy's bit packing as the reference layout)
+        packed = oracle.gate_mask(x, s, z, bits, lib)
+        _eq(packed, np.packbits((mask.ravel() != 0).astype(np.uint8), bitorder="little"), "packed gate bits")
         # (j) backward returns dy or 0, bitwise
         dyr = rng.standard_normal(shape).astype(np.float32)
         dx = oracle.fakequant_bwd(x, dyr, s, z, bits, lib)
         assert np.all((dx == dyr) | (dx == 0))
         _eq(dx, dyr * mask, "dx == dy * mask")
+        _eq(oracle.bwd_from_mask(dyr, packed, lib), dx, "backward from gate bits == backward from x")
         # every code value is used somewhere on these wide tensors, in every channel with spread
         assert len(np.unique(codes)) == qmax + 1
 

@@ -16,7 +16,7 @@ MUTANTS = [
     ("round_truncates", "return rintf(v);", "return truncf(v);", 1),
     ("dequant_drops_zero_point", "float d = q - z;", "float d = q;", 1),
     ("dequant_adds_zero_point", "float d = q - z;", "float d = q + z;", 1),
-    ("batch_and_channel_transposed", "(in * c + ic) * hw + k", "(ic * n + in) * hw + k", 5),
+    ("batch_and_channel_transposed", "(in * c + ic) * hw + k", "(ic * n + in) * hw + k", 6),
     ("range_over_first_sample_only",
      "float mx = -INFINITY;\n        for (int64_t in = 0; in < n; ++in) {",
      "float mx = -INFINITY;\n        for (int64_t in = 0; in < 1; ++in) {", 1),
@@ -27,7 +27,7 @@ MUTANTS = [
     ("levels_off_by_one", "(float)((1 << bits) - 1)", "(float)(1 << bits)", 1),
     ("no_clamp", "float q = fminf(fmaxf(u, 0.0f), qmax);", "float q = u;", 1),
     ("clamp_low_side_missing", "float q = fminf(fmaxf(u, 0.0f), qmax);", "float q = fminf(u, qmax);", 1),
-    ("mask_strict", "u >= 0.0f && u <= qmax", "u > 0.0f && u < qmax", 1),
+    ("mask_strict", "if (!(u >= 0.0f && u <= qmax))", "if (!(u > 0.0f && u < qmax))", 1),
     ("mask_on_clamped_code_always_true", "if (!(u >= 0.0f && u <= qmax))", "if (0)", 1),
     ("mask_inverted", "if (!(u >= 0.0f && u <= qmax))", "if ((u >= 0.0f && u <= qmax))", 1),
     ("degenerate_scale_not_replaced", "s = 1.0f;", "s = FLT_MIN;", 1),
@@ -39,6 +39,9 @@ MUTANTS = [
      "double t = (double)x / s;\n    double v = t + z;\n    return (float)rint(v);", 1),
     ("fused_multiply_add", "float t = x / s;\n    float v = t + z;",
      "float v = fmaf(x, 1.0f / s, z);", 1),
+    ("gate_bits_msb_first", "mask[i >> 3] |= (uint8_t)(1u << (i & 7));", "mask[i >> 3] |= (uint8_t)(0x80u >> (i & 7));", 1),
+    ("gate_bits_strict", "if (u >= 0.0f && u <= qmax)\n                    mask[i >> 3]", "if (u > 0.0f && u < qmax)\n                    mask[i >> 3]", 1),
+    ("bwd_from_mask_inverted", "if (!((mask[i >> 3] >> (i & 7)) & 1u))", "if (((mask[i >> 3] >> (i & 7)) & 1u))", 1),
     ("bf16_ties_round_up", "(dropped == 0x8000u && (kept & 1u))", "(dropped == 0x8000u)", 1),
     ("bf16_truncates", "if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))", "if (0)", 1),
     ("inloop_drops_scale", "float ws = weight[ic] * scale[ic];", "float ws = weight[ic];", 1),
