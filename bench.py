@@ -267,6 +267,31 @@ def gate_bit_variant(wl, dtype, bits, device, steps, warmup):
             "note": "same results as the four-call step; %.3f instead of %d bytes per element" % (5 * e + 0.25, 6 * e)}
 
 
+def weight_quantization(bits, device):
+    """Channel-wise weight fake-quant of all ResNet-18 weights (Sec. 5.1): one multi-tensor
+    launch against the four-call path applied tensor by tensor on the {1,O,1,I*kh*kw} view."""
+    shapes = workloads.resnet18_weight_shapes()
+    ws = [workloads.make_weight(s, i, device) for i, s in enumerate(shapes)]
+    outs = [torch.empty_like(w) for w in ws]
+    sc = [torch.empty(s[0], device=device) for s in shapes]
+    zp = [torch.empty(s[0], device=device) for s in shapes]
+    items = G.rowwise_items(ws, outs, sc, zp)
+    stream = torch.cuda.current_stream()
+    qs = [G.ActivationQuantizer((1, s[0], 1, w.numel() // s[0]), torch.float32, bits, device)
+          for s, w in zip(shapes, ws)]
+
+    def four_call():
+        for q, w, o in zip(qs, ws, outs):
+            q.forward(w, o, stream=stream)
+
+    t_multi = _timeit(lambda: G.granq_rowwise_fakequant_multi(items, torch.float32, bits, stream))
+    t_four = _timeit(four_call)
+    params = sum(w.numel() for w in ws)
+    return {"tensors": len(ws), "parameters": params, "multi_tensor_launch_us": round(t_multi, 2),
+            "multi_GBs": round(params * 8 / t_multi / 1e3, 1),
+            "four_call_per_tensor_us": round(t_four, 2)}
+
+
 def cpu_baseline(wl, bits, sample_batch, min_seconds=10.0, max_passes=8):
     """The CPU oracle, as it stands, single thread, on the same tensors at batch
     `sample_batch` (float32): whole passes (range_reduce+prescale+fwd+bwd) are
@@ -394,6 +419,7 @@ def main():
             torch.cuda.empty_cache()
         extra["other_dtypes_bits"] = others
         extra["comparison_points"] = comparison_points(wl, args.bits, device)
+        extra["resnet18_weights_channelwise"] = weight_quantization(args.bits, device)
         extra["gate_bit_variant"] = gate_bit_variant(wl, dtype, args.bits, device, args.steps, args.warmup)
         extra["gate_bit_variant"]["speedup_vs_x_based_step"] = round(
             ms_per_step / extra["gate_bit_variant"]["ms_per_step"], 3)

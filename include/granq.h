@@ -178,6 +178,52 @@ granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc,
 granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask,
                                         const granq_desc_t *desc, void *dx, void *stream);
 
+/*
+ * Row-wise fake-quantization of many small matrices in one launch -- the paper's
+ * channel-wise quantization "for all weights" (Sec. 5.1): an OIHW weight tensor is
+ * a matrix of O rows (output channels) by I*kh*kw columns, each row gets its own
+ * range, scale and zero-point (Eq. 2) and is quantized and dequantized (Eq. 1, 6).
+ * Weight tensors are small, so one block handles one row start to finish (min/max,
+ * scale and zero-point, quantize; the second sweep over the row hits the cache)
+ * and all tensors of a network share one launch.  Results are identical to
+ * granq_range_reduce + granq_prescale + granq_fakequant_fwd on the view
+ * {1, rows, 1, row_len} of each item.
+ *
+ * items: HOST array of `count` descriptors; every pointer inside is a device pointer.
+ *   w [in] rows*row_len elements of `dtype`;  w_hat [out] same (may alias w);
+ *   scale, zero_point [out] rows floats each.
+ * The descriptors are passed to the kernel by value, up to 32 per launch.
+ */
+typedef struct {
+    const void *w;
+    void *w_hat;
+    float *scale;
+    float *zero_point;
+    int64_t rows;
+    int64_t row_len;
+} granq_rowq_item_t;
+
+granq_status_t granq_rowwise_fakequant_multi(const granq_rowq_item_t *items, int count,
+                                             granq_dtype_t dtype, int bits, void *stream);
+
+/*
+ * Straight-through backward for the same items: dw = dy where 0 <= u <= 2^bits - 1,
+ * else 0, with the scale / zero-point the forward stored.
+ *   w, dy [in];  dw [out] (may alias dy);  scale, zero_point [in] rows floats each.
+ */
+typedef struct {
+    const void *w;
+    const void *dy;
+    void *dw;
+    const float *scale;
+    const float *zero_point;
+    int64_t rows;
+    int64_t row_len;
+} granq_rowq_bwd_item_t;
+
+granq_status_t granq_rowwise_fakequant_bwd_multi(const granq_rowq_bwd_item_t *items, int count,
+                                                 granq_dtype_t dtype, int bits, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,8 @@ GRANQ_BF16 = 1
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
            "granq_range_reduce",
            "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
-           "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask")
+           "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
+           "granq_rowwise_fakequant_bwd_multi")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -36,6 +37,17 @@ COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
 class granq_desc_t(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int64), ("c", ctypes.c_int64), ("h", ctypes.c_int64),
                 ("w", ctypes.c_int64), ("dtype", ctypes.c_int)]
+
+
+class granq_rowq_item_t(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("w_hat", ctypes.c_void_p), ("scale", ctypes.c_void_p),
+                ("zero_point", ctypes.c_void_p), ("rows", ctypes.c_int64), ("row_len", ctypes.c_int64)]
+
+
+class granq_rowq_bwd_item_t(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("dy", ctypes.c_void_p), ("dw", ctypes.c_void_p),
+                ("scale", ctypes.c_void_p), ("zero_point", ctypes.c_void_p),
+                ("rows", ctypes.c_int64), ("row_len", ctypes.c_int64)]
 
 
 class GranqError(RuntimeError):
@@ -75,6 +87,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_mask_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_fakequant_fwd_mask.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_bwd_mask.argtypes = [_vp, _vp, dp, _vp, _vp]
+    lib.granq_rowwise_fakequant_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
+    lib.granq_rowwise_fakequant_bwd_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
                                                ctypes.c_size_t, _vp]
     lib.granq_cmp_accumulate_inloop.argtypes = [_vp, dp, _vp, _vp, _vp, _vp, _vp]
@@ -236,6 +250,47 @@ def granq_fakequant_bwd_mask(dy: torch.Tensor, mask: torch.Tensor, dx: torch.Ten
         raise ValueError("mask must be uint8 with at least ceil(numel / 8) entries")
     _check(load().granq_fakequant_bwd_mask(_dev(dy, "dy"), _dev(mask, "mask"), ctypes.byref(d),
                                            _dev(dx, "dx"), _stream(stream)), "granq_fakequant_bwd_mask")
+
+
+def _rows_of(t: torch.Tensor):
+    if t.dim() < 2:
+        raise ValueError("a weight needs at least (rows, ...) dimensions")
+    return int(t.shape[0]), t.numel() // int(t.shape[0])
+
+
+def rowwise_items(weights, outs, scales, zero_points):
+    """Marshal lists of tensors into the host descriptor array (keep it to reuse it)."""
+    n = len(weights)
+    arr = (granq_rowq_item_t * n)()
+    for i, (w, o, s, z) in enumerate(zip(weights, outs, scales, zero_points)):
+        rows, row_len = _rows_of(w)
+        if o.dtype != w.dtype or o.numel() != w.numel():
+            raise ValueError("w_hat must match w")
+        arr[i] = granq_rowq_item_t(_dev(w, "w"), _dev(o, "w_hat"), _vec(s, rows, "scale"),
+                                   _vec(z, rows, "zero_point"), rows, row_len)
+    return arr
+
+
+def granq_rowwise_fakequant_multi(items, dtype: torch.dtype, bits: int, stream=None) -> None:
+    code = GRANQ_F32 if dtype == torch.float32 else GRANQ_BF16
+    _check(load().granq_rowwise_fakequant_multi(ctypes.cast(items, _vp), len(items), code, int(bits),
+                                                _stream(stream)), "granq_rowwise_fakequant_multi")
+
+
+def rowwise_bwd_items(weights, dys, dws, scales, zero_points):
+    n = len(weights)
+    arr = (granq_rowq_bwd_item_t * n)()
+    for i, (w, g, o, s, z) in enumerate(zip(weights, dys, dws, scales, zero_points)):
+        rows, row_len = _rows_of(w)
+        arr[i] = granq_rowq_bwd_item_t(_dev(w, "w"), _dev(g, "dy"), _dev(o, "dw"), _vec(s, rows, "scale"),
+                                       _vec(z, rows, "zero_point"), rows, row_len)
+    return arr
+
+
+def granq_rowwise_fakequant_bwd_multi(items, dtype: torch.dtype, bits: int, stream=None) -> None:
+    code = GRANQ_F32 if dtype == torch.float32 else GRANQ_BF16
+    _check(load().granq_rowwise_fakequant_bwd_multi(ctypes.cast(items, _vp), len(items), code, int(bits),
+                                                    _stream(stream)), "granq_rowwise_fakequant_bwd_multi")
 
 
 # --- comparison points for the benchmark (include/granq_compare.h) ---------------------------

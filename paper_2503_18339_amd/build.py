@@ -10,7 +10,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libgranq.so")
-SOURCES = [os.path.join(CSRC, "granq_kernels.hip"), os.path.join(CSRC, "granq_compare.hip")]
+SOURCES = [os.path.join(CSRC, "granq_kernels.hip"), os.path.join(CSRC, "granq_compare.hip"),
+           os.path.join(CSRC, "granq_rowwise.hip")]
 HEADERS = [os.path.join(CSRC, "granq_device.h"), os.path.join(CSRC, "granq_plan.h"),
            os.path.join(CSRC, "granq_quotient.h"), os.path.join(INCLUDE, "granq.h"),
            os.path.join(INCLUDE, "granq_compare.h")]

@@ -200,6 +200,17 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
     return fast;
 }
 
+#ifndef GRANQ_MASK_NT
+#define GRANQ_MASK_NT 0
+#endif
+__device__ inline void store_mask_byte(uint8_t *p, uint8_t v) {
+#if GRANQ_MASK_NT
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
 // What the forward writes besides x_hat.
 constexpr int kNoExtra = 0;   // nothing
 constexpr int kCodes = 1;     // one byte per element: the clamped code q
@@ -249,11 +260,11 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
                 const int64_t byte_at = ((r + u) * row_vecs + cv[v]) * VEC / 8;
                 uint8_t *mask = (uint8_t *)extra;
                 if (VEC == 8) {
-                    if (active[v]) mask[byte_at] = (uint8_t)gate_bits;
+                    if (active[v]) store_mask_byte(mask + byte_at, (uint8_t)gate_bits);
                 } else {
                     const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(
                         0, (int)gate_bits, kDppQuadSwap1, 0xF, 0xF, false);   // lane ^ 1
-                    if (active[v] && (threadIdx.x & 1u) == 0) mask[byte_at] = (uint8_t)(gate_bits | (other << 4));
+                    if (active[v] && (threadIdx.x & 1u) == 0) store_mask_byte(mask + byte_at, (uint8_t)(gate_bits | (other << 4)));
                 }
             }
         }

@@ -32,9 +32,9 @@ COPY_KERNEL = "__amd_rocclr_copyBuffer"
 
 def source_hash() -> str:
     """Hash of everything that determines the quantizer kernels' code: sources, headers, flags
-    (the benchmark-only comparison kernels are left out)."""
+    (the comparison kernels and the row-wise weight kernels are left out)."""
     h = hashlib.sha256()
-    paths = [p for p in _build.SOURCES + _build.HEADERS if "compare" not in os.path.basename(p)]
+    paths = [p for p in _build.SOURCES + _build.HEADERS if "compare" not in os.path.basename(p) and "rowwise" not in os.path.basename(p)]
     for path in sorted(paths):
         with open(path, "rb") as fh:
             h.update(os.path.basename(path).encode())

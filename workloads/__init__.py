@@ -203,3 +203,35 @@ WORKLOADS = {
 
 def torch_dtype(name: str) -> torch.dtype:
     return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+# ---------------------------------------------------------------------------
+# weight tensors (channel-wise weight quantization, Sec. 5.1 of the paper)
+# ---------------------------------------------------------------------------
+
+def resnet18_weight_shapes():
+    """(O, I, kh, kw) of every convolution and the classifier of ResNet-18 (ImageNet)."""
+    shapes = [(64, 3, 7, 7)]
+    cfg = [(64, 64, 2), (64, 128, 2), (128, 256, 2), (256, 512, 2)]
+    for c_in, c_out, blocks in cfg:
+        for b in range(blocks):
+            first_in = c_in if b == 0 else c_out
+            shapes.append((c_out, first_in, 3, 3))
+            shapes.append((c_out, c_out, 3, 3))
+            if b == 0 and c_in != c_out:
+                shapes.append((c_out, c_in, 1, 1))      # downsample
+    shapes.append((1000, 512, 1, 1))                    # classifier as a 1x1 weight
+    return shapes
+
+
+def make_weight(shape, seed: int = 0, device="cpu", dtype=torch.float32) -> torch.Tensor:
+    """Normal(0, sqrt(2 / fan_in)) weights with a per-output-channel spread factor
+    log-uniform in [0.3, 3] (trained filters differ in norm)."""
+    o = int(shape[0])
+    fan_in = 1
+    for d in shape[1:]:
+        fan_in *= int(d)
+    g = _gen(seed + 104729, device)
+    w = torch.randn(tuple(shape), generator=g, device=device, dtype=torch.float32) * math.sqrt(2.0 / fan_in)
+    spread = channel_sigma(o, 0.3, 3.0, seed + 31, device).view([o] + [1] * (len(shape) - 1))
+    return (w * spread).to(dtype)
