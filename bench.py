@@ -292,6 +292,39 @@ def weight_quantization(bits, device):
             "four_call_per_tensor_us": round(t_four, 2)}
 
 
+def distortion_table(wl, device):
+    """The paper's Table 2 on the synthetic benchmark tensors (3-bit): average over the layers of
+    cosine similarity and relative error, one range per layer against one range per channel;
+    also the kernel time of the fused metric on the largest tensor."""
+    rows = {"layerwise": [], "channelwise": []}
+    stream = torch.cuda.current_stream()
+    t_big = None
+    for i, a in enumerate(wl.tensors()):
+        shape = a.shape(wl.batch)
+        x = workloads.make_activation(shape, a.law, wl.sigma, i, device)
+        for view in ("layer", "channel"):
+            q = G.ActivationQuantizer(shape, torch.float32, 3, device, view=view)
+            q.calibrate(x, stream)
+            ch = torch.empty(q.desc.c, 4, dtype=torch.float64, device=device)
+            layer = torch.empty(6, dtype=torch.float64, device=device)
+            ws = torch.empty(max(16, G.granq_distortion_workspace_bytes(q.desc)), dtype=torch.uint8, device=device)
+            fn = lambda: G.granq_distortion(x, q.scale, q.zero_point, 3, ch, layer, ws, stream, q.desc)
+            fn()
+            if i == 0 and view == "channel":
+                t_big = _timeit(fn, 5)
+            rows[view + "wise"].append(layer.cpu().tolist()[4:])
+        del x
+    avg = {k: [round(sum(r[j] for r in v) / len(v), 4) for j in (0, 1)] for k, v in rows.items()}
+    big = wl.tensors()[0].numel(wl.batch)
+    return {"avg_cosine_similarity": {k: v[0] for k, v in avg.items()},
+            "avg_relative_error": {k: v[1] for k, v in avg.items()},
+            "paper_table2_resnet20_cifar100_trained": {"avg_cosine_similarity": {"layerwise": 0.5111, "channelwise": 0.6835},
+                                                        "avg_relative_error": {"layerwise": 0.3129, "channelwise": 0.1063}},
+            "fused_metric_kernel_us_256x64x112x112": round(t_big, 1),
+            "fused_metric_GBs": round(big * 4 / t_big / 1e3, 1),
+            "note": "synthetic tensors, not the paper's trained network: only the direction is comparable"}
+
+
 def cpu_baseline(wl, bits, sample_batch, min_seconds=10.0, max_passes=8):
     """The CPU oracle, as it stands, single thread, on the same tensors at batch
     `sample_batch` (float32): whole passes (range_reduce+prescale+fwd+bwd) are
@@ -419,6 +452,7 @@ def main():
             torch.cuda.empty_cache()
         extra["other_dtypes_bits"] = others
         extra["comparison_points"] = comparison_points(wl, args.bits, device)
+        extra["distortion_3bit"] = distortion_table(wl, device)
         extra["resnet18_weights_channelwise"] = weight_quantization(args.bits, device)
         extra["gate_bit_variant"] = gate_bit_variant(wl, dtype, args.bits, device, args.steps, args.warmup)
         extra["gate_bit_variant"]["speedup_vs_x_based_step"] = round(

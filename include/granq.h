@@ -224,6 +224,27 @@ typedef struct {
 granq_status_t granq_rowwise_fakequant_bwd_multi(const granq_rowq_bwd_item_t *items, int count,
                                                  granq_dtype_t dtype, int bits, void *stream);
 
+/*
+ * Distortion of the fake-quantized tensor, the two figures of the paper's Table 2:
+ *     cosine similarity  X.Q / (|X| |Q|)      relative error  |X - Q| / |X|
+ * with Q = x_hat computed on the fly from x, scale, zero_point (x is read once,
+ * x_hat is never materialised).  Products and differences are formed and summed
+ * in binary64.
+ * ch_sums  [out] device, C*4 doubles: per channel  sum x*q, sum x^2, sum q^2, sum (x-q)^2
+ * layer    [out] device, 6 doubles: the four sums over all channels (added in
+ *                channel order), then cosine similarity and relative error of the
+ *                whole tensor (0/0 gives NaN)
+ * workspace [tmp] device, granq_distortion_workspace_bytes() bytes, 16-byte aligned
+ * Sums are deterministic (fixed reduction tree); they differ from a sequential
+ * sum by binary64 rounding only.
+ */
+granq_status_t granq_distortion_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out);
+
+granq_status_t granq_distortion(const void *x, const granq_desc_t *desc,
+                                const float *scale, const float *zero_point, int bits,
+                                double *ch_sums, double *layer,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

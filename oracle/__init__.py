@@ -64,9 +64,10 @@ def load(path: str | None = None) -> ctypes.CDLL:
                                                _int, _ptr]
     lib.granq_oracle_gate_mask.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr]
     lib.granq_oracle_bwd_from_mask.argtypes = [_ptr, _ptr, _int, _i64, _ptr]
+    lib.granq_oracle_distortion.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr, _ptr]
     lib.granq_oracle_accumulate_inloop.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_prescaled.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr]
-    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask",
+    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask", "distortion",
                  "accumulate_inloop", "accumulate_prescaled"):
         getattr(lib, "granq_oracle_" + name).restype = None
     if path is None:
@@ -174,6 +175,19 @@ def bwd_from_mask(dy: np.ndarray, mask: np.ndarray, lib=None) -> np.ndarray:
     dx = np.empty_like(dy)
     lib.granq_oracle_bwd_from_mask(_p(dy), _p(np.ascontiguousarray(mask)), _dtype_code(dy), dy.size, _p(dx))
     return dx
+
+
+def distortion(x: np.ndarray, scale, zero_point, bits: int, lib=None):
+    """Table 2's figures.  Returns (ch_sums[C,4], layer[6]): per-channel sums x.q, x.x, q.q,
+    (x-q).(x-q); layer = those sums over all channels, cosine similarity, relative error."""
+    lib = lib or load()
+    n, c, hw = _nchw(x)
+    s = _f32vec(scale, c)
+    z = _f32vec(zero_point, c)
+    ch = np.empty((c, 4), np.float64)
+    layer = np.empty(6, np.float64)
+    lib.granq_oracle_distortion(_p(x), _dtype_code(x), n, c, hw, _p(s), _p(z), int(bits), _p(ch), _p(layer))
+    return ch, layer
 
 
 def fakequant(x: np.ndarray, bits: int, lib=None):

@@ -143,6 +143,19 @@ static float raw_code(float x, float s, float z)
     return rintf(v);
 }
 
+/* Codes are kept inside b bits: clamp to [0, 2^b - 1] (this build's reading; not in Eq. 1). */
+static float clamp_code(float u, float qmax)
+{
+    return fminf(fmaxf(u, 0.0f), qmax);
+}
+
+/* Dequantization of Eq. 6 (Alg. 1, "dequantize & pre-scale"): s * (q - z). */
+static float dequantize(float q, float s, float z)
+{
+    float d = q - z;
+    return s * d;
+}
+
 /*
  * Quantize, clamp, dequantize (Eq. 1 then the dequantization of Eq. 6; Alg. 1,
  * the quantize and the "dequantize & pre-scale" steps):
@@ -164,11 +177,10 @@ void granq_oracle_fakequant_fwd(const void *x, int dtype,
             for (int64_t k = 0; k < hw; ++k) {
                 int64_t i = (in * c + ic) * hw + k;
                 float u = raw_code(load_elem(x, i, dtype), s, z);
-                float q = fminf(fmaxf(u, 0.0f), qmax);
+                float q = clamp_code(u, qmax);
                 if (codes)
                     codes[i] = (uint8_t)q;
-                float d = q - z;
-                store_elem(x_hat, i, dtype, s * d);
+                store_elem(x_hat, i, dtype, dequantize(q, s, z));
             }
         }
     }
@@ -239,6 +251,53 @@ void granq_oracle_bwd_from_mask(const void *dy, const uint8_t *mask, int dtype,
             g = 0.0f;
         store_elem(dx, i, dtype, g);
     }
+}
+
+/*
+ * Distortion of the fake-quantized tensor, the two figures of Table 2:
+ *     cosine similarity  X.Q / (|X|_2 |Q|_2)     relative error  |X - Q|_2 / |X|_2
+ * with Q = x_hat of the forward above.  Everything here is binary64: the
+ * binary32 values are widened exactly, products, differences and sums are
+ * doubles, summed in index order.
+ * ch_sums[c][4] = { sum x*q, sum x^2, sum q^2, sum (x-q)^2 } per channel;
+ * layer[0..3] = the same sums over all channels (added in channel order),
+ * layer[4] = cosine similarity, layer[5] = relative error of the whole tensor.
+ */
+void granq_oracle_distortion(const void *x, int dtype, int64_t n, int64_t c, int64_t hw,
+                             const float *scale, const float *zero_point, int bits,
+                             double *ch_sums, double *layer)
+{
+    float qmax = code_max(bits);
+    for (int64_t ic = 0; ic < c; ++ic) {
+        double xq = 0.0, xx = 0.0, qq = 0.0, dd = 0.0;
+        float s = scale[ic];
+        float z = zero_point[ic];
+        for (int64_t in = 0; in < n; ++in) {
+            for (int64_t k = 0; k < hw; ++k) {
+                float xf = load_elem(x, (in * c + ic) * hw + k, dtype);
+                float qf = dequantize(clamp_code(raw_code(xf, s, z), qmax), s, z);
+                double xd = (double)xf;
+                double qd = (double)qf;
+                double d = xd - qd;
+                xq = xq + xd * qd;
+                xx = xx + xd * xd;
+                qq = qq + qd * qd;
+                dd = dd + d * d;
+            }
+        }
+        ch_sums[ic * 4 + 0] = xq;
+        ch_sums[ic * 4 + 1] = xx;
+        ch_sums[ic * 4 + 2] = qq;
+        ch_sums[ic * 4 + 3] = dd;
+    }
+    for (int j = 0; j < 4; ++j) {
+        double t = 0.0;
+        for (int64_t ic = 0; ic < c; ++ic)
+            t = t + ch_sums[ic * 4 + j];
+        layer[j] = t;
+    }
+    layer[4] = layer[0] / (sqrt(layer[1]) * sqrt(layer[2]));
+    layer[5] = sqrt(layer[3]) / sqrt(layer[1]);
 }
 
 /*

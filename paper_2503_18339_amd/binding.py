@@ -29,7 +29,7 @@ EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "gra
            "granq_range_reduce",
            "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
-           "granq_rowwise_fakequant_bwd_multi")
+           "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -89,6 +89,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_fakequant_bwd_mask.argtypes = [_vp, _vp, dp, _vp, _vp]
     lib.granq_rowwise_fakequant_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
     lib.granq_rowwise_fakequant_bwd_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
+    lib.granq_distortion_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.granq_distortion.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
                                                ctypes.c_size_t, _vp]
     lib.granq_cmp_accumulate_inloop.argtypes = [_vp, dp, _vp, _vp, _vp, _vp, _vp]
@@ -291,6 +293,28 @@ def granq_rowwise_fakequant_bwd_multi(items, dtype: torch.dtype, bits: int, stre
     code = GRANQ_F32 if dtype == torch.float32 else GRANQ_BF16
     _check(load().granq_rowwise_fakequant_bwd_multi(ctypes.cast(items, _vp), len(items), code, int(bits),
                                                     _stream(stream)), "granq_rowwise_fakequant_bwd_multi")
+
+
+def granq_distortion_workspace_bytes(desc: granq_desc_t) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().granq_distortion_workspace_bytes(ctypes.byref(desc), ctypes.byref(out)),
+           "granq_distortion_workspace_bytes")
+    return int(out.value)
+
+
+def granq_distortion(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
+                     ch_sums: torch.Tensor, layer: torch.Tensor, workspace: torch.Tensor, stream=None,
+                     desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    if ch_sums.dtype != torch.float64 or ch_sums.numel() != 4 * d.c:
+        raise ValueError("ch_sums must be float64 with 4*C entries")
+    if layer.dtype != torch.float64 or layer.numel() != 6:
+        raise ValueError("layer must be float64 with 6 entries")
+    _check(load().granq_distortion(_dev(x, "x"), ctypes.byref(d), _vec(scale, d.c, "scale"),
+                                   _vec(zero_point, d.c, "zero_point"), int(bits), _dev(ch_sums, "ch_sums"),
+                                   _dev(layer, "layer"), _dev(workspace, "workspace"),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)),
+           "granq_distortion")
 
 
 # --- comparison points for the benchmark (include/granq_compare.h) ---------------------------

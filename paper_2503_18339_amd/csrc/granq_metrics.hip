@@ -1,0 +1,151 @@
+// Distortion metrics of the fake-quantized tensor (the paper's Table 2: cosine
+// similarity and relative error between the activation X and its quantized
+// version Q), fused with the quantizer: x is read once, Q = x_hat is recomputed
+// in registers, four binary64 sums per channel come out.
+//
+// Pass 1: block (channel c, row group p); each wavefront takes whole (n,c) slabs,
+// lanes stride over H*W; per-lane binary64 accumulators, wavefront tree by
+// shuffles, block tree through LDS, one partial per (p, c).  Pass 2: per channel
+// the partials are added in order of p; one thread then adds the channels in
+// order and forms the two ratios.  Every addition order is fixed.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "granq.h"
+#include "granq_device.h"
+#include "granq_plan.h"
+
+namespace granq {
+
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void distortion_pass1(
+    const void *__restrict__ x, const float *__restrict__ scale, const float *__restrict__ zero_point,
+    float qmax, int64_t n, int64_t c, int64_t hw, RowPlan plan, double *__restrict__ ws)
+{
+    __shared__ double part[4][kBlock / kWave];
+    const int64_t ic = blockIdx.x % c;
+    const int64_t p = blockIdx.x / c;
+    const int64_t r0 = p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < n) ? r0 + plan.rows_per_group : n;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const float s = scale[ic], z = zero_point[ic];
+    double xq = 0.0, xx = 0.0, qq = 0.0, dd = 0.0;
+    for (int64_t in = r0 + wave; in < r1; in += kBlock / kWave) {
+        const int64_t base = (in * c + ic) * hw;
+        for (int64_t k = lane; k < hw; k += kWave) {
+            const float xf = T::load1(x, base + k);
+            const float qf = dequant(clamp_code(raw_code(xf, s, z), qmax), s, z);
+            const double xd = (double)xf, qd = (double)qf, d = xd - qd;
+            xq += xd * qd;
+            xx += xd * xd;
+            qq += qd * qd;
+            dd += d * d;
+        }
+    }
+    xq = wave_sum(xq);
+    xx = wave_sum(xx);
+    qq = wave_sum(qq);
+    dd = wave_sum(dd);
+    if (lane == 0) {
+        part[0][wave] = xq;
+        part[1][wave] = xx;
+        part[2][wave] = qq;
+        part[3][wave] = dd;
+    }
+    __syncthreads();
+    if (threadIdx.x < 4) {
+        double t = part[threadIdx.x][0];
+        for (int w = 1; w < kBlock / kWave; ++w) t += part[threadIdx.x][w];
+        ws[(p * c + ic) * 4 + threadIdx.x] = t;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void distortion_pass2(
+    const double *__restrict__ ws, int64_t c, int32_t groups, double *__restrict__ ch_sums)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;     // (channel, which sum)
+    if (i >= c * 4) return;
+    double t = 0.0;
+    for (int32_t p = 0; p < groups; ++p) t += ws[(int64_t)p * c * 4 + i];
+    ch_sums[i] = t;
+}
+
+__global__ void distortion_layer(const double *__restrict__ ch_sums, int64_t c, double *__restrict__ layer)
+{
+    __shared__ double tot[4];
+    if (threadIdx.x < 4) {
+        double t = 0.0;
+        for (int64_t ic = 0; ic < c; ++ic) t += ch_sums[ic * 4 + threadIdx.x];
+        tot[threadIdx.x] = t;
+        layer[threadIdx.x] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        layer[4] = tot[0] / (sqrt(tot[1]) * sqrt(tot[2]));      // X.Q / (|X| |Q|)
+        layer[5] = sqrt(tot[3]) / sqrt(tot[1]);                 // |X - Q| / |X|
+    }
+}
+
+static granq_status_t metrics_check(const granq_desc_t *d) {
+    if (!d) return GRANQ_ERR_INVALID_ARG;
+    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0) return GRANQ_ERR_INVALID_ARG;
+    if (d->dtype != GRANQ_F32 && d->dtype != GRANQ_BF16) return GRANQ_ERR_UNSUPPORTED;
+    const int64_t lim = (int64_t)1 << 40;
+    if (d->n > lim || d->c >= ((int64_t)1 << 24) || d->h > lim || d->w > lim || d->h * d->w > lim) return GRANQ_ERR_UNSUPPORTED;
+    if ((__int128)d->n * d->c * (d->h * d->w) > ((__int128)1 << 46)) return GRANQ_ERR_UNSUPPORTED;
+    return GRANQ_OK;
+}
+
+}  // namespace granq
+
+using namespace granq;
+
+extern "C" {
+
+granq_status_t granq_distortion_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out) {
+    if (!bytes_out) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = metrics_check(desc);
+    if (st != GRANQ_OK) return st;
+    RowPlan rp = make_row_plan(desc->n, desc->c, desc->h * desc->w);
+    *bytes_out = (size_t)rp.row_groups * (size_t)desc->c * 4 * sizeof(double);
+    return GRANQ_OK;
+}
+
+granq_status_t granq_distortion(const void *x, const granq_desc_t *desc, const float *scale,
+                                const float *zero_point, int bits, double *ch_sums, double *layer,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    granq_status_t st = metrics_check(desc);
+    if (st != GRANQ_OK) return st;
+    if (!x || !scale || !zero_point || !ch_sums || !layer) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (((uintptr_t)x & (desc->dtype == GRANQ_F32 ? 3u : 1u)) || ((uintptr_t)scale & 3u) ||
+        ((uintptr_t)zero_point & 3u) || ((uintptr_t)ch_sums & 7u) || ((uintptr_t)layer & 7u))
+        return GRANQ_ERR_UNSUPPORTED;
+    size_t need = 0;
+    granq_distortion_workspace_bytes(desc, &need);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u)) return GRANQ_ERR_WORKSPACE;
+    hipStream_t hs = (hipStream_t)stream;
+    const int64_t hw = desc->h * desc->w;
+    const float qmax = (float)((1 << bits) - 1);
+    RowPlan rp = make_row_plan(desc->n, desc->c, hw);
+    double *ws = (double *)workspace;
+    dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
+    if (desc->dtype == GRANQ_F32)
+        hipLaunchKernelGGL(distortion_pass1<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
+    else
+        hipLaunchKernelGGL(distortion_pass1<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
+    if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
+    hipLaunchKernelGGL(distortion_pass2, dim3((uint32_t)ceil_div(desc->c * 4, kBlock)), block, 0, hs, ws, desc->c, rp.row_groups, ch_sums);
+    if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
+    hipLaunchKernelGGL(distortion_layer, dim3(1), dim3(kWave), 0, hs, ch_sums, desc->c, layer);
+    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+}
+
+}  // extern "C"

@@ -445,6 +445,48 @@ def check_accumulation_forms(lib=None):
     assert np.max(np.abs(y6 - ref)) <= 1e-5 * scale
 
 
+def check_distortion_metrics(lib=None):
+    """Table 2's cosine similarity and relative error against numpy's dot / norm on the
+    oracle's own x_hat, exact cases, and the direction of the table."""
+    x = _workload_tensor("linear", (4, 6, 9, 9), seed=12)
+    mn, mx = oracle.range_reduce(x, lib)
+    for bits in (3, 6):
+        s, z = oracle.prescale(mn, mx, bits, lib)
+        xh, _ = oracle.fakequant_fwd(x, s, z, bits, lib)
+        ch, layer = oracle.distortion(x, s, z, bits, lib)
+        xd, qd = x.astype(np.float64), xh.astype(np.float64)
+        for c in range(6):
+            a, b = xd[:, c].ravel(), qd[:, c].ravel()
+            want = np.array([a @ b, a @ a, b @ b, (a - b) @ (a - b)])
+            assert np.allclose(ch[c], want, rtol=1e-12, atol=0), (bits, c, ch[c], want)
+        assert np.allclose(layer[:4], ch.sum(axis=0), rtol=1e-13)
+        cos = (xd.ravel() @ qd.ravel()) / (np.linalg.norm(xd.ravel()) * np.linalg.norm(qd.ravel()))
+        rel = np.linalg.norm((xd - qd).ravel()) / np.linalg.norm(xd.ravel())
+        assert abs(layer[4] - cos) <= 1e-12 and abs(layer[5] - rel) <= 1e-12 * max(rel, 1e-30)
+        assert 0 < layer[5] < 1 and 0 < layer[4] <= 1
+    # exact: a tensor that is already on the grid has cosine 1 and error 0
+    g = np.arange(16, dtype=np.float32).reshape(1, 1, 4, 4)
+    ch, layer = oracle.distortion(g, np.ones(1, np.float32), np.zeros(1, np.float32), 4, lib)
+    assert layer[3] == 0.0 and layer[5] == 0.0 and layer[4] == 1.0
+    assert ch[0, 0] == ch[0, 1] == ch[0, 2] == float((np.arange(16.0) ** 2).sum())
+    # hand case: x = (1, 2.4) with s = 1, z = 0, b = 3 -> q = (1, 2): x.q = 5.8, x.x = 6.76,
+    # q.q = 5, |x-q|^2 = 0.16 (up to the binary32 representation of 2.4)
+    h = np.array([1.0, 2.4], np.float32).reshape(1, 1, 1, 2)
+    ch, layer = oracle.distortion(h, np.ones(1, np.float32), np.zeros(1, np.float32), 3, lib)
+    x24 = float(np.float32(2.4))
+    assert np.allclose(ch[0], [1 + 2 * x24, 1 + x24 * x24, 5.0, (x24 - 2) ** 2], rtol=1e-15)
+    assert abs(layer[4] - (1 + 2 * x24) / np.sqrt((1 + x24 * x24) * 5.0)) < 1e-15
+    assert abs(layer[5] - (x24 - 2) / np.sqrt(1 + x24 * x24)) < 1e-15
+    # direction of Table 2: channel-wise ranges distort less than one range per layer
+    xr = _workload_tensor("relu", (8, 16, 16, 16), seed=0)
+    s, z = oracle.prescale(*oracle.range_reduce(xr, lib), 3, lib)
+    _, lay_c = oracle.distortion(xr, s, z, 3, lib)
+    flat = xr.reshape(1, 1, 1, -1)
+    sl, zl = oracle.prescale(*oracle.range_reduce(flat, lib), 3, lib)
+    _, lay_l = oracle.distortion(flat, sl, zl, 3, lib)
+    assert lay_c[4] > lay_l[4] and lay_c[5] < lay_l[5]
+
+
 ALL_CHECKS = [
     check_golden,
     check_dyadic_grid_exhaustive,
@@ -460,4 +502,5 @@ ALL_CHECKS = [
     check_error_halves_per_bit,
     check_channelwise_beats_layerwise,
     check_accumulation_forms,
+    check_distortion_metrics,
 ]

@@ -16,7 +16,7 @@ MUTANTS = [
     ("round_truncates", "return rintf(v);", "return truncf(v);", 1),
     ("dequant_drops_zero_point", "float d = q - z;", "float d = q;", 1),
     ("dequant_adds_zero_point", "float d = q - z;", "float d = q + z;", 1),
-    ("batch_and_channel_transposed", "(in * c + ic) * hw + k", "(ic * n + in) * hw + k", 6),
+    ("batch_and_channel_transposed", "(in * c + ic) * hw + k", "(ic * n + in) * hw + k", 7),
     ("range_over_first_sample_only",
      "float mx = -INFINITY;\n        for (int64_t in = 0; in < n; ++in) {",
      "float mx = -INFINITY;\n        for (int64_t in = 0; in < 1; ++in) {", 1),
@@ -25,8 +25,8 @@ MUTANTS = [
     ("zero_point_not_rounded", "rintf((-ch_min[ic]) / s) + 0.0f", "(-ch_min[ic]) / s + 0.0f", 1),
     ("zero_point_keeps_minus_zero", "rintf((-ch_min[ic]) / s) + 0.0f", "rintf((-ch_min[ic]) / s)", 1),
     ("levels_off_by_one", "(float)((1 << bits) - 1)", "(float)(1 << bits)", 1),
-    ("no_clamp", "float q = fminf(fmaxf(u, 0.0f), qmax);", "float q = u;", 1),
-    ("clamp_low_side_missing", "float q = fminf(fmaxf(u, 0.0f), qmax);", "float q = fminf(u, qmax);", 1),
+    ("no_clamp", "return fminf(fmaxf(u, 0.0f), qmax);", "return u;", 1),
+    ("clamp_low_side_missing", "return fminf(fmaxf(u, 0.0f), qmax);", "return fminf(u, qmax);", 1),
     ("mask_strict", "if (!(u >= 0.0f && u <= qmax))", "if (!(u > 0.0f && u < qmax))", 1),
     ("mask_on_clamped_code_always_true", "if (!(u >= 0.0f && u <= qmax))", "if (0)", 1),
     ("mask_inverted", "if (!(u >= 0.0f && u <= qmax))", "if ((u >= 0.0f && u <= qmax))", 1),
@@ -42,6 +42,11 @@ MUTANTS = [
     ("gate_bits_msb_first", "mask[i >> 3] |= (uint8_t)(1u << (i & 7));", "mask[i >> 3] |= (uint8_t)(0x80u >> (i & 7));", 1),
     ("gate_bits_strict", "if (u >= 0.0f && u <= qmax)\n                    mask[i >> 3]", "if (u > 0.0f && u < qmax)\n                    mask[i >> 3]", 1),
     ("bwd_from_mask_inverted", "if (!((mask[i >> 3] >> (i & 7)) & 1u))", "if (((mask[i >> 3] >> (i & 7)) & 1u))", 1),
+    ("cosine_without_square_roots", "layer[4] = layer[0] / (sqrt(layer[1]) * sqrt(layer[2]));", "layer[4] = layer[0] / (layer[1] * layer[2]);", 1),
+    ("relative_error_squared", "layer[5] = sqrt(layer[3]) / sqrt(layer[1]);", "layer[5] = layer[3] / layer[1];", 1),
+    ("relative_error_over_q_norm", "layer[5] = sqrt(layer[3]) / sqrt(layer[1]);", "layer[5] = sqrt(layer[3]) / sqrt(layer[2]);", 1),
+    ("distortion_difference_sign_lost", "double d = xd - qd;", "double d = xd + qd;", 1),
+    ("distortion_single_precision_sums", "double xq = 0.0, xx = 0.0, qq = 0.0, dd = 0.0;", "float xq = 0.0, xx = 0.0, qq = 0.0, dd = 0.0;", 1),
     ("bf16_ties_round_up", "(dropped == 0x8000u && (kept & 1u))", "(dropped == 0x8000u)", 1),
     ("bf16_truncates", "if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))", "if (0)", 1),
     ("inloop_drops_scale", "float ws = weight[ic] * scale[ic];", "float ws = weight[ic];", 1),
