@@ -1,0 +1,63 @@
+"""The four calls captured into a HIP graph and replayed: every replay must reproduce
+the eager result, with eager work and synchronisations in between (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_18339_amd as G
+import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.mark.parametrize("shape,dtype", [((16, 64, 28, 28), torch.float32), ((8, 96, 7, 7), torch.bfloat16)])
+def test_graph_replays_match_eager(shape, dtype):
+    bits = 4
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), 1, DEV, dtype)
+    dy = workloads.make_grad(shape, 1, DEV, dtype)
+    q = G.ActivationQuantizer(shape, dtype, bits, DEV)
+    x_hat = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    mask = torch.empty(G.granq_mask_bytes(q.desc), dtype=torch.uint8, device=DEV)
+    dx_m = torch.empty_like(x)
+
+    def step(stream):
+        q.calibrate(x, stream)
+        G.granq_fakequant_fwd_mask(x, q.scale, q.zero_point, bits, x_hat, mask, stream, q.desc)
+        G.granq_fakequant_bwd(x, dy, q.scale, q.zero_point, bits, dx, stream, q.desc)
+        G.granq_fakequant_bwd_mask(dy, mask, dx_m, stream, q.desc)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (x_hat, dx, dx_m, q.scale, q.zero_point, q.ch_min, q.ch_max)]
+
+    def check(ref):
+        for a, b in zip(snapshot(), ref):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(side)
+    torch.cuda.current_stream().wait_stream(side)
+    want1 = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream())
+    x2 = workloads.make_activation(shape, "relu", (0.05, 20.0), 2, DEV, dtype)
+    x1 = x.clone()
+    for rep in range(4):
+        src = x1 if rep % 2 == 0 else x2
+        x.copy_(src)                       # eager work between replays: new input in the captured buffer
+        for t in (x_hat, dx, dx_m):
+            t.fill_(7)                      # clobber the outputs
+        step(torch.cuda.current_stream())   # eager reference for this input
+        ref = snapshot()
+        for t in (x_hat, dx, dx_m, q.scale, q.zero_point):
+            t.fill_(3)
+        torch.cuda.synchronize()
+        graph.replay()
+        check(ref)
+        if rep == 0:
+            check(want1)
