@@ -245,6 +245,37 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc,
                                 double *ch_sums, double *layer,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Integer-domain accumulation: the 1x1 convolution that consumes the quantized
+ * activations, computed from the integer codes (Eq. 3) with the per-channel scale
+ * folded into the weights beforehand, so that the sum itself is pure int8 x int8 ->
+ * int32 work on the matrix cores:
+ *     y[n,o,k] = out_scale[o] * ( sum_c wq[o,c] * code[n,c,k]  -  corr[o] ),   k over H*W
+ *
+ * granq_fold_weights prepares wq, corr, out_scale from float weights w[o][c] and the
+ * activation quantizer's scale / zero-point:
+ *     w'[o,c]      = w[o,c] * scale[c]                      (Eq. 3's w_c * s_c)
+ *     out_scale[o] = max_c |w'[o,c]| / 127                  (1 if the row is all zero)
+ *     wq[o,c]      = clamp(round_half_even(w'[o,c] / out_scale[o]), -127, 127)
+ *     corr[o]      = sum_c wq[o,c] * (int) zero_point[c]    (Eq. 3's - z_c, summed once)
+ * so that y approximates sum_c w[o,c] * x_hat[n,c,k] (Eq. 6) up to the rounding of w'.
+ *   w [in] o*c floats; scale, zero_point [in] c floats; wq [out] o*c int8; corr [out] o
+ *   int32; out_scale [out] o floats.  zero_point must hold integers of magnitude < 2^23.
+ *
+ * granq_conv1x1_int8: codes [in] N*C*H*W bytes as written by granq_fakequant_fwd (desc
+ * gives n, c, h, w; its dtype is ignored); y [out] N*O*H*W floats, NCHW with O channels.
+ * The matrix-core kernel needs codes <= 127 (bits <= 7), C a multiple of 16, O a multiple
+ * of 32, H*W a multiple of 4 and 16-byte aligned y; anything else runs a plain integer
+ * kernel with identical results.
+ */
+granq_status_t granq_fold_weights(const float *w, const float *scale, const float *zero_point,
+                                  int64_t o, int64_t c, int8_t *wq, int32_t *corr,
+                                  float *out_scale, void *stream);
+
+granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
+                                  const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                  int bits, float *y, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

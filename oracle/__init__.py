@@ -65,9 +65,11 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.granq_oracle_gate_mask.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr]
     lib.granq_oracle_bwd_from_mask.argtypes = [_ptr, _ptr, _int, _i64, _ptr]
     lib.granq_oracle_distortion.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr, _ptr]
+    lib.granq_oracle_fold_weights.argtypes = [_ptr, _ptr, _ptr, _i64, _i64, _ptr, _ptr, _ptr]
+    lib.granq_oracle_conv1x1_int8.argtypes = [_ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_inloop.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_prescaled.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr]
-    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask", "distortion",
+    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask", "distortion", "fold_weights", "conv1x1_int8",
                  "accumulate_inloop", "accumulate_prescaled"):
         getattr(lib, "granq_oracle_" + name).restype = None
     if path is None:
@@ -196,6 +198,34 @@ def fakequant(x: np.ndarray, bits: int, lib=None):
     s, z = prescale(mn, mx, bits, lib)
     x_hat, codes = fakequant_fwd(x, s, z, bits, lib)
     return x_hat, codes, s, z
+
+
+def fold_weights(w: np.ndarray, scale, zero_point, lib=None):
+    """Eq. 3's w_c * s_c folded into int8 rows.  Returns (wq int8[O,C], corr int32[O], out_scale f32[O])."""
+    lib = lib or load()
+    w = np.ascontiguousarray(w, np.float32)
+    o, c = w.shape
+    s, z = _f32vec(scale, c), _f32vec(zero_point, c)
+    wq = np.empty((o, c), np.int8)
+    corr = np.empty(o, np.int32)
+    a = np.empty(o, np.float32)
+    lib.granq_oracle_fold_weights(_p(w), _p(s), _p(z), o, c, _p(wq), _p(corr), _p(a))
+    return wq, corr, a
+
+
+def conv1x1_int8(codes: np.ndarray, wq: np.ndarray, corr: np.ndarray, out_scale: np.ndarray, lib=None):
+    """y[n,o,k] = out_scale[o] * (sum_c wq[o,c] * code[n,c,k] - corr[o])."""
+    lib = lib or load()
+    n, c, hw = _nchw(codes)
+    if codes.dtype != np.uint8 or wq.dtype != np.int8 or wq.shape[1] != c:
+        raise TypeError("codes must be uint8 (N,C,...), wq int8 (O,C)")
+    o = wq.shape[0]
+    wq = np.ascontiguousarray(wq)
+    corr = np.ascontiguousarray(corr, np.int32)
+    a = np.ascontiguousarray(out_scale, np.float32)
+    y = np.empty((n, o) + codes.shape[2:], np.float32)
+    lib.granq_oracle_conv1x1_int8(_p(codes), n, c, hw, o, _p(wq), _p(corr), _p(a), _p(y))
+    return y
 
 
 def accumulate_inloop(codes: np.ndarray, scale, zero_point, weight, lib=None):

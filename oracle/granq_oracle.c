@@ -342,3 +342,57 @@ void granq_oracle_accumulate_prescaled(const float *x_hat,
         }
     }
 }
+
+/*
+ * Integer-domain accumulation (Eq. 3 with w_c * s_c folded into int8 weights).
+ *
+ * Fold: w'[o,c] = w[o,c] * s_c; the row is quantized symmetrically to int8 with
+ * step a_o = max_c |w'[o,c]| / 127 (1 for an all-zero row):
+ *     wq[o,c] = clamp(round(w'[o,c] / a_o), -127, 127),   corr[o] = sum_c wq[o,c] * z_c
+ * (z_c is an integer held in a float).  binary32 operations, one rounding each.
+ */
+void granq_oracle_fold_weights(const float *w, const float *scale, const float *zero_point,
+                               int64_t o, int64_t c, int8_t *wq, int32_t *corr, float *out_scale)
+{
+    for (int64_t io = 0; io < o; ++io) {
+        float amax = 0.0f;
+        for (int64_t ic = 0; ic < c; ++ic) {
+            float ws = w[io * c + ic] * scale[ic];
+            if (fabsf(ws) > amax) amax = fabsf(ws);
+        }
+        float a = amax / 127.0f;
+        if (!(a > 0.0f))
+            a = 1.0f;
+        int32_t cz = 0;
+        for (int64_t ic = 0; ic < c; ++ic) {
+            float ws = w[io * c + ic] * scale[ic];
+            float q = rintf(ws / a);
+            q = fminf(fmaxf(q, -127.0f), 127.0f);
+            wq[io * c + ic] = (int8_t)q;
+            cz += (int32_t)q * (int32_t)zero_point[ic];
+        }
+        corr[io] = cz;
+        out_scale[io] = a;
+    }
+}
+
+/*
+ * The 1x1 convolution on the codes:
+ *     y[n,o,k] = out_scale[o] * (float)( sum_c wq[o,c] * code[n,c,k]  -  corr[o] )
+ * The sum is exact in int32; the conversion to float and the product round once each.
+ */
+void granq_oracle_conv1x1_int8(const uint8_t *codes, int64_t n, int64_t c, int64_t hw, int64_t o,
+                               const int8_t *wq, const int32_t *corr, const float *out_scale,
+                               float *y)
+{
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t io = 0; io < o; ++io) {
+            for (int64_t k = 0; k < hw; ++k) {
+                int32_t acc = 0;
+                for (int64_t ic = 0; ic < c; ++ic)
+                    acc += (int32_t)wq[io * c + ic] * (int32_t)codes[(in * c + ic) * hw + k];
+                y[(in * o + io) * hw + k] = out_scale[io] * (float)(acc - corr[io]);
+            }
+        }
+    }
+}

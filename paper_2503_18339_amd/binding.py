@@ -29,7 +29,8 @@ EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "gra
            "granq_range_reduce",
            "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
-           "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion")
+           "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
+           "granq_fold_weights", "granq_conv1x1_int8")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -89,6 +90,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_fakequant_bwd_mask.argtypes = [_vp, _vp, dp, _vp, _vp]
     lib.granq_rowwise_fakequant_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
     lib.granq_rowwise_fakequant_bwd_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
+    lib.granq_fold_weights.argtypes = [_vp, _vp, _vp, ctypes.c_int64, ctypes.c_int64, _vp, _vp, _vp, _vp]
+    lib.granq_conv1x1_int8.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, _vp, _vp]
     lib.granq_distortion_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_distortion.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -293,6 +296,34 @@ def granq_rowwise_fakequant_bwd_multi(items, dtype: torch.dtype, bits: int, stre
     code = GRANQ_F32 if dtype == torch.float32 else GRANQ_BF16
     _check(load().granq_rowwise_fakequant_bwd_multi(ctypes.cast(items, _vp), len(items), code, int(bits),
                                                     _stream(stream)), "granq_rowwise_fakequant_bwd_multi")
+
+
+def granq_fold_weights(w: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, wq: torch.Tensor,
+                       corr: torch.Tensor, out_scale: torch.Tensor, stream=None) -> None:
+    o, c = int(w.shape[0]), w.numel() // int(w.shape[0])
+    if w.dtype != torch.float32 or wq.dtype != torch.int8 or wq.numel() != o * c:
+        raise ValueError("w must be float32 (O, C) and wq int8 of the same size")
+    if corr.dtype != torch.int32 or corr.numel() != o:
+        raise ValueError("corr must be int32 with O entries")
+    _check(load().granq_fold_weights(_dev(w, "w"), _vec(scale, c, "scale"), _vec(zero_point, c, "zero_point"),
+                                     o, c, _dev(wq, "wq"), _dev(corr, "corr"), _vec(out_scale, o, "out_scale"),
+                                     _stream(stream)), "granq_fold_weights")
+
+
+def granq_conv1x1_int8(codes: torch.Tensor, wq: torch.Tensor, corr: torch.Tensor, out_scale: torch.Tensor,
+                       bits: int, y: torch.Tensor, stream=None) -> None:
+    if codes.dtype != torch.uint8 or codes.dim() != 4:
+        raise ValueError("codes must be a uint8 (N, C, H, W) tensor")
+    n, c, h, w = (int(v) for v in codes.shape)
+    o = int(wq.shape[0])
+    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int32 or corr.numel() != o:
+        raise ValueError("wq must be int8 (O, C) and corr int32 (O)")
+    if y.dtype != torch.float32 or y.numel() != n * o * h * w:
+        raise ValueError("y must be float32 (N, O, H, W)")
+    d = make_desc(n, c, h, w, GRANQ_F32)
+    _check(load().granq_conv1x1_int8(_dev(codes, "codes"), ctypes.byref(d), o, _dev(wq, "wq"),
+                                     _dev(corr, "corr"), _vec(out_scale, o, "out_scale"), int(bits),
+                                     _dev(y, "y"), _stream(stream)), "granq_conv1x1_int8")
 
 
 def granq_distortion_workspace_bytes(desc: granq_desc_t) -> int:

@@ -34,7 +34,7 @@ def source_hash() -> str:
     """Hash of everything that determines the quantizer kernels' code: sources, headers, flags
     (the comparison kernels and the row-wise weight kernels are left out)."""
     h = hashlib.sha256()
-    paths = [p for p in _build.SOURCES + _build.HEADERS if "compare" not in os.path.basename(p) and "rowwise" not in os.path.basename(p) and "metrics" not in os.path.basename(p)]
+    paths = [p for p in _build.SOURCES + _build.HEADERS if "compare" not in os.path.basename(p) and "rowwise" not in os.path.basename(p) and "metrics" not in os.path.basename(p) and "conv" not in os.path.basename(p)]
     for path in sorted(paths):
         with open(path, "rb") as fh:
             h.update(os.path.basename(path).encode())

@@ -487,6 +487,44 @@ def check_distortion_metrics(lib=None):
     assert lay_c[4] > lay_l[4] and lay_c[5] < lay_l[5]
 
 
+def check_integer_accumulation(lib=None):
+    """Eq. 3 with the scale folded into int8 weights: the integer sum against numpy's integer
+    einsum, the fold against its defining properties, and the whole against Eq. 6 within the
+    bound that the rounding of the folded weights allows."""
+    rng = np.random.default_rng(31)
+    x = _workload_tensor("linear", (3, 16, 5, 4), seed=7)
+    xh, codes, s, z = oracle.fakequant(x, 4, lib)
+    w = (rng.standard_normal((6, 16)) * rng.uniform(0.1, 3, size=(6, 1))).astype(np.float32)
+    w[4] = 0.0
+    wq, corr, a = oracle.fold_weights(w, s, z, lib)
+    ws = (w * s.reshape(1, -1)).astype(np.float32)
+    assert wq.dtype == np.int8 and np.abs(wq.astype(np.int32)).max() <= 127
+    live = [0, 1, 2, 3, 5]
+    assert np.all(np.abs(wq[live].astype(np.int32)).max(axis=1) == 127)      # the largest entry maps to +-127
+    assert np.all(wq[4] == 0) and a[4] == 1.0 and corr[4] == 0
+    _eq(a[live], (np.abs(ws[live]).max(axis=1) / np.float32(127)).astype(np.float32), "row step")
+    assert np.all(np.abs(a.reshape(-1, 1) * wq - ws) <= 0.5 * a.reshape(-1, 1) * (1 + 1e-6))
+    _eq(corr, wq.astype(np.int64) @ z.astype(np.int64), "zero-point correction")
+    # integer sum: numpy's int64 einsum is exact
+    y = oracle.conv1x1_int8(codes, wq, corr, a, lib)
+    acc = np.einsum("oc,nchw->nohw", wq.astype(np.int64), codes.astype(np.int64)) - corr.reshape(1, -1, 1, 1)
+    _eq(y, (a.reshape(1, -1, 1, 1) * acc.astype(np.float32)).astype(np.float32), "int8 convolution")
+    # against Eq. 6 (float weights on x_hat): off by at most the weight rounding times |code - z|
+    ref = np.einsum("oc,nchw->nohw", w.astype(np.float64), xh.astype(np.float64))
+    bound = 0.5 * a.astype(np.float64).reshape(1, -1, 1, 1) * \
+        np.abs(codes.astype(np.float64) - z.reshape(1, -1, 1, 1)).sum(axis=1, keepdims=True)
+    assert np.all(np.abs(y - ref) <= bound * (1 + 1e-4) + 1e-4 * np.abs(ref).max())
+    # a dyadic case that is exact end to end: w = +-1, 127 entries per row irrelevant -> use s = 1
+    codes2 = rng.integers(0, 8, size=(2, 4, 3, 3)).astype(np.uint8)
+    w2 = np.array([[127, -127, 64, 0], [1, 2, 3, 127]], np.float32)
+    wq2, corr2, a2 = oracle.fold_weights(w2, np.ones(4, np.float32), np.array([0, 1, 2, 3], np.float32), lib)
+    _eq(wq2, w2.astype(np.int8), "integer weights fold to themselves")
+    _eq(a2, np.ones(2, np.float32), "unit step")
+    y2 = oracle.conv1x1_int8(codes2, wq2, corr2, a2, lib)
+    want2 = np.einsum("oc,nchw->nohw", w2.astype(np.int64), codes2.astype(np.int64) - np.arange(4).reshape(1, 4, 1, 1))
+    _eq(y2, want2.astype(np.float32), "exact integer case")
+
+
 ALL_CHECKS = [
     check_golden,
     check_dyadic_grid_exhaustive,
@@ -503,4 +541,5 @@ ALL_CHECKS = [
     check_channelwise_beats_layerwise,
     check_accumulation_forms,
     check_distortion_metrics,
+    check_integer_accumulation,
 ]
