@@ -39,7 +39,7 @@ namespace granq {
 #define GRANQ_R_V_F32 4
 #endif
 #ifndef GRANQ_R_V_BF16
-#define GRANQ_R_V_BF16 2
+#define GRANQ_R_V_BF16 1
 #endif
 #ifndef GRANQ_R_UNROLL
 #define GRANQ_R_UNROLL 8
