@@ -13,7 +13,7 @@ DEV = "cuda"
 
 SHAPES = [
     (8, 16, 32, 32), (5, 37, 9, 8), (6, 104, 7, 7), (3, 40, 1, 1), (9, 24, 14, 14), (4, 3000, 1, 1),
-    (1, 1, 1, 16384), (1, 64, 1, 1152), (1, 2048, 7, 7), (17, 520, 2, 2), (4, 4, 64, 66), (1, 8, 1, 1),
+    (1, 1, 1, 16384), (1, 64, 1, 1152), (140001, 2, 2, 2), (1, 2048, 7, 7), (17, 520, 2, 2), (4, 4, 64, 66), (1, 8, 1, 1),
     # rows that are not a multiple of eight elements, or no 16-byte structure: byte-wise kernels
     (6, 100, 7, 7), (4, 9, 2, 2), (2, 3, 7, 7), (5, 7, 3, 3), (1, 1, 1, 5), (1, 1, 1, 1), (3, 1, 7, 3),
     (1, 1, 1, 4), (2, 1, 5, 4),

@@ -48,6 +48,8 @@ SMALL = [
     (8, 16, 32, 32), (5, 37, 9, 8), (6, 100, 7, 7), (3, 40, 1, 1), (9, 24, 14, 14), (4, 3000, 1, 1),
     (1, 1, 1, 16384), (2, 1, 5, 4), (1, 64, 1, 1152), (7, 12, 14, 14), (1, 2048, 7, 7), (13, 8, 7, 7),
     (17, 520, 2, 2), (4, 4, 64, 65), (1, 1, 1, 4), (1, 4, 1, 1), (31, 8, 1, 3),
+    # more rows than the grid's second dimension holds (row groups are capped at 65535)
+    (200001, 4, 1, 4), (70001, 3, 2, 2),
     # no 16-byte structure: element-wise kernels
     (2, 3, 7, 7), (5, 7, 3, 3), (1, 1, 1, 5), (3, 1, 7, 3), (1, 1, 1, 1), (2, 5, 1, 1), (4, 9, 5, 5),
 ]
