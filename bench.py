@@ -445,7 +445,7 @@ def main():
     k_ms = sum(e[0].elapsed_time(e[1]) for e in ev)
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
     roofline = {
-        "kernel": "granq::fq_bwd_cols<granq::%s, 1, %d, true>" % ("F32" if args.dtype == "f32" else "BF16", bwd_rows),
+        "kernel": "granq::fq_bwd_cols<granq::%s, 1, %d, 0>" % ("F32" if args.dtype == "f32" else "BF16", bwd_rows),
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "launches": k_launches, "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),

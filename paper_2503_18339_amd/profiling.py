@@ -95,7 +95,8 @@ def summarise_counters(fetch_csv: str, write_csv: str, copy_bytes: int, dominant
         rec[0] += fb
         rec[1] += wb
         rec[2] += 1
-    dom = [(k, r) for k, r in per_kernel.items() if dominant in k and k.rstrip(">").endswith("true")]
+    # the instance whose last template argument is 0: one channel per 16-byte vector
+    dom = [(k, r) for k, r in per_kernel.items() if dominant in k and k.rstrip(">").rstrip().endswith(", 0")]
     if not dom:
         raise SystemExit("dominant kernel %r not found" % dominant)
     name, (fb, wb, shapes) = max(dom, key=lambda kr: kr[1][0] + kr[1][1])
