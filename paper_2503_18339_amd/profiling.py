@@ -31,10 +31,11 @@ COPY_KERNEL = "__amd_rocclr_copyBuffer"
 
 
 def source_hash() -> str:
-    """Hash of everything that determines the quantizer kernels' code: sources, headers, flags
-    (the comparison kernels and the row-wise weight kernels are left out)."""
+    """Hash of everything that determines the code of the four-call kernels: their source,
+    the device headers it includes and the compiler flags."""
     h = hashlib.sha256()
-    paths = [p for p in _build.SOURCES + _build.HEADERS if "compare" not in os.path.basename(p) and "rowwise" not in os.path.basename(p) and "metrics" not in os.path.basename(p) and "conv" not in os.path.basename(p)]
+    names = ("granq_kernels.hip", "granq_device.h", "granq_plan.h", "granq_quotient.h")
+    paths = [os.path.join(_build.CSRC, n) for n in names]
     for path in sorted(paths):
         with open(path, "rb") as fh:
             h.update(os.path.basename(path).encode())
