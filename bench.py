@@ -394,6 +394,34 @@ def cpu_baseline(wl, bits, sample_batch, min_seconds=10.0, max_passes=8):
     return total_bytes / total_s / 1e9, total_s, passes
 
 
+def cpu_baseline_threads(wl, bits, sample_batch, threads):
+    """The same oracle with the batch split over `threads` host threads (ctypes releases the
+    GIL): per-thread partial ranges are combined with numpy's minimum / maximum, the
+    element-wise passes are independent per sample.  One whole pass."""
+    import numpy as np
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    total_bytes = 0
+    total_s = 0.0
+    with ThreadPoolExecutor(threads) as ex:
+        for i, a in enumerate(wl.tensors()):
+            shape = a.shape(sample_batch)
+            x = workloads.make_activation(shape, a.law, wl.sigma, i, "cpu").numpy()
+            dy = workloads.make_grad(shape, i, "cpu").numpy()
+            step = max(1, -(-shape[0] // threads))
+            cuts = [(j, min(shape[0], j + step)) for j in range(0, shape[0], step)]
+            t0 = time.perf_counter()
+            parts = list(ex.map(lambda ab: oracle.range_reduce(x[ab[0]:ab[1]]), cuts))
+            mn = np.minimum.reduce([p[0] for p in parts])
+            mx = np.maximum.reduce([p[1] for p in parts])
+            s, z = oracle.prescale(mn, mx, bits)
+            list(ex.map(lambda ab: oracle.fakequant_fwd(x[ab[0]:ab[1]], s, z, bits), cuts))
+            list(ex.map(lambda ab: oracle.fakequant_bwd(x[ab[0]:ab[1]], dy[ab[0]:ab[1]], s, z, bits), cuts))
+            total_s += time.perf_counter() - t0
+            total_bytes += x.size * 4 * 6
+    return total_bytes / total_s / 1e9, total_s
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -518,6 +546,14 @@ def main():
                       "(range_reduce+prescale+fwd+bwd), %.1f s of oracle time"
                       % (args.cpu_sample_batch, args.bits, passes, secs),
         }
+
+        threads = min(16, os.cpu_count() or 1)
+        if threads > 1:
+            gbs_t, secs_t = cpu_baseline_threads(wl, args.bits, args.cpu_sample_batch, threads)
+            out["cpu_baseline_all_cores"] = {
+                "value": round(gbs_t, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+                "sample": "one whole pass at batch %d, the batch split over %d threads, %.1f s"
+                          % (args.cpu_sample_batch, threads, secs_t)}
 
     print(json.dumps(out))
 
