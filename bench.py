@@ -59,12 +59,17 @@ def build_layers(wl, dtype, bits, device):
     return [Layer(a, wl.batch, wl.sigma, dtype, bits, i, device) for i, a in enumerate(wl.tensors())]
 
 
-def run_step(layers, stream, ev=None):
-    """One pass of the hot path.  `ev`, if given, collects one (start, end, bytes,
+def run_step(layers, stream, ev=None, one_call=False):
+    """One pass of the hot path (four calls per tensor; `one_call` swaps the first two for
+    granq_calibrate, same results with one launch fewer).  `ev`, if given, collects one (start, end, bytes,
     launches) record per step around the consecutive backward launches of the
     dominant kernel (the layers are ordered so that those launches are adjacent)."""
     for L in layers:
-        L.q.calibrate(L.x, stream)
+        if one_call:
+            L.q.calibrate(L.x, stream)
+        else:
+            G.granq_range_reduce(L.x, L.q.ch_min, L.q.ch_max, L.q.workspace, stream, L.q.desc)
+            G.granq_prescale(L.q.ch_min, L.q.ch_max, L.q.bits, L.q.scale, L.q.zero_point, stream)
         G.granq_fakequant_fwd(L.x, L.q.scale, L.q.zero_point, L.q.bits, L.x_hat, None, stream, L.q.desc)
     rev = list(reversed(layers))
     # the longest run of adjacent launches of the dominant kernel in the backward sweep
@@ -94,31 +99,31 @@ def run_step(layers, stream, ev=None):
             ev.append((a, b, sum(M.bytes("bwd") for M in doms), len(doms)))
 
 
-def time_steps(layers, steps, warmup, with_events):
+def time_steps(layers, steps, warmup, with_events, one_call=False):
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
-        run_step(layers, stream)
+        run_step(layers, stream, None, one_call)
     ev = [] if with_events else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        run_step(layers, stream, ev)
+        run_step(layers, stream, ev, one_call)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     return dt, ev
 
 
-def time_graph_steps(layers, steps, warmup):
+def time_graph_steps(layers, steps, warmup, one_call=False):
     """The same step captured once into a HIP graph and replayed (no per-kernel events)."""
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        run_step(layers, side)
+        run_step(layers, side, None, one_call)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        run_step(layers, torch.cuda.current_stream())
+        run_step(layers, torch.cuda.current_stream(), None, one_call)
     for _ in range(warmup):
         graph.replay()
     torch.cuda.synchronize()
@@ -451,6 +456,7 @@ def main():
 
     device = "cuda"
     wl = workloads.WORKLOADS[args.workload]()
+    variants_only = args.workload != "config3" and not args.no_extras
     if args.workload != "config3":
         args.no_extras = True
         args.cpu_sample_batch = 0
@@ -505,6 +511,19 @@ def main():
         out["pmc_calibration"] = {"kernel": "torch copy_ (elementwise copy)", "launches": 3,
                                   "bytes_read": big.numel * esize, "bytes_written": big.numel * esize}
 
+    if variants_only:
+        # the other workloads: only the step variants (no events, one-call calibration, graph replay)
+        variants = {}
+        dt2, _ = time_steps(layers, args.steps, 2, with_events=False)
+        variants["value_without_kernel_events_GBs"] = round(step_bytes / (dt2 / args.steps) / 1e9, 1)
+        dt4, _ = time_steps(layers, args.steps, 2, with_events=False, one_call=True)
+        variants["value_one_call_calibration_GBs"] = round(step_bytes / (dt4 / args.steps) / 1e9, 1)
+        dt3 = time_graph_steps(layers, args.steps, 2)
+        variants["value_hip_graph_replay_GBs"] = round(step_bytes / (dt3 / args.steps) / 1e9, 1)
+        dt5 = time_graph_steps(layers, args.steps, 2, one_call=True)
+        variants["value_hip_graph_replay_one_call_GBs"] = round(step_bytes / (dt5 / args.steps) / 1e9, 1)
+        out["extra"] = variants
+
     if not args.no_extras:
         extra = {"per_kernel": kernel_breakdown(layers)}
         fb_us = sum(r["fwd_us"] + r["bwd_us"] for r in extra["per_kernel"])
@@ -512,6 +531,8 @@ def main():
         # same step without the per-launch events: what the events cost
         dt2, _ = time_steps(layers, args.steps, 2, with_events=False)
         extra["value_without_kernel_events_GBs"] = round(step_bytes / (dt2 / args.steps) / 1e9, 1)
+        dt4, _ = time_steps(layers, args.steps, 2, with_events=False, one_call=True)
+        extra["value_one_call_calibration_GBs"] = round(step_bytes / (dt4 / args.steps) / 1e9, 1)
         dt3 = time_graph_steps(layers, args.steps, 2)
         extra["value_hip_graph_replay_GBs"] = round(step_bytes / (dt3 / args.steps) / 1e9, 1)
         del layers

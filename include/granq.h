@@ -125,6 +125,19 @@ granq_status_t granq_prescale(const float *ch_min, const float *ch_max,
                               float *scale, float *zero_point, void *stream);
 
 /*
+ * granq_range_reduce followed by granq_prescale in one call and one launch
+ * fewer (Eq. 4, then Eq. 5: Alg. 1 up to its quantize step): the second pass of
+ * the reduction applies Eq. 5 to each channel's range as it produces it.  All
+ * four output vectors are written and are bit-identical to those of the two
+ * separate calls.  Arguments, workspace and errors as for those two.  Worth it
+ * for small tensors, where each dependent launch costs as much as the data.
+ */
+granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits,
+                               float *ch_min, float *ch_max,
+                               float *scale, float *zero_point,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Quantize, clamp, dequantize (Eq. 1, then the dequantization of Eq. 6; Alg. 1's
  * "quantize" and "dequantize & pre-scale" steps):
  *     u     = round_half_even(x / scale[c] + zero_point[c])

@@ -27,7 +27,7 @@ GRANQ_BF16 = 1
 
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
            "granq_range_reduce",
-           "granq_prescale", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
+           "granq_prescale", "granq_calibrate", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
            "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
            "granq_fold_weights", "granq_conv1x1_int8")
@@ -83,6 +83,7 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_plan_describe.argtypes = [dp, ctypes.POINTER(ctypes.c_int64 * 16)]
     lib.granq_range_reduce.argtypes = [_vp, dp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_prescale.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int, _vp, _vp, _vp]
+    lib.granq_calibrate.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_fakequant_fwd.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_bwd.argtypes = [_vp, _vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp]
     lib.granq_mask_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
@@ -195,6 +196,17 @@ def granq_prescale(ch_min: torch.Tensor, ch_max: torch.Tensor, bits: int, scale:
     _check(load().granq_prescale(_vec(ch_min, c, "ch_min"), _vec(ch_max, c, "ch_max"), c, int(bits),
                                  _vec(scale, c, "scale"), _vec(zero_point, c, "zero_point"),
                                  _stream(stream)), "granq_prescale")
+
+
+def granq_calibrate(x: torch.Tensor, bits: int, ch_min: torch.Tensor, ch_max: torch.Tensor,
+                    scale: torch.Tensor, zero_point: torch.Tensor, workspace: torch.Tensor,
+                    stream=None, desc: Optional[granq_desc_t] = None) -> None:
+    d = desc or desc_of(x)
+    _check(load().granq_calibrate(_dev(x, "x"), ctypes.byref(d), int(bits), _vec(ch_min, d.c, "ch_min"),
+                                  _vec(ch_max, d.c, "ch_max"), _vec(scale, d.c, "scale"),
+                                  _vec(zero_point, d.c, "zero_point"), _dev(workspace, "workspace"),
+                                  workspace.numel() * workspace.element_size(), _stream(stream)),
+           "granq_calibrate")
 
 
 def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,

@@ -590,9 +590,20 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
     }
 }
 
+// Eq. 5 for one channel: step size and zero-point from the channel's range.
+__device__ __forceinline__ void prescale_one(float mn, float mx, float qmax, float &s, float &z) {
+    const float range = mx - mn;
+    s = range / qmax;
+    if (!(s >= FLT_MIN)) s = 1.0f;                     // zero, subnormal or NaN scale
+    z = __builtin_rintf((-mn) / s) + 0.0f;             // "+ 0" turns -0 into +0
+}
+
+// `scale` / `zero_point` may be null (ranges only); otherwise Eq. 5 is applied
+// to the channel's range in the same launch.
 __global__ __launch_bounds__(kBlock) void range_cols_pass2(
     const float *__restrict__ ws_min, const float *__restrict__ ws_max,
-    float *__restrict__ ch_min, float *__restrict__ ch_max, ColPlan plan)
+    float *__restrict__ ch_min, float *__restrict__ ch_max, ColPlan plan,
+    float qmax, float *__restrict__ scale, float *__restrict__ zero_point)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t c = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x / kWave);
@@ -615,6 +626,12 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass2(
     if (lane == 0) {
         ch_min[c] = mn;
         ch_max[c] = mx;
+        if (scale) {
+            float sc, zp;
+            prescale_one(mn, mx, qmax, sc, zp);
+            scale[c] = sc;
+            zero_point[c] = zp;
+        }
     }
 }
 
@@ -663,7 +680,8 @@ __global__ __launch_bounds__(kBlock) void range_rows_pass1(
 
 __global__ __launch_bounds__(kBlock) void range_rows_pass2(
     const float *__restrict__ ws_min, const float *__restrict__ ws_max,
-    float *__restrict__ ch_min, float *__restrict__ ch_max, int64_t c, int32_t groups)
+    float *__restrict__ ch_min, float *__restrict__ ch_max, int64_t c, int32_t groups,
+    float qmax, float *__restrict__ scale, float *__restrict__ zero_point)
 {
     const int64_t ic = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (ic >= c) return;
@@ -674,6 +692,12 @@ __global__ __launch_bounds__(kBlock) void range_rows_pass2(
     }
     ch_min[ic] = mn;
     ch_max[ic] = mx;
+    if (scale) {
+        float sc, zp;
+        prescale_one(mn, mx, qmax, sc, zp);
+        scale[ic] = sc;
+        zero_point[ic] = zp;
+    }
 }
 
 // One wavefront per (n,c) slab at a time; scale and zero-point are
@@ -729,11 +753,8 @@ __global__ __launch_bounds__(kBlock) void prescale_kernel(
 {
     const int64_t ic = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (ic >= c) return;
-    const float mn = ch_min[ic];
-    const float range = ch_max[ic] - mn;
-    float s = range / qmax;
-    if (!(s >= FLT_MIN)) s = 1.0f;                     // zero, subnormal or NaN scale
-    const float z = __builtin_rintf((-mn) / s) + 0.0f; // "+ 0" turns -0 into +0
+    float s, z;
+    prescale_one(ch_min[ic], ch_max[ic], qmax, s, z);
     scale[ic] = s;
     zero_point[ic] = z;
 }
@@ -925,9 +946,10 @@ granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[16]) {
     return GRANQ_OK;
 }
 
-granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float *ch_min,
-                                  float *ch_max, void *workspace, size_t workspace_bytes,
-                                  void *stream) {
+// Ranges, and with non-null `scale` / `zero_point` also Eq. 5, in two launches.
+static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float *ch_min,
+                                 float *ch_max, float qmax, float *scale, float *zero_point,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
     granq_status_t st = check_desc(desc);
     if (st != GRANQ_OK) return st;
     if (!x || !ch_min || !ch_max) return GRANQ_ERR_INVALID_ARG;
@@ -948,7 +970,8 @@ granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float
         st = launched();
         if (st != GRANQ_OK) return st;
         dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave)), block(kBlock);
-        hipLaunchKernelGGL(range_cols_pass2, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp);
+        hipLaunchKernelGGL(range_cols_pass2, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+                           qmax, scale, zero_point);
         return launched();
     }
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);
@@ -963,8 +986,25 @@ granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float
     st = launched();
     if (st != GRANQ_OK) return st;
     dim3 grid2((uint32_t)ceil_div(desc->c, kBlock));
-    hipLaunchKernelGGL(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, rp.row_groups);
+    hipLaunchKernelGGL(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, rp.row_groups,
+                       qmax, scale, zero_point);
     return launched();
+}
+
+granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float *ch_min,
+                                  float *ch_max, void *workspace, size_t workspace_bytes,
+                                  void *stream) {
+    return range_impl(x, desc, ch_min, ch_max, 0.0f, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits, float *ch_min,
+                               float *ch_max, float *scale, float *zero_point, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    if (!scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32)) return GRANQ_ERR_UNSUPPORTED;
+    return range_impl(x, desc, ch_min, ch_max, (float)((1 << bits) - 1), scale, zero_point,
+                      workspace, workspace_bytes, stream);
 }
 
 granq_status_t granq_prescale(const float *ch_min, const float *ch_max, int64_t c, int bits,

@@ -45,9 +45,9 @@ class ActivationQuantizer:
                                      device=device)
 
     def calibrate(self, x: torch.Tensor, stream=None) -> None:
-        """range_reduce + prescale: refresh scale / zero-point from x."""
-        B.granq_range_reduce(x, self.ch_min, self.ch_max, self.workspace, stream, self.desc)
-        B.granq_prescale(self.ch_min, self.ch_max, self.bits, self.scale, self.zero_point, stream)
+        """range_reduce + prescale (the two in one call): refresh scale / zero-point from x."""
+        B.granq_calibrate(x, self.bits, self.ch_min, self.ch_max, self.scale, self.zero_point,
+                          self.workspace, stream, self.desc)
 
     def forward(self, x: torch.Tensor, x_hat: torch.Tensor, codes: Optional[torch.Tensor] = None,
                 stream=None, recalibrate: bool = True) -> torch.Tensor:

@@ -84,6 +84,11 @@ def gpu_path(x: torch.Tensor, bits: int, dy: torch.Tensor = None, want_codes=Tru
         G.granq_range_reduce(x, ch_min, ch_max, ws, desc=d)
         G.granq_prescale(ch_min, ch_max, bits, s, z)
         out["min"], out["max"] = ch_min.cpu().numpy(), ch_max.cpu().numpy()
+        # the one-call form must write the same four vectors, bit for bit
+        four = [torch.full((c,), float("nan"), **f32) for _ in range(4)]
+        G.granq_calibrate(x, bits, four[0], four[1], four[2], four[3], ws, desc=d)
+        for got, ref, name in zip(four, (ch_min, ch_max, s, z), ("min", "max", "scale", "zero_point")):
+            assert torch.equal(got.view(torch.int32), ref.view(torch.int32)), "granq_calibrate: " + name
     else:
         s = torch.as_tensor(scale, **f32)
         z = torch.as_tensor(zero_point, **f32)

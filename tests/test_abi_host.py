@@ -79,6 +79,18 @@ def test_argument_validation_happens_before_any_gpu_work():
     assert lib.granq_range_reduce(16, ctypes.byref(good), 16, 16, 0, need, 0) == G.GRANQ_ERR_WORKSPACE
     assert lib.granq_range_reduce(16, ctypes.byref(good), 16, 16, 16, need - 1, 0) == G.GRANQ_ERR_WORKSPACE
     assert lib.granq_range_reduce(16, ctypes.byref(good), 16, 16, 20, need, 0) == G.GRANQ_ERR_WORKSPACE
+    # the one-call calibration: same checks as the two calls it stands for
+    cal = lambda x=16, bits=4, mn=16, mx=16, s=16, z=16, ws=16, nb=need: lib.granq_calibrate(
+        x, ctypes.byref(good), bits, mn, mx, s, z, ws, nb, 0)
+    for bits in (0, 9):
+        assert cal(bits=bits) == G.GRANQ_ERR_INVALID_ARG
+    assert cal(x=0) == G.GRANQ_ERR_INVALID_ARG
+    assert cal(mn=0) == G.GRANQ_ERR_INVALID_ARG
+    assert cal(s=0) == G.GRANQ_ERR_INVALID_ARG
+    assert cal(z=0) == G.GRANQ_ERR_INVALID_ARG
+    assert cal(z=18) == G.GRANQ_ERR_UNSUPPORTED
+    assert cal(ws=0) == G.GRANQ_ERR_WORKSPACE
+    assert cal(nb=need - 1) == G.GRANQ_ERR_WORKSPACE
     out = ctypes.c_size_t()
     assert lib.granq_workspace_bytes(ctypes.byref(good), None) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_workspace_bytes(None, ctypes.byref(out)) == G.GRANQ_ERR_INVALID_ARG
