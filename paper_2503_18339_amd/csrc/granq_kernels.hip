@@ -203,6 +203,23 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
 #ifndef GRANQ_MASK_NT
 #define GRANQ_MASK_NT 0
 #endif
+// Shape of a block of the forward that also writes gate bits: vectors per lane
+// along the row and rows.  A wavefront's bits for one row are contiguous:
+// 32 bytes per float32 vector slot, 64 per bfloat16 one.
+// Measured on the 822 MB tensor: float32 2 x 1 costs 14 us more than the plain
+// forward, 1 x 2 costs 22, 4 x 1 costs 39; bfloat16 1 x 2 and 2 x 1 cost 11-13.
+#ifndef GRANQ_M_V_F32
+#define GRANQ_M_V_F32 2
+#endif
+#ifndef GRANQ_M_ROWS_F32
+#define GRANQ_M_ROWS_F32 1
+#endif
+#ifndef GRANQ_M_V_BF16
+#define GRANQ_M_V_BF16 1
+#endif
+#ifndef GRANQ_M_ROWS_BF16
+#define GRANQ_M_ROWS_BF16 2
+#endif
 __device__ inline void store_mask_byte(uint8_t *p, uint8_t v) {
 #if GRANQ_MASK_NT
     __builtin_nontemporal_store(v, p);
@@ -805,6 +822,14 @@ static ColPlan fwd_plan(const granq_desc_t *d) {
     split_large(p, d);
     return p;
 }
+static ColPlan fwd_mask_plan(const granq_desc_t *d) {
+    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
+                              d->dtype == GRANQ_F32 ? GRANQ_M_V_F32 : GRANQ_M_V_BF16, kEBlock,
+                              (int64_t)1 << 40,
+                              d->dtype == GRANQ_F32 ? GRANQ_M_ROWS_F32 : GRANQ_M_ROWS_BF16);
+    split_large(p, d);
+    return p;
+}
 static ColPlan bwd_plan(const granq_desc_t *d) {
     ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
                               d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kEBlock,
@@ -841,11 +866,22 @@ static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, void 
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
     if (kind == kCodes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
-    else if (kind == kMask) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kMask>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
     else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
 }
 
-// kind: kNoExtra, kCodes (extra = codes) or kMask (extra = gate bits)
+template <typename T, int V, int U>
+static void launch_fwd_mask_cols(const ColPlan &pl, const void *x, void *x_hat, void *mask,
+                                 const float *s, const float *z, float qmax, hipStream_t st) {
+    using vec_t = typename T::vec_t;
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
+    auto xv = (const vec_t *)x;
+    auto yv = (vec_t *)x_hat;
+    if (pl.mode == kOne) hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kOne, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
+    else if (pl.mode == kTwo) hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kTwo, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
+    else hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kEach, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
+}
+
+// kind: kNoExtra or kCodes (extra = codes)
 template <typename T, int V>
 static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, void *extra, int kind,
                             const float *s, const float *z, float qmax, hipStream_t st) {
@@ -1082,7 +1118,7 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
 // The vectorised mask kernels need whole bytes per lane pair: rows that are a multiple of
 // eight elements (and, as everywhere, 16-byte vectors).
 static bool mask_vector_ok(const ColPlan &cp) {
-    return cp.ok && cp.row_len % 8 == 0 && GRANQ_E_V_F32 == 1 && GRANQ_E_V_BF16 == 1;
+    return cp.ok && cp.row_len % 8 == 0;
 }
 
 granq_status_t granq_mask_bytes(const granq_desc_t *desc, size_t *bytes_out) {
@@ -1105,10 +1141,10 @@ granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc,
         return GRANQ_ERR_UNSUPPORTED;
     const float qmax = (float)((1 << bits) - 1);
     hipStream_t hs = (hipStream_t)stream;
-    ColPlan cp = fwd_plan(desc);
+    ColPlan cp = fwd_mask_plan(desc);
     if (mask_vector_ok(cp) && aligned16(x) && aligned16(x_hat)) {
-        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, mask, kMask, scale, zero_point, qmax, hs);
-        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, mask, kMask, scale, zero_point, qmax, hs);
+        if (desc->dtype == GRANQ_F32) launch_fwd_mask_cols<F32, GRANQ_M_V_F32, GRANQ_M_ROWS_F32>(cp, x, x_hat, mask, scale, zero_point, qmax, hs);
+        else launch_fwd_mask_cols<BF16, GRANQ_M_V_BF16, GRANQ_M_ROWS_BF16>(cp, x, x_hat, mask, scale, zero_point, qmax, hs);
         return launched();
     }
     // any other shape or alignment: gate bits from x first (x_hat may alias x), then the forward
@@ -1133,7 +1169,8 @@ granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask, con
     if (!aligned_elem(dy, desc->dtype) || !aligned_elem(dx, desc->dtype)) return GRANQ_ERR_UNSUPPORTED;
     hipStream_t hs = (hipStream_t)stream;
     ColPlan cp = bwd_plan(desc);
-    if (mask_vector_ok(cp) && aligned16(dy) && aligned16(dx)) {
+    // fq_bwd_mask_cols handles one vector per lane
+    if (mask_vector_ok(cp) && GRANQ_E_V_F32 == 1 && GRANQ_E_V_BF16 == 1 && aligned16(dy) && aligned16(dx)) {
         dim3 grid((uint32_t)cp.col_tiles, (uint32_t)cp.row_groups), block(kEBlock);
         const bool nt = cp.nt_row_end > 0;
         if (desc->dtype == GRANQ_F32) {
