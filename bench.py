@@ -342,34 +342,44 @@ def distortion_table(wl, device):
 
 
 def integer_accumulation(wl, bits, device):
-    """The 1x1 convolution that consumes the quantized activations, 64 -> 64 channels on
-    256x64x56x56: from the integer codes on the int8 matrix cores (Eq. 3, scale folded into the
-    weights) against torch's float convolution on x_hat (Eq. 6)."""
-    shape = (wl.batch, 64, 56, 56)
-    x = workloads.make_activation(shape, "relu", wl.sigma, 1, device)
-    q = G.ActivationQuantizer(shape, torch.float32, bits, device)
-    xh = torch.empty_like(x)
-    codes = torch.empty(shape, dtype=torch.uint8, device=device)
+    """The 1x1 convolution that consumes the quantized activations, on ResNet bottleneck shapes
+    at batch 256: from the integer codes on the int8 matrix cores (Eq. 3, scale folded into the
+    weights) against torch's float32 and bfloat16 convolutions on x_hat (Eq. 6)."""
     stream = torch.cuda.current_stream()
-    q.forward(x, xh, codes, stream)
-    o = 64
-    wt = workloads.make_weight((o, 64, 1, 1), 3, device)
-    wq = torch.empty(o, 64, dtype=torch.int8, device=device)
-    corr = torch.empty(o, dtype=torch.int32, device=device)
-    a = torch.empty(o, device=device)
-    y = torch.empty(shape[0], o, 56, 56, device=device)
-    t_fold = _timeit(lambda: G.granq_fold_weights(wt, q.scale, q.zero_point, wq, corr, a, stream))
-    t_int = _timeit(lambda: G.granq_conv1x1_int8(codes, wq, corr, a, bits, y, stream))
-    t_f32 = _timeit(lambda: torch.nn.functional.conv2d(xh, wt))
-    ref = torch.nn.functional.conv2d(xh, wt)
-    rel = float((y - ref).norm() / ref.norm())
-    e = x.numel()
-    ops = 2.0 * o * 64 * shape[0] * 56 * 56
-    return {"int8_mfma_from_codes_us": round(t_int, 1), "int8_GBs": round((e + y.numel() * 4) / t_int / 1e3, 1),
+    rows = {}
+    for c, o, hw in ((64, 64, 56), (64, 256, 56), (256, 64, 56), (1024, 256, 14)):
+        shape = (wl.batch, c, hw, hw)
+        x = workloads.make_activation(shape, "relu", wl.sigma, 1, device)
+        q = G.ActivationQuantizer(shape, torch.float32, bits, device)
+        xh = torch.empty_like(x)
+        codes = torch.empty(shape, dtype=torch.uint8, device=device)
+        q.forward(x, xh, codes, stream)
+        del x
+        wt = workloads.make_weight((o, c, 1, 1), 3, device)
+        wq = torch.empty(o, c, dtype=torch.int8, device=device)
+        corr = torch.empty(o, dtype=torch.int32, device=device)
+        a = torch.empty(o, device=device)
+        y = torch.empty(shape[0], o, hw, hw, device=device)
+        t_fold = _timeit(lambda: G.granq_fold_weights(wt, q.scale, q.zero_point, wq, corr, a, stream))
+        t_int = _timeit(lambda: G.granq_conv1x1_int8(codes, wq, corr, a, bits, y, stream))
+        t_f32 = _timeit(lambda: torch.nn.functional.conv2d(xh, wt))
+        ref = torch.nn.functional.conv2d(xh, wt)
+        rel = float((y - ref).norm() / ref.norm())
+        del ref
+        xh16, wt16 = xh.to(torch.bfloat16), wt.to(torch.bfloat16)
+        t_b16 = _timeit(lambda: torch.nn.functional.conv2d(xh16, wt16))
+        e = codes.numel()
+        ops = 2.0 * o * c * shape[0] * hw * hw
+        rows["%d->%d@%dx%d" % (c, o, hw, hw)] = {
+            "int8_mfma_from_codes_us": round(t_int, 1), "int8_GBs": round((e + y.numel() * 4) / t_int / 1e3, 1),
             "int8_TOPs": round(ops / t_int / 1e6, 2), "fold_weights_us": round(t_fold, 1),
-            "torch_f32_conv_on_x_hat_us": round(t_f32, 1),
-            "relative_difference_to_float_conv": round(rel, 5),
-            "note": "int8 path reads 1 byte per activation and writes float32; the float path reads 4"}
+            "torch_f32_conv_on_x_hat_us": round(t_f32, 1), "torch_bf16_conv_on_bf16_x_hat_us": round(t_b16, 1),
+            "relative_difference_to_float_conv": round(rel, 5)}
+        del xh, xh16, codes, y
+        torch.cuda.empty_cache()
+    rows["note"] = ("int8 path reads 1 byte per activation and writes float32; torch float32 reads 4 and "
+                    "writes 4, torch bfloat16 reads 2 and writes 2")
+    return rows
 
 
 def cpu_baseline(wl, bits, sample_batch, min_seconds=10.0, max_passes=8):
@@ -551,7 +561,7 @@ def main():
             torch.cuda.empty_cache()
         extra["other_dtypes_bits"] = others
         extra["comparison_points"] = comparison_points(wl, args.bits, device)
-        extra["integer_accumulation_256x64x56x56"] = integer_accumulation(wl, args.bits, device)
+        extra["integer_accumulation_1x1_batch256"] = integer_accumulation(wl, args.bits, device)
         extra["distortion_3bit"] = distortion_table(wl, device)
         extra["resnet18_weights_channelwise"] = weight_quantization(args.bits, device)
         extra["gate_bit_variant"] = gate_bit_variant(wl, dtype, args.bits, device, args.steps, args.warmup)

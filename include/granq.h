@@ -278,8 +278,8 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc,
  * granq_conv1x1_int8: codes [in] N*C*H*W bytes as written by granq_fakequant_fwd (desc
  * gives n, c, h, w; its dtype is ignored); y [out] N*O*H*W floats, NCHW with O channels.
  * The matrix-core kernel needs codes <= 127 (bits <= 7), C a multiple of 16, O a multiple
- * of 32, H*W a multiple of 4 and 16-byte aligned y; anything else runs a plain integer
- * kernel with identical results.
+ * of 32, H*W a multiple of 4, C*H*W < 2^25, 4-byte aligned codes and 16-byte aligned wq
+ * and y; anything else runs a plain integer kernel with identical results.
  */
 granq_status_t granq_fold_weights(const float *w, const float *scale, const float *zero_point,
                                   int64_t o, int64_t c, int8_t *wq, int32_t *corr,

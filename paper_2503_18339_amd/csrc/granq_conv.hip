@@ -4,16 +4,18 @@
 // once per output channel).
 //
 // Per sample the product is  D[O x HW] = Wq[O x C] . code[C x HW], int8 x int8 ->
-// int32 with v_mfma_i32_32x32x16_i8.  A wavefront owns 128 consecutive pixels and
-// all output channels.  Operand layout of the instruction (64 lanes, lane l):
-//   A (32 x 16): row l % 32, eight consecutive k starting at 8 * (l / 32), one byte each
-//   B (16 x 32): column l % 32, the same eight k
+// int32 with v_mfma_i32_32x32x32_i8.  Operand layout of the instruction (64 lanes,
+// lane l; checked on the device against an integer matrix product):
+//   A (32 x 32): row l % 32, sixteen consecutive k starting at 16 * (l / 32), one byte each
+//   B (32 x 32): column l % 32, the same sixteen k
 //   D (32 x 32): column l % 32, register r holds row 8 * (r / 4) + 4 * (l / 32) + r % 4
 // The codes are NCHW, so consecutive k (channels) of one pixel are H*W bytes
-// apart: a lane loads, for its eight channels, one dword (four neighbouring
-// pixels) each and transposes the 8 x 4 bytes in registers into four B operands;
-// MFMA j of a group therefore covers pixels 4 * (l % 32) + j, and a lane ends up
-// with four neighbouring pixels of every output row: one 16-byte store per row.
+// apart: a lane loads, for its sixteen channels, one dword (four neighbouring
+// pixels) each and transposes the 16 x 4 bytes in registers (v_perm_b32) into
+// four B operands; MFMA j of a group therefore covers pixels 4 * (l % 32) + j,
+// and a lane ends up with four neighbouring pixels of every output row: one
+// 16-byte store per row.  The weights of the block's 64 output channels are
+// staged in LDS and shared by its four wavefronts.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -23,67 +25,141 @@
 namespace granq {
 
 typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// OT = output-channel tiles of 32 handled by one wavefront.
-template <int OT>
-__global__ __launch_bounds__(kBlock) void conv1x1_i8_mfma(
+constexpr int kConvOT = 2;                 // 32-channel output tiles per sweep
+constexpr int kConvRows = 32 * kConvOT;    // output channels per sweep
+constexpr int kConvKChunk = 512;           // channels staged in LDS at a time
+#ifndef GRANQ_CONV_TARGET_BLOCKS
+#define GRANQ_CONV_TARGET_BLOCKS 6000
+#endif
+constexpr int kConvPad = 16;               // bytes between LDS rows: 16-byte reads of 32 rows spread over all banks
+
+// dword i of `d` holds four neighbouring pixels of channel i; the result's dword q of
+// operand j holds channels 4q .. 4q+3 of pixel j.
+__device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&b)[4]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t d0 = d[4 * q], d1 = d[4 * q + 1], d2 = d[4 * q + 2], d3 = d[4 * q + 3];
+        // v_perm_b32(hi, lo, sel): selector bytes 0..3 pick bytes of lo, 4..7 bytes of hi
+        const uint32_t p01 = __builtin_amdgcn_perm(d1, d0, 0x05010400u);   // pixels 0,1 of channels 0,1
+        const uint32_t q01 = __builtin_amdgcn_perm(d1, d0, 0x07030602u);   // pixels 2,3 of channels 0,1
+        const uint32_t p23 = __builtin_amdgcn_perm(d3, d2, 0x05010400u);
+        const uint32_t q23 = __builtin_amdgcn_perm(d3, d2, 0x07030602u);
+        b[0][q] = (int)__builtin_amdgcn_perm(p23, p01, 0x05040100u);
+        b[1][q] = (int)__builtin_amdgcn_perm(p23, p01, 0x07060302u);
+        b[2][q] = (int)__builtin_amdgcn_perm(q23, q01, 0x05040100u);
+        b[3][q] = (int)__builtin_amdgcn_perm(q23, q01, 0x07060302u);
+    }
+}
+
+// A wavefront owns 128 pixels (32 groups of four neighbouring pixels of one sample;
+// groups are numbered through the whole batch, so only the batch's last wavefront
+// is ragged); a block's four wavefronts share a range of "sweeps" of 64 output
+// channels.  blockIdx.y splits the sweeps when the pixels alone do not give enough
+// blocks to fill the chip; within a block the codes of later sweeps come from the
+// caches.  The channel loop is software-pipelined: the loads of the next 32
+// channels are issued before the matrix instructions of the current ones.
+__global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
     const float *__restrict__ out_scale, float *__restrict__ y, int64_t c, int64_t hw, int64_t o,
-    int64_t o_base)
+    int64_t groups_total, int32_t sweeps_per_block, int32_t lds_stride)
 {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_w[];   // kConvRows x lds_stride bytes
     const int lane = threadIdx.x & (kWave - 1);
     const int half = lane / 32, col = lane % 32;
-    const int64_t n = blockIdx.y;
-    const int64_t pb = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * 128 + 4 * col;
-    const bool live = pb < hw;                         // hw % 4 == 0: a lane's four pixels are all in or all out
+    const int64_t g = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * 32 + col;
+    const bool live = g < groups_total;
+    const bool wave_live = __any(live);                // a dead wavefront only keeps the barriers
+    const int64_t hw4 = hw / 4;                        // hw % 4 == 0 on this path
+    const int64_t n = live ? g / hw4 : 0;
+    const int64_t pb = live ? 4 * (g - n * hw4) : 0;
+    // addresses of the codes = wave-uniform base (scalar registers) + one 32-bit lane offset:
+    // the wavefront's lanes lie within 33 samples of its first lane's sample (C*H*W < 2^25 here)
+    const int64_t g_first = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * 32;
+    const int64_t n_first = g_first < groups_total ? g_first / hw4 : 0;     // wave-uniform
+    const uint8_t *wave_base = codes + n_first * c * hw;
+    const uint32_t lane_off = live ? (uint32_t)((n - n_first) * c * hw + pb + 16 * half * hw) : 0u;
 
-    i32x16 acc[OT][4];
-#pragma unroll
-    for (int t = 0; t < OT; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][j][r] = 0;
+    const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
+    const int64_t s0 = (int64_t)blockIdx.y * sweeps_per_block;
+    const int64_t s1 = s0 + sweeps_per_block < sweeps ? s0 + sweeps_per_block : sweeps;
 
-    const uint8_t *src = codes + (n * c + 8 * half) * hw + (live ? pb : 0);
-    for (int64_t k0 = 0; k0 < c; k0 += 16) {
-        uint32_t d[8];
+    for (int64_t sw = s0; sw < s1; ++sw) {
+        const int64_t o_base = sw * kConvRows;
+        i32x16 acc[kConvOT][4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) d[i] = live ? *(const uint32_t *)(src + (k0 + i) * hw) : 0u;
-        long b[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {                  // byte j of each of the eight dwords
-            uint32_t lo = 0, hi = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lo |= ((d[i] >> (8 * j)) & 0xFFu) << (8 * i);
-                hi |= ((d[4 + i] >> (8 * j)) & 0xFFu) << (8 * i);
-            }
-            b[j] = (long)(((uint64_t)hi << 32) | lo);
-        }
-#pragma unroll
-        for (int t = 0; t < OT; ++t) {
-            const long a = *(const long *)(wq + (o_base + 32 * t + col) * c + k0 + 8 * half);
+        for (int t = 0; t < kConvOT; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                acc[t][j] = __builtin_amdgcn_mfma_i32_32x32x16_i8(a, b[j], acc[t][j], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][j][r] = 0;
+
+        for (int64_t kc0 = 0; kc0 < c; kc0 += kConvKChunk) {
+            const int32_t kcn = (int32_t)(c - kc0 < kConvKChunk ? c - kc0 : kConvKChunk);   // multiple of 16
+            const int32_t kcr = (kcn + 31) / 32 * 32;
+            __syncthreads();                           // the previous chunk's readers are done
+            // stage Wq[o_base .. o_base+63][kc0 .. kc0+kcn) in 16-byte segments; rows past O and
+            // channels past C read as zero
+            const int32_t segs = kcr / 16;
+            for (int32_t idx = threadIdx.x; idx < kConvRows * segs; idx += kBlock) {
+                const int32_t row = idx / segs, seg = idx - row * segs;
+                i32x4 v = {0, 0, 0, 0};
+                if (o_base + row < o && seg * 16 < kcn)
+                    v = *(const i32x4 *)(wq + (o_base + row) * c + kc0 + seg * 16);
+                *(i32x4 *)(lds_w + row * lds_stride + seg * 16) = v;
+            }
+            __syncthreads();
+            if (!wave_live) continue;
+
+            const uint8_t *a_row0 = lds_w + col * lds_stride + 16 * half;
+            const uint8_t *a_row1 = lds_w + (32 + col) * lds_stride + 16 * half;
+            uint32_t d0[16];
+            // this lane's sixteen channels of the 32-channel step that starts at chunk offset k
+#define GRANQ_CONV_FETCH(d, k)                                                              \
+            {                                                                                \
+                const int64_t ch0 = kc0 + (k);             /* wave-uniform */                \
+                const bool ok = live && ch0 + 16 * half < c;                                 \
+                const uint8_t *step_base = wave_base + ch0 * hw;                             \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i)                               \
+                    d[i] = ok ? *(const uint32_t *)(step_base + i * hw + lane_off) : 0u;     \
+            }
+#define GRANQ_CONV_MULTIPLY(d, k)                                                            \
+            {                                                                                \
+                i32x4 b[4];                                                                  \
+                transpose_16x4(d, b);                                                        \
+                const i32x4 a0 = *(const i32x4 *)(a_row0 + (k));                             \
+                const i32x4 a1 = *(const i32x4 *)(a_row1 + (k));                             \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
+                    acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b[j], acc[0][j], 0, 0, 0); \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
+                    acc[1][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b[j], acc[1][j], 0, 0, 0); \
+            }
+            for (int32_t k = 0; k < kcr; k += 32) {
+                GRANQ_CONV_FETCH(d0, k)
+                GRANQ_CONV_MULTIPLY(d0, k)
+            }
+#undef GRANQ_CONV_FETCH
+#undef GRANQ_CONV_MULTIPLY
+        }
+        if (!live) continue;
+#pragma unroll
+        for (int t = 0; t < kConvOT; ++t) {
+            if (o_base + 32 * t >= o) break;           // wave-uniform: o is a multiple of 32
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+                const int32_t cz = corr[oc];
+                const float sc = out_scale[oc];
+                f32x4 v;
+                v.x = sc * (float)(acc[t][0][r] - cz);
+                v.y = sc * (float)(acc[t][1][r] - cz);
+                v.z = sc * (float)(acc[t][2][r] - cz);
+                v.w = sc * (float)(acc[t][3][r] - cz);
+                __builtin_nontemporal_store(v, (f32x4 *)(y + (n * o + oc) * hw + pb));
+            }
         }
     }
-    if (!live) return;
-#pragma unroll
-    for (int t = 0; t < OT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
-            const int32_t cz = corr[oc];
-            const float a = out_scale[oc];
-            f32x4 v;
-            v.x = a * (float)(acc[t][0][r] - cz);
-            v.y = a * (float)(acc[t][1][r] - cz);
-            v.z = a * (float)(acc[t][2][r] - cz);
-            v.w = a * (float)(acc[t][3][r] - cz);
-            __builtin_nontemporal_store(v, (f32x4 *)(y + (n * o + oc) * hw + pb));
-        }
 }
 
 // Any shape: one thread per output element, integer loop over the channels.
@@ -174,21 +250,26 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
     if (c >= ((int64_t)1 << 16) || o >= 65536 || n >= 65536 || hw >= ((int64_t)1 << 40)) return GRANQ_ERR_UNSUPPORTED;
     if (((uintptr_t)corr & 3u) || ((uintptr_t)out_scale & 3u) || ((uintptr_t)y & 3u)) return GRANQ_ERR_UNSUPPORTED;
     hipStream_t hs = (hipStream_t)stream;
-    const bool mfma = bits <= 7 && c % 16 == 0 && o % 32 == 0 && hw % 4 == 0 &&
-                      ((uintptr_t)codes & 3u) == 0 && ((uintptr_t)wq & 7u) == 0 && ((uintptr_t)y & 15u) == 0;
+    const bool mfma = bits <= 7 && c % 16 == 0 && o % 32 == 0 && hw % 4 == 0 && c * hw < ((int64_t)1 << 25) &&
+                      ((uintptr_t)codes & 3u) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & 15u) == 0;
     if (mfma) {
-        dim3 grid((uint32_t)((hw + 128 * (kBlock / kWave) - 1) / (128 * (kBlock / kWave))), (uint32_t)n), block(kBlock);
-        int64_t ob = 0;
-        while (ob < o) {                               // 64 output channels per launch, then 32
-            if (o - ob >= 64) {
-                hipLaunchKernelGGL(conv1x1_i8_mfma<2>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o, ob);
-                ob += 64;
-            } else {
-                hipLaunchKernelGGL(conv1x1_i8_mfma<1>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o, ob);
-                ob += 32;
-            }
-            if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
-        }
+        const int64_t groups_total = n * (hw / 4);
+        const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));
+        const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
+        // split the sweeps over blockIdx.y until the launch has about this many blocks
+        int64_t gy = (GRANQ_CONV_TARGET_BLOCKS + gx - 1) / gx;
+        if (gy > sweeps) gy = sweeps;
+        if (gy < 1) gy = 1;
+        const int64_t spb = (sweeps + gy - 1) / gy;
+        gy = (sweeps + spb - 1) / spb;
+        if (gx >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
+        const int64_t kc = c < kConvKChunk ? (c + 31) / 32 * 32 : kConvKChunk;
+        const int32_t lds_stride = (int32_t)kc + kConvPad;
+        const size_t lds_bytes = (size_t)kConvRows * lds_stride;
+        dim3 grid((uint32_t)gx, (uint32_t)gy), block(kBlock);
+        hipLaunchKernelGGL(conv1x1_i8_mfma, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+                           groups_total, (int32_t)spb, lds_stride);
+        if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
         return GRANQ_OK;
     }
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)o, (uint32_t)n), block(kBlock);

@@ -44,6 +44,8 @@ def _case(shape, o, bits, law="linear", seed=0):
 @pytest.mark.parametrize("shape,o,bits", [
     ((2, 16, 8, 8), 32, 4), ((3, 64, 14, 14), 64, 4), ((2, 32, 7, 12), 96, 3), ((1, 128, 28, 28), 160, 5),
     ((4, 48, 2, 2), 32, 7), ((2, 64, 56, 56), 64, 4), ((1, 256, 1, 4), 64, 4), ((2, 16, 23, 12), 128, 2),
+    # more channels than one LDS chunk of weights (512), with a 16-channel tail; many samples per wavefront
+    ((2, 1040, 2, 4), 96, 4), ((1, 528, 4, 4), 64, 6), ((70, 32, 1, 4), 32, 4), ((3, 1024, 14, 14), 256, 4),
 ])
 def test_conv_mfma_path(shape, o, bits):
     _case(shape, o, bits)
