@@ -354,6 +354,7 @@ def integer_accumulation(wl, bits, device):
         xh = torch.empty_like(x)
         codes = torch.empty(shape, dtype=torch.uint8, device=device)
         q.forward(x, xh, codes, stream)
+        t_q = _timeit(lambda: G.granq_fakequant_fwd(x, q.scale, q.zero_point, bits, None, codes, stream, q.desc))
         del x
         wt = workloads.make_weight((o, c, 1, 1), 3, device)
         wq = torch.empty(o, c, dtype=torch.int8, device=device)
@@ -373,6 +374,7 @@ def integer_accumulation(wl, bits, device):
         rows["%d->%d@%dx%d" % (c, o, hw, hw)] = {
             "int8_mfma_from_codes_us": round(t_int, 1), "int8_GBs": round((e + y.numel() * 4) / t_int / 1e3, 1),
             "int8_TOPs": round(ops / t_int / 1e6, 2), "fold_weights_us": round(t_fold, 1),
+            "quantize_to_codes_only_us": round(t_q, 1), "quantize_GBs": round(e * 5 / t_q / 1e3, 1),
             "torch_f32_conv_on_x_hat_us": round(t_f32, 1), "torch_bf16_conv_on_bf16_x_hat_us": round(t_b16, 1),
             "relative_difference_to_float_conv": round(rel, 5)}
         del xh, xh16, codes, y

@@ -147,8 +147,11 @@ granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits
  * top of the range lands on a rounding tie or when scale / zero-point come
  * from another tensor.
  * x      [in]  device, desc elements
- * x_hat  [out] device, desc elements (may alias x: in-place)
- * codes  [out] device, N*C*H*W bytes holding q, or NULL to skip them
+ * x_hat  [out] device, desc elements (may alias x: in-place), or NULL when only the
+ *              codes are wanted (the quantize step alone: the input of the
+ *              integer-domain convolution below)
+ * codes  [out] device, N*C*H*W bytes holding q, or NULL to skip them; x_hat and
+ *              codes both NULL is GRANQ_ERR_INVALID_ARG
  */
 granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc,
                                    const float *scale, const float *zero_point,

@@ -210,10 +210,13 @@ def granq_calibrate(x: torch.Tensor, bits: int, ch_min: torch.Tensor, ch_max: to
 
 
 def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
-                        x_hat: torch.Tensor, codes: Optional[torch.Tensor] = None, stream=None,
+                        x_hat: Optional[torch.Tensor], codes: Optional[torch.Tensor] = None, stream=None,
                         desc: Optional[granq_desc_t] = None) -> None:
+    """x_hat None: only the codes are written (codes must then be given)."""
     d = desc or desc_of(x)
-    if x_hat.dtype != x.dtype or x_hat.numel() != x.numel():
+    if x_hat is None and codes is None:
+        raise ValueError("x_hat and codes are both None: nothing to write")
+    if x_hat is not None and (x_hat.dtype != x.dtype or x_hat.numel() != x.numel()):
         raise ValueError("x_hat must match x")
     cp = 0
     if codes is not None:
@@ -222,7 +225,8 @@ def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.
         cp = _dev(codes, "codes")
     _check(load().granq_fakequant_fwd(_dev(x, "x"), ctypes.byref(d), _vec(scale, d.c, "scale"),
                                       _vec(zero_point, d.c, "zero_point"), int(bits),
-                                      _dev(x_hat, "x_hat"), cp, _stream(stream)),
+                                      _dev(x_hat, "x_hat") if x_hat is not None else 0, cp,
+                                      _stream(stream)),
            "granq_fakequant_fwd")
 
 

@@ -234,6 +234,7 @@ constexpr int kCodes = 1;     // one byte per element: the clamped code q
 constexpr int kMask = 2;      // one bit per element: 1 where the clamp was inactive (the
                               // straight-through gate), bit (i & 7) of byte (i >> 3), i the
                               // flat NCHW index
+constexpr int kCodesOnly = 3; // the codes, and x_hat is not written at all
 
 template <typename T, int V, int U, int MODE, int EXTRA, bool FAST, bool NT>
 __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
@@ -264,11 +265,12 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
                     q[e] = clamp_code(code, qmax);
                     // the clamp left the code alone <=> 0 <= code <= qmax (-0 == +0; NaN fails)
                     if (EXTRA == kMask) gate_bits |= (code == q[e] ? 1u : 0u) << e;
-                    f[e] = dequant(q[e], c.s, c.z);
+                    if (EXTRA != kCodesOnly) f[e] = dequant(q[e], c.s, c.z);
                 }
                 const int64_t at = (r + u) * row_vecs + cv[v];
-                store_vec(x_hat + at, T::pack(f));
-                if (EXTRA == kCodes) store_vec((typename T::code_t *)extra + at, T::pack_codes(q));
+                if (EXTRA != kCodesOnly) store_vec(x_hat + at, T::pack(f));
+                if (EXTRA == kCodes || EXTRA == kCodesOnly)
+                    store_vec((typename T::code_t *)extra + at, T::pack_codes(q));
             }
             if (EXTRA == kMask && u < nrows) {         // wave-uniform condition: all lanes take part
                 // byte index of this lane's vector; VEC == 8: one byte per lane, VEC == 4: two
@@ -734,7 +736,7 @@ __global__ __launch_bounds__(kBlock) void fq_fwd_rows(
         const int64_t base = slab * hw;
         for (int64_t k = lane; k < hw; k += kWave) {
             float q = clamp_code(raw_code(T::load1(x, base + k), s, z), qmax);
-            T::store1(x_hat, base + k, dequant(q, s, z));
+            if (x_hat) T::store1(x_hat, base + k, dequant(q, s, z));
             if (codes) codes[base + k] = (uint8_t)q;
         }
     }
@@ -866,6 +868,7 @@ static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, void 
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
     if (kind == kCodes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else if (kind == kCodesOnly) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodesOnly>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
     else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
 }
 
@@ -881,7 +884,7 @@ static void launch_fwd_mask_cols(const ColPlan &pl, const void *x, void *x_hat, 
     else hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kEach, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
 }
 
-// kind: kNoExtra or kCodes (extra = codes)
+// kind: kNoExtra, kCodes (extra = codes) or kCodesOnly (extra = codes, x_hat unused)
 template <typename T, int V>
 static void launch_fwd_cols(const ColPlan &pl, const void *x, void *x_hat, void *extra, int kind,
                             const float *s, const float *z, float qmax, hipStream_t st) {
@@ -1062,9 +1065,10 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
                                    uint8_t *codes_or_null, void *stream) {
     granq_status_t st = check_desc(desc);
     if (st != GRANQ_OK) return st;
-    if (!x || !x_hat || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (!x || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (!x_hat && !codes_or_null) return GRANQ_ERR_INVALID_ARG;      // nothing to write
     if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
-    if (!aligned_elem(x, desc->dtype) || !aligned_elem(x_hat, desc->dtype) ||
+    if (!aligned_elem(x, desc->dtype) || (x_hat && !aligned_elem(x_hat, desc->dtype)) ||
         !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
         return GRANQ_ERR_UNSUPPORTED;
     const float qmax = (float)((1 << bits) - 1);
@@ -1072,9 +1076,10 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
     ColPlan cp = fwd_plan(desc);
     // packed codes are stored VEC bytes at a time
     const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
-    if (cp.ok && aligned16(x) && aligned16(x_hat) && codes_ok) {
-        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, codes_or_null ? kCodes : kNoExtra, scale, zero_point, qmax, hs);
-        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, codes_or_null ? kCodes : kNoExtra, scale, zero_point, qmax, hs);
+    if (cp.ok && aligned16(x) && (!x_hat || aligned16(x_hat)) && codes_ok) {
+        const int kind = !x_hat ? kCodesOnly : (codes_or_null ? kCodes : kNoExtra);
+        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
         return launched();
     }
     const int64_t hw = desc->h * desc->w;

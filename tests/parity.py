@@ -99,6 +99,10 @@ def gpu_path(x: torch.Tensor, bits: int, dy: torch.Tensor = None, want_codes=Tru
     out["xhat"] = to_numpy(x_hat)
     if want_codes:
         out["codes"] = codes.cpu().numpy()
+        # the quantize step alone (no x_hat) must write the same codes
+        only = torch.full(x.shape, 254, dtype=torch.uint8, device=dev)
+        G.granq_fakequant_fwd(x, s, z, bits, None, only, desc=d)
+        assert torch.equal(only, codes), "codes-only forward differs from the forward with x_hat"
     if dy is not None:
         dx = torch.empty_like(x)
         G.granq_fakequant_bwd(x, dy, s, z, bits, dx, desc=d)

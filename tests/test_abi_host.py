@@ -58,7 +58,8 @@ def test_argument_validation_happens_before_any_gpu_work():
     # null pointers
     assert _call_fwd(lib, good, x=0) == G.GRANQ_ERR_INVALID_ARG
     assert _call_fwd(lib, good, s=0) == G.GRANQ_ERR_INVALID_ARG
-    assert _call_fwd(lib, good, out=0) == G.GRANQ_ERR_INVALID_ARG
+    assert _call_fwd(lib, good, out=0) == G.GRANQ_ERR_INVALID_ARG           # neither x_hat nor codes
+    assert _call_fwd(lib, good, out=0, codes=16, x=0) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_fakequant_bwd(16, 0, ctypes.byref(good), 16, 16, 4, 16, 0) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_prescale(0, 16, 3, 4, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_range_reduce(0, ctypes.byref(good), 16, 16, 16, 1 << 20, 0) == G.GRANQ_ERR_INVALID_ARG
