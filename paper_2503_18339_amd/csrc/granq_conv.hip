@@ -29,6 +29,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kConvOT = 2;                 // 32-channel output tiles per sweep
 constexpr int kConvRows = 32 * kConvOT;    // output channels per sweep
+
 constexpr int kConvKChunk = 512;           // channels staged in LDS at a time
 #ifndef GRANQ_CONV_TARGET_BLOCKS
 #define GRANQ_CONV_TARGET_BLOCKS 6000
@@ -58,8 +59,9 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // is ragged); a block's four wavefronts share a range of "sweeps" of 64 output
 // channels.  blockIdx.y splits the sweeps when the pixels alone do not give enough
 // blocks to fill the chip; within a block the codes of later sweeps come from the
-// caches.  The channel loop is software-pipelined: the loads of the next 32
-// channels are issued before the matrix instructions of the current ones.
+// caches.  The channel loop is software-pipelined by hand: the loads of the next 32
+// channels are issued before the matrix instructions of the current ones, and
+// scheduling barriers keep them there.
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
     const float *__restrict__ out_scale, float *__restrict__ y, int64_t c, int64_t hw, int64_t o,
@@ -68,7 +70,10 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_w[];   // kConvRows x lds_stride bytes
     const int lane = threadIdx.x & (kWave - 1);
     const int half = lane / 32, col = lane % 32;
-    const int64_t g = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * 32 + col;
+    // the wavefront's index, in a scalar register: everything derived from it is wave-uniform
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const int64_t g_first = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * 32;
+    const int64_t g = g_first + col;
     const bool live = g < groups_total;
     const bool wave_live = __any(live);                // a dead wavefront only keeps the barriers
     const int64_t hw4 = hw / 4;                        // hw % 4 == 0 on this path
@@ -76,9 +81,11 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const int64_t pb = live ? 4 * (g - n * hw4) : 0;
     // addresses of the codes = wave-uniform base (scalar registers) + one 32-bit lane offset:
     // the wavefront's lanes lie within 33 samples of its first lane's sample (C*H*W < 2^25 here)
-    const int64_t g_first = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * 32;
-    const int64_t n_first = g_first < groups_total ? g_first / hw4 : 0;     // wave-uniform
-    const uint8_t *wave_base = codes + n_first * c * hw;
+    const int64_t n_first = g_first < groups_total ? g_first / hw4 : 0;
+    // raw buffer over the codes from the wavefront's first sample on: loads take the form
+    // resource (scalar) + channel offset (scalar) + lane offset (one vector register)
+    const __amdgpu_buffer_rsrc_t code_buf = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(codes + n_first * c * hw), 0, 0x7fffffff, 0x00020000);
     const uint32_t lane_off = live ? (uint32_t)((n - n_first) * c * hw + pb + 16 * half * hw) : 0u;
 
     const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
@@ -97,7 +104,7 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
 
         for (int64_t kc0 = 0; kc0 < c; kc0 += kConvKChunk) {
             const int32_t kcn = (int32_t)(c - kc0 < kConvKChunk ? c - kc0 : kConvKChunk);   // multiple of 16
-            const int32_t kcr = (kcn + 31) / 32 * 32;
+            const int32_t kcr = (kcn + 63) / 64 * 64;  // the channel loop takes two 32-channel steps at a time
             __syncthreads();                           // the previous chunk's readers are done
             // stage Wq[o_base .. o_base+63][kc0 .. kc0+kcn) in 16-byte segments; rows past O and
             // channels past C read as zero
@@ -114,30 +121,46 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
 
             const uint8_t *a_row0 = lds_w + col * lds_stride + 16 * half;
             const uint8_t *a_row1 = lds_w + (32 + col) * lds_stride + 16 * half;
-            uint32_t d0[16];
-            // this lane's sixteen channels of the 32-channel step that starts at chunk offset k
+            uint32_t d0[16], d1[16];
+            // Issue the loads of this lane's sixteen channels of the 32-channel step at chunk
+            // offset k.  Every lane loads, always: a lane or step without work (ragged last
+            // wavefront, channels past C) reads in-bounds bytes that the multiply discards, so
+            // the loop body is free of branches and the loads stay in flight across it.
 #define GRANQ_CONV_FETCH(d, k)                                                              \
             {                                                                                \
                 const int64_t ch0 = kc0 + (k);             /* wave-uniform */                \
                 const bool ok = live && ch0 + 16 * half < c;                                 \
-                const uint8_t *step_base = wave_base + ch0 * hw;                             \
+                const int off = (int)(ok ? lane_off : 0u);                                   \
+                const int64_t ch0c = ch0 < c - 16 ? ch0 : c - 16;                            \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i)                               \
-                    d[i] = ok ? *(const uint32_t *)(step_base + i * hw + lane_off) : 0u;     \
+                    d[i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(                   \
+                        code_buf, off, (int)((ch0c + i) * hw), 0);                           \
             }
 #define GRANQ_CONV_MULTIPLY(d, k)                                                            \
             {                                                                                \
+                const bool ok = live && kc0 + (k) + 16 * half < c;                           \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i)                               \
+                    d[i] = ok ? d[i] : 0u;                                                   \
                 i32x4 b[4];                                                                  \
                 transpose_16x4(d, b);                                                        \
                 const i32x4 a0 = *(const i32x4 *)(a_row0 + (k));                             \
-                const i32x4 a1 = *(const i32x4 *)(a_row1 + (k));                             \
                 _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
                     acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b[j], acc[0][j], 0, 0, 0); \
+                const i32x4 a1 = *(const i32x4 *)(a_row1 + (k));                             \
                 _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
                     acc[1][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b[j], acc[1][j], 0, 0, 0); \
             }
-            for (int32_t k = 0; k < kcr; k += 32) {
-                GRANQ_CONV_FETCH(d0, k)
+            // the scheduling barriers keep each batch of loads ahead of the multiply before it
+            GRANQ_CONV_FETCH(d0, 0)
+            for (int32_t k = 0; k < kcr; k += 64) {
+                GRANQ_CONV_FETCH(d1, k + 32)
+                __builtin_amdgcn_sched_barrier(0);
                 GRANQ_CONV_MULTIPLY(d0, k)
+                __builtin_amdgcn_sched_barrier(0);
+                GRANQ_CONV_FETCH(d0, k + 64)               // past the chunk in the last round: discarded
+                __builtin_amdgcn_sched_barrier(0);
+                GRANQ_CONV_MULTIPLY(d1, k + 32)
+                __builtin_amdgcn_sched_barrier(0);
             }
 #undef GRANQ_CONV_FETCH
 #undef GRANQ_CONV_MULTIPLY
@@ -255,6 +278,7 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
     if (mfma) {
         const int64_t groups_total = n * (hw / 4);
         const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));
+        if (gx >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
         // split the sweeps over blockIdx.y until the launch has about this many blocks
         int64_t gy = (GRANQ_CONV_TARGET_BLOCKS + gx - 1) / gx;
@@ -262,8 +286,7 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
         if (gy < 1) gy = 1;
         const int64_t spb = (sweeps + gy - 1) / gy;
         gy = (sweeps + spb - 1) / spb;
-        if (gx >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
-        const int64_t kc = c < kConvKChunk ? (c + 31) / 32 * 32 : kConvKChunk;
+        const int64_t kc = c < kConvKChunk ? (c + 63) / 64 * 64 : kConvKChunk;
         const int32_t lds_stride = (int32_t)kc + kConvPad;
         const size_t lds_bytes = (size_t)kConvRows * lds_stride;
         dim3 grid((uint32_t)gx, (uint32_t)gy), block(kBlock);
