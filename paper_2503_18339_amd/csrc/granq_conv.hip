@@ -30,10 +30,12 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kConvOT = 2;                 // 32-channel output tiles per sweep
 constexpr int kConvRows = 32 * kConvOT;    // output channels per sweep
 
+
 constexpr int kConvKChunk = 512;           // channels staged in LDS at a time
 #ifndef GRANQ_CONV_TARGET_BLOCKS
 #define GRANQ_CONV_TARGET_BLOCKS 6000
 #endif
+constexpr int kConvDies = 8;               // XCDs of the chip
 constexpr int kConvPad = 16;               // bytes between LDS rows: 16-byte reads of 32 rows spread over all banks
 
 // dword i of `d` holds four neighbouring pixels of channel i; the result's dword q of
@@ -57,22 +59,29 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // A wavefront owns 128 pixels (32 groups of four neighbouring pixels of one sample;
 // groups are numbered through the whole batch, so only the batch's last wavefront
 // is ragged); a block's four wavefronts share a range of "sweeps" of 64 output
-// channels.  blockIdx.y splits the sweeps when the pixels alone do not give enough
-// blocks to fill the chip; within a block the codes of later sweeps come from the
-// caches.  The channel loop is software-pipelined by hand: the loads of the next 32
+// channels.  The sweeps are split over several blocks when the pixels alone do not
+// give enough blocks to fill the chip; within a block the codes of later sweeps come
+// from the caches.  Blocks are numbered so that the blocks that share a pixel tile
+// (its `splits` groups of sweeps) are consecutive on ONE die: workgroups go to the
+// eight dies round-robin in launch order and each die has its own L2, so the
+// re-reads of a tile's codes by its other sweep groups hit that L2.  The channel loop is software-pipelined by hand: the loads of the next 32
 // channels are issued before the matrix instructions of the current ones, and
 // scheduling barriers keep them there.
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
     const float *__restrict__ out_scale, float *__restrict__ y, int64_t c, int64_t hw, int64_t o,
-    int64_t groups_total, int32_t sweeps_per_block, int32_t lds_stride)
+    int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_w[];   // kConvRows x lds_stride bytes
     const int lane = threadIdx.x & (kWave - 1);
     const int half = lane / 32, col = lane % 32;
     // the wavefront's index, in a scalar register: everything derived from it is wave-uniform
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
-    const int64_t g_first = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * 32;
+    // launch order -> (pixel tile, sweep group): die = id % 8, then the sweep groups of a tile
+    const uint32_t die = blockIdx.x % kConvDies, m = blockIdx.x / kConvDies;
+    const uint32_t split = m % (uint32_t)splits;
+    const int64_t tile = (int64_t)(m / (uint32_t)splits) * kConvDies + die;
+    const int64_t g_first = (tile * (kBlock / kWave) + wave) * 32;
     const int64_t g = g_first + col;
     const bool live = g < groups_total;
     const bool wave_live = __any(live);                // a dead wavefront only keeps the barriers
@@ -89,7 +98,7 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint32_t lane_off = live ? (uint32_t)((n - n_first) * c * hw + pb + 16 * half * hw) : 0u;
 
     const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
-    const int64_t s0 = (int64_t)blockIdx.y * sweeps_per_block;
+    const int64_t s0 = (int64_t)split * sweeps_per_block;
     const int64_t s1 = s0 + sweeps_per_block < sweeps ? s0 + sweeps_per_block : sweeps;
 
     for (int64_t sw = s0; sw < s1; ++sw) {
@@ -280,7 +289,7 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
         const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));
         if (gx >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
-        // split the sweeps over blockIdx.y until the launch has about this many blocks
+        // split the sweeps over several blocks until the launch has about this many
         int64_t gy = (GRANQ_CONV_TARGET_BLOCKS + gx - 1) / gx;
         if (gy > sweeps) gy = sweeps;
         if (gy < 1) gy = 1;
@@ -289,9 +298,12 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
         const int64_t kc = c < kConvKChunk ? (c + 63) / 64 * 64 : kConvKChunk;
         const int32_t lds_stride = (int32_t)kc + kConvPad;
         const size_t lds_bytes = (size_t)kConvRows * lds_stride;
-        dim3 grid((uint32_t)gx, (uint32_t)gy), block(kBlock);
+        // tiles rounded up to a multiple of the dies; blocks of tiles past the end find no live group
+        const int64_t blocks = (gx + kConvDies - 1) / kConvDies * kConvDies * gy;
+        if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
+        dim3 grid((uint32_t)blocks), block(kBlock);
         hipLaunchKernelGGL(conv1x1_i8_mfma, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                           groups_total, (int32_t)spb, lds_stride);
+                           groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
         return GRANQ_OK;
     }
