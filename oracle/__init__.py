@@ -7,7 +7,7 @@ out.  Nothing here is shared with, imported by or derived from the HIP library.
 Callers: the tests, the smoke check and the benchmark's CPU-baseline leg.
 
 Arrays: ``x`` is a C-contiguous array of shape (N, C, H, W) -- or any shape
-(N, C, ...) -- of dtype float32, or uint16 holding bfloat16 bit patterns.
+(N, C, ...) -- of dtype float32, float16, or uint16 holding bfloat16 bit patterns.
 """
 from __future__ import annotations
 
@@ -69,7 +69,9 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.granq_oracle_conv1x1_int8.argtypes = [_ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_inloop.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_prescaled.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr]
-    for name in ("range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask", "distortion", "fold_weights", "conv1x1_int8",
+    lib.granq_oracle_f16_widen.argtypes = [_ptr, _i64, _ptr]
+    lib.granq_oracle_f16_narrow.argtypes = [_ptr, _i64, _ptr]
+    for name in ("f16_widen", "f16_narrow", "range_reduce", "prescale", "fakequant_fwd", "fakequant_bwd", "gate_mask", "bwd_from_mask", "distortion", "fold_weights", "conv1x1_int8",
                  "accumulate_inloop", "accumulate_prescaled"):
         getattr(lib, "granq_oracle_" + name).restype = None
     if path is None:
@@ -82,7 +84,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return 0
     if a.dtype == np.uint16:
         return 1
-    raise TypeError("oracle takes float32, or uint16 holding bfloat16 bits; got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return 2
+    raise TypeError("oracle takes float32, float16, or uint16 holding bfloat16 bits; got %s" % a.dtype)
 
 
 def _nchw(a: np.ndarray):
@@ -250,6 +254,22 @@ def accumulate_prescaled(x_hat: np.ndarray, weight, lib=None):
     y = np.empty((n,) + x_hat.shape[2:], np.float32)
     lib.granq_oracle_accumulate_prescaled(_p(x_hat), n, c, hw, _p(w), _p(y))
     return y
+
+
+def f16_widen(h: np.ndarray, lib=None) -> np.ndarray:
+    """The oracle's own binary16 -> binary32 conversion on uint16 bit patterns (test hook)."""
+    h = np.ascontiguousarray(h, np.uint16)
+    out = np.empty(h.shape, np.float32)
+    (lib or load()).granq_oracle_f16_widen(_p(h), h.size, _p(out))
+    return out
+
+
+def f16_narrow(f: np.ndarray, lib=None) -> np.ndarray:
+    """The oracle's own binary32 -> binary16 conversion, as uint16 bit patterns (test hook)."""
+    f = np.ascontiguousarray(f, np.float32)
+    out = np.empty(f.shape, np.uint16)
+    (lib or load()).granq_oracle_f16_narrow(_p(f), f.size, _p(out))
+    return out
 
 
 def bf16_bits_from_f32(a: np.ndarray) -> np.ndarray:

@@ -28,8 +28,9 @@
  * Parity unpinned with respect to the authors' own code for the first, fourth
  * and last of these: the paper gives nothing that could confirm them.
  *
- * dtype: 0 = binary32 storage, 1 = bfloat16 storage (uint16 bit patterns).
- * With bfloat16 storage only loads and stores change: a load widens exactly,
+ * dtype: 0 = binary32 storage, 1 = bfloat16 storage (uint16 bit patterns),
+ * 2 = IEEE binary16 storage (uint16 bit patterns).
+ * With 16-bit storage only loads and stores change: a load widens exactly,
  * a store rounds to nearest even; ranges, scale, zero-point and all arithmetic
  * stay binary32.
  */
@@ -38,7 +39,7 @@
 #include <stdint.h>
 #include <string.h>
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 /* bfloat16 is the top half of a binary32: widening appends 16 zero bits. */
 static float bf16_widen(uint16_t h)
@@ -64,10 +65,67 @@ static uint16_t bf16_narrow(float f)
     return (uint16_t)kept;
 }
 
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits, bias 15) to binary32:
+ * every binary16 value is a binary32 value.  value = (-1)^sign * fraction/1024 *
+ * 2^-14 for exponent field 0 (zero and subnormals), (1 + fraction/1024) *
+ * 2^(exponent-15) for fields 1..30; field 31 is infinity (fraction 0) or NaN. */
+static float f16_widen(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int exponent = (h >> 10) & 0x1F;
+    int fraction = h & 0x3FF;
+    float magnitude;
+    if (exponent == 0)
+        magnitude = ldexpf((float)fraction, -24);
+    else if (exponent == 31)
+        magnitude = fraction ? NAN : INFINITY;
+    else
+        magnitude = ldexpf((float)(1024 + fraction), exponent - 25);
+    return sign ? -magnitude : magnitude;
+}
+
+/* Narrow a binary32 to binary16, round to nearest, ties to even.  The binary16
+ * grid around |f| has spacing 2^(e-10) with e = max(floor(log2|f|), -14); the
+ * quotient |f| / spacing is computed exactly (a power-of-two scaling of a
+ * binary32 that needs at most 24 bits here), rounded to an integer with ties
+ * to even, and scaled back.  A result of 2^16 or more is beyond the largest
+ * finite binary16 (65504) and becomes infinity. */
+static uint16_t f16_narrow(float f)
+{
+    uint16_t sign = signbit(f) ? 0x8000u : 0u;
+    float a = fabsf(f);
+    if (isnan(a))
+        return (uint16_t)(sign | 0x7E00u);
+    if (a == 0.0f)
+        return sign;
+    if (isinf(a))
+        return (uint16_t)(sign | 0x7C00u);
+    int e;
+    (void)frexpf(a, &e);            /* a = m * 2^e with m in [0.5, 1) */
+    e -= 1;                         /* floor(log2 a) */
+    if (e < -14)
+        e = -14;
+    if (e > 16)
+        return (uint16_t)(sign | 0x7C00u);
+    double steps = rint(ldexp((double)a, 10 - e));   /* exact scaling; rint under FE_TONEAREST ties to even */
+    /* steps is in [0, 2048]; 2048 means the next binade */
+    if (e == -14 && steps < 1024.0)
+        return (uint16_t)(sign | (uint16_t)steps);                 /* subnormal or zero */
+    if (steps >= 2048.0) {
+        steps = 1024.0;
+        e += 1;
+    }
+    if (e > 15)
+        return (uint16_t)(sign | 0x7C00u);
+    return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)((int)steps - 1024));
+}
+
 static float load_elem(const void *base, int64_t i, int dtype)
 {
     if (dtype == ORACLE_BF16)
         return bf16_widen(((const uint16_t *)base)[i]);
+    if (dtype == ORACLE_F16)
+        return f16_widen(((const uint16_t *)base)[i]);
     return ((const float *)base)[i];
 }
 
@@ -75,8 +133,24 @@ static void store_elem(void *base, int64_t i, int dtype, float v)
 {
     if (dtype == ORACLE_BF16)
         ((uint16_t *)base)[i] = bf16_narrow(v);
+    else if (dtype == ORACLE_F16)
+        ((uint16_t *)base)[i] = f16_narrow(v);
     else
         ((float *)base)[i] = v;
+}
+
+/* Test hooks for the two binary16 conversions (pinned against an independent
+ * implementation in the tests). */
+void granq_oracle_f16_widen(const uint16_t *h, int64_t count, float *out)
+{
+    for (int64_t i = 0; i < count; ++i)
+        out[i] = f16_widen(h[i]);
+}
+
+void granq_oracle_f16_narrow(const float *f, int64_t count, uint16_t *out)
+{
+    for (int64_t i = 0; i < count; ++i)
+        out[i] = f16_narrow(f[i]);
 }
 
 /* Largest code, 2^b - 1, as a float (Eq. 2 denominator). */

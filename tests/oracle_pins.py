@@ -273,6 +273,48 @@ def check_bf16_vs_torch(lib=None):
         assert f32_to_fraction(oracle.f32_from_bf16_bits(np.array([hb]))[0]) == rn_bf16(exact)
 
 
+def check_f16_vs_numpy(lib=None):
+    """binary16 storage: the oracle's own widening and round-to-nearest-even narrowing against
+    numpy's float16 (an independent implementation) on every binary16 pattern, on every exact
+    midpoint between neighbouring binary16 values, around the overflow threshold and the
+    subnormal range; then the quantizer on binary16 data against the same values held in binary32."""
+    h = np.arange(65536, dtype=np.uint16)
+    ref = h.view(np.float16).astype(np.float32)
+    got = oracle.f16_widen(h, lib)
+    fin = ~np.isnan(ref)
+    _eq(got.view(np.uint32)[fin], ref.view(np.uint32)[fin], "binary16 -> binary32")
+    assert np.isnan(got[~fin]).all()
+    rng = np.random.default_rng(0)
+    pos = h[:0x7C00].view(np.float16).astype(np.float64)                     # 0 .. 65504 ascending
+    mids = ((pos[:-1] + pos[1:]) / 2).astype(np.float32)                     # exact in binary32
+    f = np.concatenate([
+        (rng.standard_normal(400000) * np.exp(rng.uniform(-20, 12, 400000))).astype(np.float32),
+        mids, np.nextafter(mids, np.float32(0)), np.nextafter(mids, np.float32(np.inf)),
+        np.array([65504, 65519.996, 65520, 65536, 1e9, np.inf, 0.0, 2.0 ** -24, 2.0 ** -25,
+                  np.nextafter(np.float32(2.0 ** -25), np.float32(1)), 3 * 2.0 ** -25, 2.0 ** -14,
+                  2.0 ** -14 - 2.0 ** -25], np.float32)])
+    f = np.concatenate([f, -f])
+    with np.errstate(over="ignore"):
+        want = f.astype(np.float16).view(np.uint16)
+    _eq(oracle.f16_narrow(f, lib), want, "binary32 -> binary16, ties to even")
+    # the quantizer on binary16 storage
+    x16 = (rng.standard_normal((3, 4, 5, 6)) * 3).astype(np.float16)
+    x32 = x16.astype(np.float32)
+    mn, mx = oracle.range_reduce(x16, lib)
+    _eq(mn, x32.min(axis=(0, 2, 3)), "f16 min")
+    _eq(mx, x32.max(axis=(0, 2, 3)), "f16 max")
+    for bits in (3, 8):
+        s, z = oracle.prescale(mn, mx, bits, lib)
+        xh16, c16 = oracle.fakequant_fwd(x16, s, z, bits, lib)
+        xh32, c32 = oracle.fakequant_fwd(x32, s, z, bits, lib)
+        _eq(c16, c32, "f16 codes == f32 codes on the same values")
+        _eq(xh16.view(np.uint16), xh32.astype(np.float16).view(np.uint16), "f16 xhat == numpy narrowing of the f32 xhat")
+        dy16 = rng.standard_normal((3, 4, 5, 6)).astype(np.float16)
+        dx16 = oracle.fakequant_bwd(x16, dy16, s, z, bits, lib)
+        dx32 = oracle.fakequant_bwd(x32, dy16.astype(np.float32), s, z, bits, lib)
+        _eq(dx16.astype(np.float32), dx32, "f16 dx")
+
+
 # ---------------------------------------------------------------------------
 # P3 / P5: invariants on workload-like tensors
 # ---------------------------------------------------------------------------
@@ -534,6 +576,7 @@ ALL_CHECKS = [
     check_minmax_vs_numpy,
     check_unit_scale_is_clip_rint,
     check_bf16_vs_torch,
+    check_f16_vs_numpy,
     check_invariants,
     check_collapse_to_layerwise,
     check_per_sample_view,

@@ -54,6 +54,11 @@ MUTANTS = [
     ("conv_weights_transposed", "acc += (int32_t)wq[io * c + ic] * (int32_t)codes[(in * c + ic) * hw + k];", "acc += (int32_t)wq[ic * o + io] * (int32_t)codes[(in * c + ic) * hw + k];", 1),
     ("bf16_ties_round_up", "(dropped == 0x8000u && (kept & 1u))", "(dropped == 0x8000u)", 1),
     ("bf16_truncates", "if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))", "if (0)", 1),
+    ("f16_ties_round_up", "double steps = rint(ldexp((double)a, 10 - e));", "double steps = floor(ldexp((double)a, 10 - e) + 0.5);", 1),
+    ("f16_truncates", "double steps = rint(ldexp((double)a, 10 - e));", "double steps = floor(ldexp((double)a, 10 - e));", 1),
+    ("f16_subnormals_flushed", "if (e < -14)\n        e = -14;", "if (e < -14)\n        return sign;", 1),
+    ("f16_overflow_saturates", "if (e > 15)\n        return (uint16_t)(sign | 0x7C00u);", "if (e > 15)\n        return (uint16_t)(sign | 0x7BFFu);", 1),
+    ("f16_widen_wrong_bias", "magnitude = ldexpf((float)(1024 + fraction), exponent - 25);", "magnitude = ldexpf((float)(1024 + fraction), exponent - 24);", 1),
     ("inloop_drops_scale", "float ws = weight[ic] * scale[ic];", "float ws = weight[ic];", 1),
     ("inloop_drops_zero_point", "- zero_point[ic];\n                float ws", ";\n                float ws", 1),
     ("prescaled_sum_skips_last_channel",
