@@ -444,7 +444,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--dtype", choices=["f32", "bf16", "f16"], default="f32")
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--cpu-sample-batch", type=int, default=256,
                     help="batch size of the sample the CPU oracle is timed on (0 = skip)")
@@ -558,7 +558,7 @@ def main():
         del layers
         torch.cuda.empty_cache()
         others = {}
-        for dname, bits in [("f32", 4), ("f32", 5), ("bf16", 4), ("bf16", 5)]:
+        for dname, bits in [("f32", 4), ("f32", 5), ("bf16", 4), ("bf16", 5), ("f16", 4)]:
             if dname == args.dtype and bits == args.bits:
                 continue
             ls = build_layers(wl, workloads.torch_dtype(dname), bits, device)

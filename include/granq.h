@@ -22,8 +22,8 @@
  *    zero-point vectors are always float32 of length C.
  *  - Arithmetic is IEEE-754 binary32 with round-to-nearest-even, each operation
  *    rounded on its own (true division, no fused multiply-add, subnormals
- *    kept).  With bfloat16 storage only loads (exact widening) and stores
- *    (round to nearest even) differ.
+ *    kept).  With bfloat16 or binary16 storage only loads (exact widening) and
+ *    stores (round to nearest even; binary16 overflows to infinity) differ.
  *  - Inputs must be finite.  NaN or infinity in x gives unspecified values
  *    (never a fault or a hang).
  *  - Data pointers should be 16-byte aligned and C*H*W*sizeof(element) a
@@ -59,7 +59,8 @@ typedef enum {
 
 typedef enum {
     GRANQ_F32 = 0,               /* IEEE binary32 storage */
-    GRANQ_BF16 = 1               /* bfloat16 storage      */
+    GRANQ_BF16 = 1,              /* bfloat16 storage      */
+    GRANQ_F16 = 2                /* IEEE binary16 storage */
 } granq_dtype_t;
 
 /* Dense contiguous NCHW tensor. */

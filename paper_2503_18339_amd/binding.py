@@ -24,6 +24,7 @@ GRANQ_ERR_HIP = 4
 
 GRANQ_F32 = 0
 GRANQ_BF16 = 1
+GRANQ_F16 = 2
 
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
            "granq_range_reduce",
@@ -119,12 +120,16 @@ def _check(status: int, where: str) -> None:
         raise GranqError(status, where)
 
 
+def dtype_code(dtype: torch.dtype) -> int:
+    """granq_dtype_t of a torch dtype."""
+    try:
+        return {torch.float32: GRANQ_F32, torch.bfloat16: GRANQ_BF16, torch.float16: GRANQ_F16}[dtype]
+    except KeyError:
+        raise TypeError("GranQ takes float32, bfloat16 or float16 tensors, got %s" % dtype) from None
+
+
 def _dtype_code(t: torch.Tensor) -> int:
-    if t.dtype == torch.float32:
-        return GRANQ_F32
-    if t.dtype == torch.bfloat16:
-        return GRANQ_BF16
-    raise TypeError("GranQ takes float32 or bfloat16 tensors, got %s" % t.dtype)
+    return dtype_code(t.dtype)
 
 
 def make_desc(n: int, c: int, h: int, w: int, dtype: int) -> granq_desc_t:
@@ -293,7 +298,7 @@ def rowwise_items(weights, outs, scales, zero_points):
 
 
 def granq_rowwise_fakequant_multi(items, dtype: torch.dtype, bits: int, stream=None) -> None:
-    code = GRANQ_F32 if dtype == torch.float32 else GRANQ_BF16
+    code = dtype_code(dtype)
     _check(load().granq_rowwise_fakequant_multi(ctypes.cast(items, _vp), len(items), code, int(bits),
                                                 _stream(stream)), "granq_rowwise_fakequant_multi")
 
@@ -309,7 +314,7 @@ def rowwise_bwd_items(weights, dys, dws, scales, zero_points):
 
 
 def granq_rowwise_fakequant_bwd_multi(items, dtype: torch.dtype, bits: int, stream=None) -> None:
-    code = GRANQ_F32 if dtype == torch.float32 else GRANQ_BF16
+    code = dtype_code(dtype)
     _check(load().granq_rowwise_fakequant_bwd_multi(ctypes.cast(items, _vp), len(items), code, int(bits),
                                                     _stream(stream)), "granq_rowwise_fakequant_bwd_multi")
 

@@ -25,6 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------
 // storage traits: one 16-byte vector per lane and per load
@@ -70,11 +71,33 @@ __device__ inline uint32_t bf16_round(float f) {
     return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
 
-struct BF16 {
-    using vec_t = u32x4;            // 8 bfloat16 in four 32-bit words
+// What the two 16-bit storage types share: eight elements in four 32-bit words,
+// element 2i in the low half of word i.
+struct Pack16 {
+    using vec_t = u32x4;            // 8 elements in four 32-bit words
     using code_t = u32x2;           // 8 packed 8-bit codes
     static constexpr int VEC = 8;
     static constexpr int ESIZE = 2;
+    __device__ static inline code_t pack_codes(const float (&q)[VEC]) {
+        code_t c;
+        c.x = (uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) | ((uint32_t)q[3] << 24);
+        c.y = (uint32_t)q[4] | ((uint32_t)q[5] << 8) | ((uint32_t)q[6] << 16) | ((uint32_t)q[7] << 24);
+        return c;
+    }
+    __device__ static inline vec_t gate(const vec_t &g, const bool (&keep)[VEC]) {
+        vec_t r;
+        r.x = g.x & ((keep[0] ? 0x0000FFFFu : 0u) | (keep[1] ? 0xFFFF0000u : 0u));
+        r.y = g.y & ((keep[2] ? 0x0000FFFFu : 0u) | (keep[3] ? 0xFFFF0000u : 0u));
+        r.z = g.z & ((keep[4] ? 0x0000FFFFu : 0u) | (keep[5] ? 0xFFFF0000u : 0u));
+        r.w = g.w & ((keep[6] ? 0x0000FFFFu : 0u) | (keep[7] ? 0xFFFF0000u : 0u));
+        return r;
+    }
+    __device__ static inline void store_gated1(void *dx, const void *dy, int64_t i, bool keep) {
+        ((uint16_t *)dx)[i] = keep ? ((const uint16_t *)dy)[i] : (uint16_t)0;
+    }
+};
+
+struct BF16 : Pack16 {
     __device__ static inline void unpack(const vec_t &v, float (&f)[VEC]) {
         f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
         f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
@@ -96,28 +119,60 @@ struct BF16 {
         v.w = pack2(f[6], f[7]);
         return v;
     }
-    __device__ static inline code_t pack_codes(const float (&q)[VEC]) {
-        code_t c;
-        c.x = (uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) | ((uint32_t)q[3] << 24);
-        c.y = (uint32_t)q[4] | ((uint32_t)q[5] << 8) | ((uint32_t)q[6] << 16) | ((uint32_t)q[7] << 24);
-        return c;
-    }
-    __device__ static inline vec_t gate(const vec_t &g, const bool (&keep)[VEC]) {
-        vec_t r;
-        r.x = g.x & ((keep[0] ? 0x0000FFFFu : 0u) | (keep[1] ? 0xFFFF0000u : 0u));
-        r.y = g.y & ((keep[2] ? 0x0000FFFFu : 0u) | (keep[3] ? 0xFFFF0000u : 0u));
-        r.z = g.z & ((keep[4] ? 0x0000FFFFu : 0u) | (keep[5] ? 0xFFFF0000u : 0u));
-        r.w = g.w & ((keep[6] ? 0x0000FFFFu : 0u) | (keep[7] ? 0xFFFF0000u : 0u));
-        return r;
-    }
     __device__ static inline float load1(const void *p, int64_t i) {
         return __uint_as_float((uint32_t)((const uint16_t *)p)[i] << 16);
     }
     __device__ static inline void store1(void *p, int64_t i, float v) {
         ((uint16_t *)p)[i] = (uint16_t)bf16_round(v);
     }
-    __device__ static inline void store_gated1(void *dx, const void *dy, int64_t i, bool keep) {
-        ((uint16_t *)dx)[i] = keep ? ((const uint16_t *)dy)[i] : (uint16_t)0;
+};
+
+// IEEE binary16.  Widening (v_cvt_f32_f16) is exact, subnormals included; narrowing
+// (v_cvt_f16_f32) rounds to nearest even in the default rounding mode, produces
+// subnormals and overflows to infinity above 65504 + half a step.
+struct F16 : Pack16 {
+    // The value to narrow is a binary32 result that must be rounded to binary32 first and to
+    // binary16 second.  Left alone, the compiler fuses the multiply that produced it with the
+    // narrowing (v_fma_mixlo_f16), which rounds once, from the exact product: a different
+    // binary16 value whenever the binary32 rounding lands exactly between two binary16 values.
+    // The empty statement pins the binary32 value in a register.
+    __device__ static inline float rounded_f32(float v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    }
+    __device__ static inline void unpack2(uint32_t w, float &lo, float &hi) {
+        f16x2 h;
+        __builtin_memcpy(&h, &w, sizeof h);
+        f32x2 v = __builtin_convertvector(h, f32x2);
+        lo = v.x;
+        hi = v.y;
+    }
+    __device__ static inline void unpack(const vec_t &v, float (&f)[VEC]) {
+        unpack2(v.x, f[0], f[1]);
+        unpack2(v.y, f[2], f[3]);
+        unpack2(v.z, f[4], f[5]);
+        unpack2(v.w, f[6], f[7]);
+    }
+    __device__ static inline uint32_t pack2(float lo, float hi) {
+        f32x2 v = {rounded_f32(lo), rounded_f32(hi)};
+        f16x2 h = __builtin_convertvector(v, f16x2);
+        uint32_t u;
+        __builtin_memcpy(&u, &h, sizeof u);
+        return u;
+    }
+    __device__ static inline vec_t pack(const float (&f)[VEC]) {
+        vec_t v;
+        v.x = pack2(f[0], f[1]);
+        v.y = pack2(f[2], f[3]);
+        v.z = pack2(f[4], f[5]);
+        v.w = pack2(f[6], f[7]);
+        return v;
+    }
+    __device__ static inline float load1(const void *p, int64_t i) {
+        return (float)((const _Float16 *)p)[i];
+    }
+    __device__ static inline void store1(void *p, int64_t i, float v) {
+        ((_Float16 *)p)[i] = (_Float16)rounded_f32(v);
     }
 };
 

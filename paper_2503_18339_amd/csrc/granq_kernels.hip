@@ -787,7 +787,7 @@ static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 static granq_status_t check_desc(const granq_desc_t *d) {
     if (!d) return GRANQ_ERR_INVALID_ARG;
     if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0) return GRANQ_ERR_INVALID_ARG;
-    if (d->dtype != GRANQ_F32 && d->dtype != GRANQ_BF16) return GRANQ_ERR_UNSUPPORTED;
+    if (d->dtype != GRANQ_F32 && d->dtype != GRANQ_BF16 && d->dtype != GRANQ_F16) return GRANQ_ERR_UNSUPPORTED;
     // element count and every index must fit in int64 with room to spare
     const int64_t lim = (int64_t)1 << 40;
     if (d->n > lim || d->c >= ((int64_t)1 << 31) || d->h > lim || d->w > lim) return GRANQ_ERR_UNSUPPORTED;
@@ -801,7 +801,7 @@ static bool aligned_elem(const void *p, granq_dtype_t dt) {
     return ((uintptr_t)p & (dt == GRANQ_F32 ? 3u : 1u)) == 0;
 }
 
-static int vec_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? F32::VEC : BF16::VEC; }
+static int vec_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? F32::VEC : Pack16::VEC; }
 
 static int64_t tensor_bytes(const granq_desc_t *d) {
     return d->n * d->c * d->h * d->w * (d->dtype == GRANQ_F32 ? 4 : 2);
@@ -1005,7 +1005,8 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
         float *ws_min = (float *)workspace;
         float *ws_max = ws_min + floats;
         if (desc->dtype == GRANQ_F32) launch_range_cols<F32, GRANQ_R_V_F32>(cp, x, ws_min, ws_max, hs);
-        else launch_range_cols<BF16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
+        else if (desc->dtype == GRANQ_BF16) launch_range_cols<BF16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
+        else launch_range_cols<F16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
         st = launched();
         if (st != GRANQ_OK) return st;
         dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave)), block(kBlock);
@@ -1020,8 +1021,10 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
     dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
         hipLaunchKernelGGL(range_rows_pass1<F32>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
-    else
+    else if (desc->dtype == GRANQ_BF16)
         hipLaunchKernelGGL(range_rows_pass1<BF16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
+    else
+        hipLaunchKernelGGL(range_rows_pass1<F16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
     st = launched();
     if (st != GRANQ_OK) return st;
     dim3 grid2((uint32_t)ceil_div(desc->c, kBlock));
@@ -1079,7 +1082,8 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
     if (cp.ok && aligned16(x) && (!x_hat || aligned16(x_hat)) && codes_ok) {
         const int kind = !x_hat ? kCodesOnly : (codes_or_null ? kCodes : kNoExtra);
         if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
-        else launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
+        else if (desc->dtype == GRANQ_BF16) launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<F16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
         return launched();
     }
     const int64_t hw = desc->h * desc->w;
@@ -1087,8 +1091,10 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
     dim3 grid(row_grid(slabs)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
         hipLaunchKernelGGL(fq_fwd_rows<F32>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
-    else
+    else if (desc->dtype == GRANQ_BF16)
         hipLaunchKernelGGL(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+    else
+        hipLaunchKernelGGL(fq_fwd_rows<F16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
     return launched();
 }
 
@@ -1107,7 +1113,8 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
     ColPlan cp = bwd_plan(desc);
     if (cp.ok && aligned16(x) && aligned16(dy) && aligned16(dx)) {
         if (desc->dtype == GRANQ_F32) launch_bwd_cols<F32, GRANQ_E_V_F32>(cp, x, dy, dx, scale, zero_point, qmax, hs);
-        else launch_bwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, dy, dx, scale, zero_point, qmax, hs);
+        else if (desc->dtype == GRANQ_BF16) launch_bwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, dy, dx, scale, zero_point, qmax, hs);
+        else launch_bwd_cols<F16, GRANQ_E_V_BF16>(cp, x, dy, dx, scale, zero_point, qmax, hs);
         return launched();
     }
     const int64_t hw = desc->h * desc->w;
@@ -1115,8 +1122,10 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
     dim3 grid(row_grid(slabs)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
         hipLaunchKernelGGL(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
-    else
+    else if (desc->dtype == GRANQ_BF16)
         hipLaunchKernelGGL(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+    else
+        hipLaunchKernelGGL(fq_bwd_rows<F16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
     return launched();
 }
 
@@ -1149,7 +1158,8 @@ granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc,
     ColPlan cp = fwd_mask_plan(desc);
     if (mask_vector_ok(cp) && aligned16(x) && aligned16(x_hat)) {
         if (desc->dtype == GRANQ_F32) launch_fwd_mask_cols<F32, GRANQ_M_V_F32, GRANQ_M_ROWS_F32>(cp, x, x_hat, mask, scale, zero_point, qmax, hs);
-        else launch_fwd_mask_cols<BF16, GRANQ_M_V_BF16, GRANQ_M_ROWS_BF16>(cp, x, x_hat, mask, scale, zero_point, qmax, hs);
+        else if (desc->dtype == GRANQ_BF16) launch_fwd_mask_cols<BF16, GRANQ_M_V_BF16, GRANQ_M_ROWS_BF16>(cp, x, x_hat, mask, scale, zero_point, qmax, hs);
+        else launch_fwd_mask_cols<F16, GRANQ_M_V_BF16, GRANQ_M_ROWS_BF16>(cp, x, x_hat, mask, scale, zero_point, qmax, hs);
         return launched();
     }
     // any other shape or alignment: gate bits from x first (x_hat may alias x), then the forward
@@ -1159,8 +1169,10 @@ granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc,
     dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
         hipLaunchKernelGGL(mask_from_x_bytes<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
-    else
+    else if (desc->dtype == GRANQ_BF16)
         hipLaunchKernelGGL(mask_from_x_bytes<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
+    else
+        hipLaunchKernelGGL(mask_from_x_bytes<F16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
     st = launched();
     if (st != GRANQ_OK) return st;
     return granq_fakequant_fwd(x, desc, scale, zero_point, bits, x_hat, nullptr, stream);
@@ -1182,8 +1194,9 @@ granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask, con
             if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
             else hipLaunchKernelGGL((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
         } else {
-            if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<BF16, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const BF16::vec_t *)dy, mask, (BF16::vec_t *)dx, cp);
-            else hipLaunchKernelGGL((fq_bwd_mask_cols<BF16, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const BF16::vec_t *)dy, mask, (BF16::vec_t *)dx, cp);
+            // gating moves 16-bit patterns without interpreting them: one kernel for both 16-bit types
+            if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<Pack16, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const Pack16::vec_t *)dy, mask, (Pack16::vec_t *)dx, cp);
+            else hipLaunchKernelGGL((fq_bwd_mask_cols<Pack16, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const Pack16::vec_t *)dy, mask, (Pack16::vec_t *)dx, cp);
         }
         return launched();
     }
@@ -1191,7 +1204,7 @@ granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask, con
     const int64_t want = ceil_div(ceil_div(total, 8), kBlock);
     dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
     if (desc->dtype == GRANQ_F32) hipLaunchKernelGGL(bwd_mask_bytes<F32>, grid, block, 0, hs, dy, mask, total, dx);
-    else hipLaunchKernelGGL(bwd_mask_bytes<BF16>, grid, block, 0, hs, dy, mask, total, dx);
+    else hipLaunchKernelGGL(bwd_mask_bytes<Pack16>, grid, block, 0, hs, dy, mask, total, dx);
     return launched();
 }
 

@@ -96,7 +96,7 @@ __global__ void distortion_layer(const double *__restrict__ ch_sums, int64_t c, 
 static granq_status_t metrics_check(const granq_desc_t *d) {
     if (!d) return GRANQ_ERR_INVALID_ARG;
     if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0) return GRANQ_ERR_INVALID_ARG;
-    if (d->dtype != GRANQ_F32 && d->dtype != GRANQ_BF16) return GRANQ_ERR_UNSUPPORTED;
+    if (d->dtype != GRANQ_F32 && d->dtype != GRANQ_BF16 && d->dtype != GRANQ_F16) return GRANQ_ERR_UNSUPPORTED;
     const int64_t lim = (int64_t)1 << 40;
     if (d->n > lim || d->c >= ((int64_t)1 << 24) || d->h > lim || d->w > lim || d->h * d->w > lim) return GRANQ_ERR_UNSUPPORTED;
     if ((__int128)d->n * d->c * (d->h * d->w) > ((__int128)1 << 46)) return GRANQ_ERR_UNSUPPORTED;
@@ -139,8 +139,10 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc, const f
     dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
         hipLaunchKernelGGL(distortion_pass1<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
-    else
+    else if (desc->dtype == GRANQ_BF16)
         hipLaunchKernelGGL(distortion_pass1<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
+    else
+        hipLaunchKernelGGL(distortion_pass1<F16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
     if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
     hipLaunchKernelGGL(distortion_pass2, dim3((uint32_t)ceil_div(desc->c * 4, kBlock)), block, 0, hs, ws, desc->c, rp.row_groups, ch_sums);
     if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;

@@ -114,7 +114,7 @@ granq_status_t granq_rowwise_fakequant_multi(const granq_rowq_item_t *items, int
                                              granq_dtype_t dtype, int bits, void *stream) {
     if (!items || count <= 0) return GRANQ_ERR_INVALID_ARG;
     if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
-    if (dtype != GRANQ_F32 && dtype != GRANQ_BF16) return GRANQ_ERR_UNSUPPORTED;
+    if (dtype != GRANQ_F32 && dtype != GRANQ_BF16 && dtype != GRANQ_F16) return GRANQ_ERR_UNSUPPORTED;
     for (int i = 0; i < count; ++i) {
         const granq_rowq_item_t &it = items[i];
         if (!it.w || !it.w_hat || !it.scale || !it.zero_point) return GRANQ_ERR_INVALID_ARG;
@@ -138,8 +138,10 @@ granq_status_t granq_rowwise_fakequant_multi(const granq_rowq_item_t *items, int
         if (rows >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         if (dtype == GRANQ_F32)
             hipLaunchKernelGGL(rowq_fwd_kernel<F32>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
-        else
+        else if (dtype == GRANQ_BF16)
             hipLaunchKernelGGL(rowq_fwd_kernel<BF16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+        else
+            hipLaunchKernelGGL(rowq_fwd_kernel<F16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
         if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
     }
     return GRANQ_OK;
@@ -149,7 +151,7 @@ granq_status_t granq_rowwise_fakequant_bwd_multi(const granq_rowq_bwd_item_t *it
                                                  granq_dtype_t dtype, int bits, void *stream) {
     if (!items || count <= 0) return GRANQ_ERR_INVALID_ARG;
     if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
-    if (dtype != GRANQ_F32 && dtype != GRANQ_BF16) return GRANQ_ERR_UNSUPPORTED;
+    if (dtype != GRANQ_F32 && dtype != GRANQ_BF16 && dtype != GRANQ_F16) return GRANQ_ERR_UNSUPPORTED;
     for (int i = 0; i < count; ++i) {
         const granq_rowq_bwd_item_t &it = items[i];
         if (!it.w || !it.dy || !it.dw || !it.scale || !it.zero_point) return GRANQ_ERR_INVALID_ARG;
@@ -173,8 +175,10 @@ granq_status_t granq_rowwise_fakequant_bwd_multi(const granq_rowq_bwd_item_t *it
         if (rows >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         if (dtype == GRANQ_F32)
             hipLaunchKernelGGL(rowq_bwd_kernel<F32>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
-        else
+        else if (dtype == GRANQ_BF16)
             hipLaunchKernelGGL(rowq_bwd_kernel<BF16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+        else
+            hipLaunchKernelGGL(rowq_bwd_kernel<F16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
         if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
     }
     return GRANQ_OK;

@@ -23,7 +23,7 @@ class ActivationQuantizer:
             hw *= int(d)
         h = int(shape[2]) if len(shape) > 2 else 1
         w = hw // h
-        code = B.GRANQ_F32 if dtype == torch.float32 else B.GRANQ_BF16
+        code = B.dtype_code(dtype)
         if view == "channel":            # one range per channel over (n,h,w)
             self.desc = B.make_desc(n, c, h, w, code)
         elif view == "layer":            # one range for the whole tensor

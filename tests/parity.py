@@ -22,12 +22,16 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
 def bits_view(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.float32:
         return a.view(np.uint32)
+    if a.dtype == np.float16:
+        return a.view(np.uint16)
     return a
 
 
 def values(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.uint16:
         return oracle.f32_from_bf16_bits(a)
+    if a.dtype == np.float16:
+        return a.astype(np.float32)
     return a
 
 
@@ -150,13 +154,16 @@ def assert_parity(got: dict, want: dict, what=""):
         assert mm is None, "%s codes differ at flat index %d (%d in total)" % ((what,) + mm)
     gv, wv = values(got["xhat"]), values(want["xhat"])
     # tolerance for floating-point outputs: 1e-6 relative
-    tol = 1e-6 * np.abs(wv)
-    assert np.all(np.abs(gv.astype(np.float64) - wv.astype(np.float64)) <= tol), what + " xhat beyond 1e-6 relative"
+    fin = np.isfinite(wv)                    # binary16 storage overflows to infinity above 65504
+    tol = 1e-6 * np.abs(wv[fin])
+    far = np.nonzero(np.abs(gv[fin].astype(np.float64) - wv[fin].astype(np.float64)) > tol)[0]
+    assert far.size == 0, "%s xhat beyond 1e-6 relative at %d places, first (finite-flat index %d): got %r want %r" % (
+        what, far.size, far[0], gv[fin][far[0]], wv[fin][far[0]])
     mm = first_mismatch(gv, wv)              # expectation: identical values (only +-0 may differ in bits)
     assert mm is None, "%s xhat differs at flat index %d (%d in total)" % ((what,) + mm)
-    if got["xhat"].dtype == np.uint16:
+    if got["xhat"].dtype in (np.uint16, np.float16):
         nz = wv != 0
-        assert np.array_equal(got["xhat"][nz], want["xhat"][nz]), what + " bf16 xhat bits differ"
+        assert np.array_equal(bits_view(got["xhat"])[nz], bits_view(want["xhat"])[nz]), what + " 16-bit xhat bits differ"
     if "dx" in want and "dx" in got:
         g, w = got["dx"], want["dx"]
         mm = first_mismatch(bits_view(g), bits_view(w))

@@ -44,7 +44,7 @@ def _compare(ch, layer, want_ch, want_layer):
     assert abs(layer[5] - want_layer[5]) <= 2 * RTOL * max(want_layer[5], 1e-300)
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
 @pytest.mark.parametrize("shape,law,bits", [((8, 16, 32, 32), "relu", 3), ((5, 37, 9, 8), "linear", 4),
                                             ((6, 100, 7, 7), "laplace", 5), ((3, 40, 1, 1), "linear", 8),
                                             ((2, 3, 7, 7), "relu", 3), ((64, 64, 56, 56), "relu", 4),

@@ -29,7 +29,7 @@ def _cases(seed, count):
         else:                # anything
             shape = tuple(int(v) for v in rng.integers(1, 24, size=4))
         out.append((shape, LAWS[int(rng.integers(0, 4))], int(rng.integers(1, 9)),
-                    torch.float32 if rng.integers(0, 2) else torch.bfloat16, int(rng.integers(0, 3))))
+                    (torch.float32, torch.bfloat16, torch.float16)[int(rng.integers(0, 3))], int(rng.integers(0, 3))))
     return out
 
 
@@ -37,8 +37,7 @@ def _cases(seed, count):
 def test_random_cases(chunk):
     for i, (shape, law, bits, dtype, offset) in enumerate(_cases(1000 + chunk, 30)):
         n_el = int(np.prod(shape))
-        esz = 4 if dtype == torch.float32 else 2
-        # offset 0: aligned allocation; 1, 2: start `offset` elements into a larger buffer
+                # offset 0: aligned allocation; 1, 2: start `offset` elements into a larger buffer
         buf = torch.zeros(n_el + 16, dtype=dtype, device=DEV)
         gbuf = torch.zeros(n_el + 16, dtype=dtype, device=DEV)
         x = buf[offset:offset + n_el].view(shape)

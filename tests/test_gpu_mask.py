@@ -33,7 +33,7 @@ def _run_mask_pair(x, dy, s, z, bits, desc=None):
     return to_numpy(x_hat), mask.cpu().numpy(), to_numpy(dx)
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_mask_pair_small_shapes(shape, dtype):
     for i, (law, bits) in enumerate([("linear", 4), ("relu", 3)]):

@@ -55,7 +55,7 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: "x".join(map(str, s)))
 def test_small_shapes(shape, dtype):
     for i, (law, bits) in enumerate([("relu", 3), ("linear", 4), ("laplace", 8), ("relu6", 1)]):
@@ -97,7 +97,7 @@ def test_golden_examples_on_gpu():
 
 def test_stale_ranges_clamp_both_sides():
     """Scale / zero-point from another tensor: both clamp sides and the gate are exercised."""
-    for dtype in (torch.float32, torch.bfloat16):
+    for dtype in (torch.float32, torch.bfloat16, torch.float16):
         ref = workloads.make_activation((4, 24, 14, 14), "linear", (0.5, 2.0), seed=1, device=DEV, dtype=dtype)
         x = workloads.make_activation((4, 24, 14, 14), "linear", (0.5, 6.0), seed=2, device=DEV, dtype=dtype)
         dy = workloads.make_grad(x.shape, 3, DEV, dtype)
@@ -157,7 +157,7 @@ def test_in_place_forward_and_gradient():
 
 def test_misaligned_pointers_take_the_elementwise_path():
     """A tensor that starts 4 bytes into an allocation: same results, no fault."""
-    for dtype in (torch.float32, torch.bfloat16):
+    for dtype in (torch.float32, torch.bfloat16, torch.float16):
         shape = (3, 8, 8, 8)
         n = 3 * 8 * 8 * 8
         off = 1 if dtype == torch.float32 else 2
@@ -238,3 +238,54 @@ def test_channels_outside_the_fast_quotient_window():
         got = gpu_path(xs, 4, dy, scale=s, zero_point=z)
         want = oracle_path(to_numpy(xs), 4, to_numpy(dy), scale=s, zero_point=z)
         assert_parity(got, want, "stale extreme %s" % (shape,))
+
+
+def test_binary16_overflow_subnormals_and_ties():
+    """binary16 storage where its narrowing matters: dequantized values beyond 65504 become
+    infinity, tiny ones become subnormals, and products that fall exactly between two binary16
+    values go to the even one -- as in the oracle's own conversion."""
+    g = torch.Generator(device=DEV).manual_seed(11)
+    x = torch.empty(4, 6, 8, 8, dtype=torch.float16, device=DEV)
+    scales = torch.tensor([6.0e4, 3.0e-6, 1.0e-7, 1.0, 255.0, 0.37], device=DEV).view(1, 6, 1, 1)
+    x.copy_((torch.rand(4, 6, 8, 8, generator=g, device=DEV) * 2 - 1) * scales)
+    x[0, 0, 0, 0] = 65504.0
+    x[1, 0, 0, 0] = -65504.0
+    dy = workloads.make_grad(x.shape, 5, DEV, torch.float16)
+    for bits in (2, 3, 8):
+        got = gpu_path(x, bits, dy)
+        want = oracle_path(to_numpy(x), bits, to_numpy(dy))
+        assert_parity(got, want, "binary16 edge values b%d" % bits)
+    # given scale 17/16: x_hat = q * 17/16 has exactly 12 significant bits for odd q in [121, 240],
+    # i.e. lies exactly between two binary16 values (11 significant bits)
+    s = np.full(6, 17.0 / 16.0, np.float32)
+    z = np.zeros(6, np.float32)
+    xq = torch.arange(0, 4 * 6 * 8 * 8, device=DEV, dtype=torch.float32).remainder(256).view(4, 6, 8, 8).to(torch.float16)
+    got = gpu_path(xq, 8, None, scale=s, zero_point=z)
+    want = oracle_path(to_numpy(xq), 8, None, scale=s, zero_point=z)
+    assert_parity(got, want, "binary16 midpoints")
+    odd = got["codes"][(got["codes"] % 2 == 1) & (got["codes"] >= 121)]
+    assert odd.size > 300
+
+
+def test_binary16_store_rounds_twice():
+    """x_hat is a binary32 product that is then narrowed: two roundings.  Scales s = RN(m / 3) for
+    binary16 midpoints m make RN32(3 s) land exactly on m while the exact product 3 s does not, so a
+    narrowing fused with the multiply (one rounding from the exact product) gives the other
+    neighbour in about half of the channels.  Both the vector kernels and the element-wise ones."""
+    h = np.arange(0x3C00, 0x6C00, dtype=np.uint16)                     # binary16 values 1 .. 4096
+    lo = h.view(np.float16).astype(np.float64)
+    mids = ((lo[:-1] + lo[1:]) / 2)[::3][:4096]                        # 4096 exact midpoints
+    s = (mids / 3.0).astype(np.float32)
+    hit = (s.astype(np.float32) * np.float32(3.0)).astype(np.float64) == mids     # RN32(3 s) is the midpoint
+    inexact = s.astype(np.float64) * 3.0 != mids                                   # the exact product is not
+    assert (hit & inexact).sum() > 1000
+    c = s.size
+    z = np.zeros(c, np.float32)
+    for offset in (0, 1):                                              # aligned: vector path; +1 element: element-wise
+        buf = torch.zeros(2 * c * 4 + 16, dtype=torch.float16, device=DEV)
+        x = buf[offset:offset + 2 * c * 4].view(2, c, 2, 2)
+        x.copy_(torch.from_numpy(mids.astype(np.float32)).to(DEV).view(1, c, 1, 1).expand(2, c, 2, 2))
+        got = gpu_path(x, 4, None, scale=s, zero_point=z)
+        want = oracle_path(to_numpy(x), 4, None, scale=s, zero_point=z)
+        assert np.all(want["codes"] == 3)
+        assert_parity(got, want, "binary16 double rounding, offset %d" % offset)

@@ -47,7 +47,7 @@ def _run(shapes, dtype, bits):
     return ws, outs, sc, zp
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
 @pytest.mark.parametrize("bits", [3, 4, 8])
 def test_resnet18_weights_one_launch(dtype, bits):
     _run(workloads.resnet18_weight_shapes(), dtype, bits)

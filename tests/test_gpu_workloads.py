@@ -51,7 +51,7 @@ def test_config2_resnet20_cifar(idx, bits):
     _run(CFG2, CFG2.tensors()[idx], bits, "f32", seed=idx)
 
 
-@pytest.mark.parametrize("dtype,bits", [("f32", 4), ("bf16", 4), ("f32", 5), ("bf16", 5)])
+@pytest.mark.parametrize("dtype,bits", [("f32", 4), ("bf16", 4), ("f32", 5), ("bf16", 5), ("f16", 4)])
 @pytest.mark.parametrize("idx", range(len(CFG3.acts)))
 def test_config3_resnet18_imagenet(idx, dtype, bits):
     got = _run(CFG3, CFG3.acts[idx], bits, dtype, seed=idx)

@@ -202,7 +202,7 @@ WORKLOADS = {
 
 
 def torch_dtype(name: str) -> torch.dtype:
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[name]
 
 
 # ---------------------------------------------------------------------------
