@@ -251,6 +251,27 @@ def comparison_points(wl, bits, device):
     return out
 
 
+def channels_last_view(bits, device):
+    """A channels-last activation (N,H,W,C) = (256,56,56,64), float32, through the same four calls
+    on the view {N*H*W, C, 1, 1}: rows of 64 elements, which the plans glue into rows of a block's span."""
+    shape = (256 * 56 * 56, 64, 1, 1)
+    x = workloads.make_activation(shape, "relu", (0.05, 20.0), 2, device)
+    dy = workloads.make_grad(shape, 2, device)
+    q = G.ActivationQuantizer(shape, torch.float32, bits, device)
+    xh, dx = torch.empty_like(x), torch.empty_like(x)
+    st = torch.cuda.current_stream()
+    e = x.numel()
+    t_r = _timeit(lambda: G.granq_range_reduce(x, q.ch_min, q.ch_max, q.workspace, st, q.desc))
+    G.granq_prescale(q.ch_min, q.ch_max, bits, q.scale, q.zero_point, st)
+    t_f = _timeit(lambda: G.granq_fakequant_fwd(x, q.scale, q.zero_point, bits, xh, None, st, q.desc))
+    t_b = _timeit(lambda: G.granq_fakequant_bwd(x, dy, q.scale, q.zero_point, bits, dx, st, q.desc))
+    pl = G.granq_plan_describe(q.desc)
+    return {"rows_glued": pl["fold"], "reduce_us": round(t_r, 1), "reduce_GBs": round(e * 4 / t_r / 1e3, 1),
+            "fwd_us": round(t_f, 1), "fwd_GBs": round(e * 8 / t_f / 1e3, 1),
+            "bwd_us": round(t_b, 1), "bwd_GBs": round(e * 12 / t_b / 1e3, 1),
+            "same_tensor_nchw_us": "see per_kernel, layer1 256x64x56x56"}
+
+
 def gate_bit_variant(wl, dtype, bits, device, steps, warmup):
     """The same step with the forward emitting one gate bit per element and the backward reading
     dy + bits instead of x + dy (granq_fakequant_fwd_mask / granq_fakequant_bwd_mask)."""
@@ -574,6 +595,7 @@ def main():
         extra["integer_accumulation_1x1_batch256"] = integer_accumulation(wl, args.bits, device)
         extra["distortion_3bit"] = distortion_table(wl, device)
         extra["resnet18_weights_channelwise"] = weight_quantization(args.bits, device)
+        extra["channels_last_view_256x56x56x64"] = channels_last_view(args.bits, device)
         extra["gate_bit_variant"] = gate_bit_variant(wl, dtype, args.bits, device, args.steps, args.warmup)
         extra["gate_bit_variant"]["speedup_vs_x_based_step"] = round(
             ms_per_step / extra["gate_bit_variant"]["ms_per_step"], 3)

@@ -84,17 +84,22 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
 
 /*
  * Host-only introspection (no GPU call): how the vectorised kernels would tile
- * this descriptor.  Fills out[0..15] with
+ * this descriptor.  Fills out[0..23] with
  *   [0] 1 if the shape is eligible for the 128-bit column kernels, else 0
  *   [1] rows  [2] row length  [3] elements per channel within a row
  *   [4] columns per block  [5] column tiles  [6] row groups  [7] rows per group
  *   [8] partial slots per column tile  [9] 1 if no 16-byte vector straddles channels
  *   [10..12] multiplier and the two shifts of the column -> channel division
  *   [13] rows per block of the forward  [14] of the backward  [15] their columns per block
- * of the matrix view (rows x row length) the kernels walk; [4]..[8] describe the
- * reduction.  For tests and tuning.
+ *   [16] true rows glued into one row of the reduction's matrix (1: none; short rows,
+ *        e.g. a channels-last tensor seen as {N*H*W, C, 1, 1}, are glued so that a block's
+ *        lanes all have a column; [1], [2] are the glued counts, the channel of a column
+ *        follows from the column modulo the true row length)
+ *   [17..23] zero, reserved
+ * of the matrix view (rows x row length) the kernels walk; [1]..[12] and [16] describe
+ * the reduction.  For tests and tuning.
  */
-granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[16]);
+granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[24]);
 
 /*
  * Activation decomposition (Eq. 4; Alg. 1's min/max step; Sec. 5.1: channel-wise

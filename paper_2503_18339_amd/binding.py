@@ -81,7 +81,7 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_version.argtypes = []
     lib.granq_version.restype = ctypes.c_char_p
     lib.granq_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
-    lib.granq_plan_describe.argtypes = [dp, ctypes.POINTER(ctypes.c_int64 * 16)]
+    lib.granq_plan_describe.argtypes = [dp, ctypes.POINTER(ctypes.c_int64 * 24)]
     lib.granq_range_reduce.argtypes = [_vp, dp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_prescale.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_calibrate.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
@@ -178,11 +178,11 @@ def granq_workspace_bytes(desc: granq_desc_t) -> int:
 
 
 def granq_plan_describe(desc: granq_desc_t) -> dict:
-    out = (ctypes.c_int64 * 16)()
+    out = (ctypes.c_int64 * 24)()
     _check(load().granq_plan_describe(ctypes.byref(desc), ctypes.byref(out)), "granq_plan_describe")
     keys = ("vector_path", "rows", "row_len", "hw", "span", "col_tiles", "row_groups",
             "rows_per_group", "kmax", "uniform", "div_m", "div_s1", "div_s2", "fwd_rows", "bwd_rows",
-            "elem_span")
+            "elem_span", "fold")
     return dict(zip(keys, [int(v) for v in out]))
 
 

@@ -187,7 +187,7 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
         active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
         int32_t ch[NS];
-        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? col : 0u, plan, ch);
+        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? true_column(col, plan) : 0u, plan, ch);
 #pragma unroll
         for (int e = 0; e < NS; ++e) {
             const float s = scale[ch[e]], z = zero_point[ch[e]];
@@ -557,8 +557,9 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
     constexpr int NG = Slots<MODE, VEC>::N;             // channel groups per vector
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        // inactive lanes hold the identities and point at the tile's first channel
-        const uint32_t col = active[v] ? cv[v] * VEC : j * (uint32_t)plan.span;
+        // inactive lanes hold the identities and point at the tile's first channel; with glued
+        // rows the channel follows from the column within the true row
+        const uint32_t col = true_column(active[v] ? cv[v] * VEC : j * (uint32_t)plan.span, plan);
         int32_t ch[NG];
         const uint32_t split = vector_channels<MODE, VEC, NG>(col, plan, ch);
         float gmn[NG], gmx[NG];
@@ -960,7 +961,7 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
     return GRANQ_OK;
 }
 
-granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[16]) {
+granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[24]) {
     if (!out) return GRANQ_ERR_INVALID_ARG;
     granq_status_t st = check_desc(desc);
     if (st != GRANQ_OK) return st;
@@ -982,6 +983,8 @@ granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[16]) {
     out[13] = fp.rows_per_group;
     out[14] = bp.rows_per_group;
     out[15] = fp.span;
+    out[16] = cp.fold;
+    for (int i = 17; i < 24; ++i) out[i] = 0;
     return GRANQ_OK;
 }
 

@@ -17,6 +17,13 @@
 // A tensor with a single channel (the layer-wise view {1,1,1,E}) has only one
 // row; since every element then belongs to channel 0 the matrix may be folded
 // to any rows x columns factorisation, and the plan does so.
+//
+// Short rows (a channels-last tensor seen as {N*H*W, C, 1, 1} has rows of C
+// elements) would leave most lanes of a block without a column.  The plans
+// therefore glue `fold` consecutive rows into one row of the matrix they walk:
+// a lane's column, taken modulo the true row length, still fixes its channel(s)
+// for good.  The fold is chosen so that the glued row is exactly what one block
+// spans or less, and divides the row count.
 #pragma once
 
 #include <stdint.h>
@@ -96,8 +103,16 @@ struct ColPlan {
     FastDiv hw_div;          // column -> channel
     bool uniform;            // every 16-byte vector lies inside one channel
     int32_t mode;            // 0: one channel per vector, 1: at most two, 2: up to one per element
+    int32_t fold;            // true rows glued into one row of this matrix (1: none)
+    FastDiv true_len_div;    // column -> column within the true row (used when fold > 1)
     bool ok;                 // false: shape not eligible for the vector kernels
 };
+
+// Column within the true row of the tensor.
+GRANQ_PLAN_HD inline uint32_t true_column(uint32_t col, const ColPlan &p) {
+    if (p.fold <= 1) return col;
+    return col - fastdiv(col, p.true_len_div) * p.true_len_div.d;
+}
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -106,6 +121,7 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
                              int64_t target_blocks, int64_t min_rows) {
     ColPlan p{};
     p.ok = false;
+    p.fold = 1;
     int64_t rows = n, row_len = c * hw, chan = c, per = hw;
     if (c == 1) {
         // fold rows * row_len = E so that rows is a power of two up to 1024
@@ -121,6 +137,16 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
     }
     if (row_len % vec != 0) return p;
     if (row_len >= (int64_t)1 << 31) return p;
+    p.true_len_div = make_fastdiv((uint32_t)row_len);
+    const int64_t block_span = (int64_t)block * vec * v;
+    if (c > 1 && row_len < block_span) {
+        // the largest fold that keeps the glued row within one block's span and divides the rows
+        int64_t f = block_span / row_len;
+        while (f > 1 && rows % f != 0) --f;
+        p.fold = (int32_t)f;
+        rows /= f;
+        row_len *= f;
+    }
     p.rows = rows;
     p.row_len = row_len;
     p.hw = per;

@@ -117,6 +117,7 @@ SHAPES = [
     (256, 512, 7, 7), (256, 2048, 7, 7), (256, 960, 7, 7), (256, 24, 56, 56), (1, 1, 1, 205520896),
     (1, 1, 1, 4096), (1, 2048, 7, 7), (3, 40, 1, 1), (5, 37, 9, 8), (2, 3, 7, 7), (4, 8, 7, 7),
     (1, 64, 1, 1152), (7, 12, 14, 14), (1, 1, 1, 131072 * 3), (2, 1, 5, 4),
+    (802816, 64, 1, 1), (50176, 256, 1, 1), (12544, 512, 1, 1), (4096, 3, 1, 4), (6, 16, 2, 2), (331, 16, 1, 1),
 ]
 
 
@@ -135,21 +136,27 @@ def test_plan_invariants(shape, dtype):
         return
     assert pl["rows"] * pl["row_len"] == e
     assert pl["row_len"] % vec == 0 and pl["row_len"] < 2 ** 31
+    f = pl["fold"]
     if c == 1:
-        assert pl["hw"] == pl["row_len"]
+        assert pl["hw"] == pl["row_len"] and f == 1
     else:
-        assert pl["hw"] == h * w and pl["rows"] == n and pl["row_len"] == c * h * w
+        assert pl["hw"] == h * w and pl["rows"] * f == n and pl["row_len"] == c * h * w * f
+        # rows are glued only when they are shorter than a block's span, and then into one tile
+        assert f == 1 or (pl["row_len"] <= pl["span"] and pl["col_tiles"] == 1 and pl["kmax"] == c)
+        if c * h * w * 2 <= pl["span"] and n % 2 == 0:
+            assert f >= 2
     assert pl["span"] % (256 * vec) == 0
     assert (pl["col_tiles"] - 1) * pl["span"] < pl["row_len"] <= pl["col_tiles"] * pl["span"]
     assert (pl["row_groups"] - 1) * pl["rows_per_group"] < pl["rows"] <= pl["row_groups"] * pl["rows_per_group"]
     assert pl["uniform"] == (1 if pl["hw"] % vec == 0 else 0)
     assert 2 * 4 * pl["row_groups"] * pl["col_tiles"] * pl["kmax"] <= need
     # every column tile touches at most kmax channels
-    j = np.arange(pl["col_tiles"], dtype=np.int64)
-    first = (j * pl["span"]) // pl["hw"]
-    last = (np.minimum((j + 1) * pl["span"], pl["row_len"]) - 1) // pl["hw"]
-    assert int((last - first).max()) + 1 <= pl["kmax"]
-    assert int(last.max()) == pl["row_len"] // pl["hw"] - 1
+    if f == 1:
+        j = np.arange(pl["col_tiles"], dtype=np.int64)
+        first = (j * pl["span"]) // pl["hw"]
+        last = (np.minimum((j + 1) * pl["span"], pl["row_len"]) - 1) // pl["hw"]
+        assert int((last - first).max()) + 1 <= pl["kmax"]
+        assert int(last.max()) == pl["row_len"] // pl["hw"] - 1
 
 
 @pytest.mark.parametrize("hw", [1, 2, 3, 4, 7, 49, 64, 196, 784, 1000, 3136, 12544, 65535, 65536, 65537,
@@ -177,7 +184,8 @@ def _emulate_range_cols(x2d, pl, vec):
     rows, row_len = x2d.shape
     span, hw, kmax = pl["span"], pl["hw"], pl["kmax"]
     J, P, rpg = pl["col_tiles"], pl["row_groups"], pl["rows_per_group"]
-    channels = row_len // hw
+    true_len = row_len // pl["fold"]                     # glued rows: the channel follows from the column
+    channels = true_len // hw                            # within the true row
     v_per_lane = span // (256 * vec)
     ws_min = np.full(P * J * kmax, np.nan, np.float32)
     ws_max = np.full(P * J * kmax, np.nan, np.float32)
@@ -192,7 +200,7 @@ def _emulate_range_cols(x2d, pl, vec):
                 cols = j * span + (np.arange(256) + v * 256) * vec
                 for col in cols[cols < row_len]:
                     for e in range(vec):
-                        k = (col + e) // hw - ch_first
+                        k = ((col + e) % true_len) // hw - ch_first
                         assert 0 <= k < kmax
                         seg = x2d[r0:r1, col + e]
                         lds_min[k] = min(lds_min[k], seg.min())
@@ -218,7 +226,10 @@ def _emulate_range_cols(x2d, pl, vec):
 
 @pytest.mark.parametrize("shape,dtype", [((5, 37, 9, 8), G.GRANQ_F32), ((6, 100, 7, 7), G.GRANQ_F32),
                                          ((3, 40, 1, 1), G.GRANQ_F32), ((9, 24, 14, 14), G.GRANQ_BF16),
-                                         ((4, 3000, 1, 1), G.GRANQ_BF16), ((1, 1, 1, 16384), G.GRANQ_F32)])
+                                         ((4, 3000, 1, 1), G.GRANQ_BF16), ((1, 1, 1, 16384), G.GRANQ_F32),
+                                         # short rows, glued: channels-last views and an odd row count
+                                         ((512, 64, 1, 1), G.GRANQ_F32), ((96, 24, 1, 4), G.GRANQ_BF16),
+                                         ((489, 10, 2, 2), G.GRANQ_F32), ((331, 16, 1, 1), G.GRANQ_F32)])
 def test_two_pass_reduction_indexing(shape, dtype):
     n, c, h, w = shape
     pl = G.granq_plan_describe(G.make_desc(n, c, h, w, dtype))

@@ -289,3 +289,23 @@ def test_binary16_store_rounds_twice():
         want = oracle_path(to_numpy(x), 4, None, scale=s, zero_point=z)
         assert np.all(want["codes"] == 3)
         assert_parity(got, want, "binary16 double rounding, offset %d" % offset)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(6, 64, 14, 14), (3, 24, 7, 5), (16, 256, 4, 4), (5, 3, 9, 8)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_channels_last_is_the_view_with_unit_maps(shape, dtype):
+    """A channels-last (N,H,W,C) tensor is the NCHW call on {N*H*W, C, 1, 1}: the results must be
+    those of the oracle on the ordinary NCHW tensor, element for element after the permutation."""
+    n, c, h, w = shape
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), seed=4, device=DEV, dtype=dtype)
+    dy = workloads.make_grad(shape, 4, DEV, dtype)
+    want = oracle_path(to_numpy(x), 4, to_numpy(dy))
+    x_cl = x.permute(0, 2, 3, 1).contiguous().view(n * h * w, c, 1, 1)
+    dy_cl = dy.permute(0, 2, 3, 1).contiguous().view(n * h * w, c, 1, 1)
+    got = gpu_path(x_cl, 4, dy_cl)
+
+    def back(a):
+        return np.ascontiguousarray(a.reshape(n, h, w, c).transpose(0, 3, 1, 2))
+    got = dict(got, xhat=back(got["xhat"]), codes=back(got["codes"]), dx=back(got["dx"]))
+    assert_parity(got, want, "channels-last %s" % (shape,))
