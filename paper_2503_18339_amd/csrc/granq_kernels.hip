@@ -555,8 +555,21 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
 
     const int32_t ch_first = (int32_t)fastdiv(j * (uint32_t)plan.span, plan.hw_div);
     constexpr int NG = Slots<MODE, VEC>::N;             // channel groups per vector
+    // glued rows whose length divides the distance between a lane's vectors: all V vectors
+    // belong to the same channels, so they are combined in registers and only the first one
+    // goes to LDS (inactive vectors hold the identities)
+    if (V > 1 && plan.v_same) {
+#pragma unroll
+        for (int v = 1; v < V; ++v)
+#pragma unroll
+            for (int e = 0; e < NS; ++e) {
+                mn[0][e] = __builtin_fminf(mn[0][e], mn[v][e]);
+                mx[0][e] = __builtin_fmaxf(mx[0][e], mx[v][e]);
+            }
+    }
 #pragma unroll
     for (int v = 0; v < V; ++v) {
+        if (v > 0 && plan.v_same) break;               // block-uniform
         // inactive lanes hold the identities and point at the tile's first channel; with glued
         // rows the channel follows from the column within the true row
         const uint32_t col = true_column(active[v] ? cv[v] * VEC : j * (uint32_t)plan.span, plan);
@@ -619,31 +632,53 @@ __device__ __forceinline__ void prescale_one(float mn, float mx, float qmax, flo
 }
 
 // `scale` / `zero_point` may be null (ranges only); otherwise Eq. 5 is applied
-// to the channel's range in the same launch.
+// to the channel's range in the same launch.  WPC wavefronts share one channel:
+// 1 where a channel has a few hundred partials at most, 4 (the whole block, combined
+// through LDS) where it has thousands (glued rows: one partial per row group).
+template <int WPC>
 __global__ __launch_bounds__(kBlock) void range_cols_pass2(
     const float *__restrict__ ws_min, const float *__restrict__ ws_max,
     float *__restrict__ ch_min, float *__restrict__ ch_max, ColPlan plan,
     float qmax, float *__restrict__ scale, float *__restrict__ zero_point)
 {
+    constexpr int kPerBlock = kBlock / kWave / WPC;    // channels per block
+    __shared__ float part[2][kBlock / kWave];
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t c = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x / kWave);
-    if (c >= plan.channels) return;                    // whole wavefront leaves together
-    const int64_t j_lo = (c * plan.hw) / plan.span;
-    const int64_t j_hi = ((c + 1) * plan.hw - 1) / plan.span;
-    const int64_t nj = j_hi - j_lo + 1;
-    const int64_t total = nj * plan.row_groups;
+    const int wave = threadIdx.x / kWave;
+    const int64_t c = (int64_t)blockIdx.x * kPerBlock + wave / WPC;
+    const bool live = c < plan.channels;               // wave-uniform
     float mn = __builtin_inff(), mx = -__builtin_inff();
-    for (int64_t i = lane; i < total; i += kWave) {
-        const int64_t jj = j_lo + i % nj;
-        const int64_t pp = i / nj;
-        const int64_t k = c - (jj * plan.span) / plan.hw;
-        const int64_t at = (pp * plan.col_tiles + jj) * plan.kmax + k;
-        mn = __builtin_fminf(mn, ws_min[at]);
-        mx = __builtin_fmaxf(mx, ws_max[at]);
+    if (live) {
+        const uint32_t j_lo = (uint32_t)((c * plan.hw) / plan.span);
+        const uint32_t j_hi = (uint32_t)(((c + 1) * plan.hw - 1) / plan.span);
+        const uint32_t nj = j_hi - j_lo + 1;
+        const uint32_t total = nj * (uint32_t)plan.row_groups;     // < 2^31: tiles x 65535 at most
+        for (uint32_t i = (uint32_t)((wave % WPC) * kWave + lane); i < total; i += kWave * WPC) {
+            const uint32_t pp = i / nj;
+            const uint32_t jj = j_lo + (i - pp * nj);
+            const int64_t k = c - ((int64_t)jj * plan.span) / plan.hw;
+            const int64_t at = ((int64_t)pp * plan.col_tiles + jj) * plan.kmax + k;
+            mn = __builtin_fminf(mn, ws_min[at]);
+            mx = __builtin_fmaxf(mx, ws_max[at]);
+        }
+        mn = wave_min(mn);
+        mx = wave_max(mx);
     }
-    mn = wave_min(mn);
-    mx = wave_max(mx);
-    if (lane == 0) {
+    if (WPC > 1) {
+        if (lane == 0) {
+            part[0][wave] = mn;
+            part[1][wave] = mx;
+        }
+        __syncthreads();
+        if (wave % WPC == 0) {
+#pragma unroll
+            for (int w = 1; w < WPC; ++w) {
+                mn = __builtin_fminf(mn, part[0][wave + w]);
+                mx = __builtin_fmaxf(mx, part[1][wave + w]);
+            }
+        }
+    }
+    if (live && lane == 0 && wave % WPC == 0) {
         ch_min[c] = mn;
         ch_max[c] = mx;
         if (scale) {
@@ -1012,9 +1047,18 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
         else launch_range_cols<F16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
         st = launched();
         if (st != GRANQ_OK) return st;
-        dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave)), block(kBlock);
-        hipLaunchKernelGGL(range_cols_pass2, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
-                           qmax, scale, zero_point);
+        dim3 block(kBlock);
+        // partials per channel: row groups x the column tiles a channel overlaps
+        const int64_t per_channel = (int64_t)cp.row_groups * ((cp.hw - 1) / cp.span + 2);
+        if (per_channel > 512) {
+            dim3 grid((uint32_t)cp.channels);
+            hipLaunchKernelGGL(range_cols_pass2<kBlock / kWave>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+                               qmax, scale, zero_point);
+        } else {
+            dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave));
+            hipLaunchKernelGGL(range_cols_pass2<1>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+                               qmax, scale, zero_point);
+        }
         return launched();
     }
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);

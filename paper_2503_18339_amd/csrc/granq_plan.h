@@ -104,6 +104,7 @@ struct ColPlan {
     bool uniform;            // every 16-byte vector lies inside one channel
     int32_t mode;            // 0: one channel per vector, 1: at most two, 2: up to one per element
     int32_t fold;            // true rows glued into one row of this matrix (1: none)
+    bool v_same;             // glued rows: a lane's V vectors all see the same channels
     FastDiv true_len_div;    // column -> column within the true row (used when fold > 1)
     bool ok;                 // false: shape not eligible for the vector kernels
 };
@@ -122,6 +123,7 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
     ColPlan p{};
     p.ok = false;
     p.fold = 1;
+    p.v_same = false;
     int64_t rows = n, row_len = c * hw, chan = c, per = hw;
     if (c == 1) {
         // fold rows * row_len = E so that rows is a power of two up to 1024
@@ -144,6 +146,8 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
         int64_t f = block_span / row_len;
         while (f > 1 && rows % f != 0) --f;
         p.fold = (int32_t)f;
+        // a lane's vectors are block * vec columns apart: a whole number of true rows?
+        p.v_same = f > 1 && ((int64_t)block * vec) % row_len == 0;
         rows /= f;
         row_len *= f;
     }
