@@ -463,8 +463,8 @@ def cpu_baseline_threads(wl, bits, sample_batch, threads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--dtype", choices=["f32", "bf16", "f16"], default="f32")
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--cpu-sample-batch", type=int, default=256,
@@ -512,7 +512,7 @@ def main():
     k_ms = sum(e[0].elapsed_time(e[1]) for e in ev)
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
     roofline = {
-        "kernel": "granq::fq_bwd_cols<granq::%s, 1, %d, 0>" % ("F32" if args.dtype == "f32" else "BF16", bwd_rows),
+        "kernel": "granq::fq_bwd_cols<granq::%s, 1, %d, false, 0>" % (args.dtype.upper(), bwd_rows),
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "launches": k_launches, "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),

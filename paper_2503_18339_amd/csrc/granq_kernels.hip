@@ -173,7 +173,8 @@ __device__ inline uint32_t vector_channels(uint32_t col, const ColPlan &plan, in
 
 // Shared prologue: this lane's vectors within a row and their channels' registers.
 // Returns true when every channel this lane touches admits the fast quotient.
-template <typename T, int V, int MODE>
+// GLUED: the plan may have glued rows (column -> column within the true row first).
+template <typename T, int V, int MODE, bool GLUED = true>
 __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *__restrict__ scale,
                                   const float *__restrict__ zero_point,
                                   ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N], uint32_t (&split)[V],
@@ -187,7 +188,8 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
         active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
         int32_t ch[NS];
-        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? true_column(col, plan) : 0u, plan, ch);
+        const uint32_t tcol = GLUED ? true_column(col, plan) : col;
+        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? tcol : 0u, plan, ch);
 #pragma unroll
         for (int e = 0; e < NS; ++e) {
             const float s = scale[ch[e]], z = zero_point[ch[e]];
@@ -359,7 +361,9 @@ __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
             }
 }
 
-template <typename T, int V, int U, int MODE>
+// GLUED is a template argument here because a block of the backward is a single row of one
+// vector per lane: what its prologue loads and tests shows in the kernel's time (0.4 % measured).
+template <typename T, int V, int U, bool GLUED, int MODE>
 __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
     const typename T::vec_t *__restrict__ x, const typename T::vec_t *__restrict__ dy,
     typename T::vec_t *__restrict__ dx, const float *__restrict__ scale,
@@ -374,7 +378,7 @@ __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
     uint32_t split[V], cv[V];
     bool active[V];
     // wave-uniform: if any lane's channel needs the general division, the whole wavefront takes it
-    const bool fast = __all(lane_setup<T, V, MODE>(plan, j, scale, zero_point, cr, split, cv, active));
+    const bool fast = __all(lane_setup<T, V, MODE, GLUED>(plan, j, scale, zero_point, cr, split, cv, active));
 
     const int64_t r0 = (int64_t)p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
@@ -937,12 +941,19 @@ static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, vo
     auto xv = (const vec_t *)x;
     auto gv = (const vec_t *)dy;
     auto ov = (vec_t *)dx;
-    if (pl.mode == kOne)
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+    if (pl.fold > 1) {
+        if (pl.mode == kOne)
+            hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        else if (pl.mode == kTwo)
+            hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        else
+            hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+    } else if (pl.mode == kOne)
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
     else if (pl.mode == kTwo)
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
     else
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
 }
 
 template <typename T, int V>
