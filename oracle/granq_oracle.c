@@ -217,7 +217,7 @@ static float raw_code(float x, float s, float z)
     return rintf(v);
 }
 
-/* Codes are kept inside b bits: clamp to [0, 2^b - 1] (this build's reading; not in Eq. 1). */
+/* Codes are kept inside b bits: clamp to [0, 2^b - 1] (a reading taken here; the clamp is not in Eq. 1). */
 static float clamp_code(float u, float qmax)
 {
     return fminf(fmaxf(u, 0.0f), qmax);
@@ -234,7 +234,7 @@ static float dequantize(float q, float s, float z)
  * Quantize, clamp, dequantize (Eq. 1 then the dequantization of Eq. 6; Alg. 1,
  * the quantize and the "dequantize & pre-scale" steps):
  *     u     = round(x / s_c + z_c)
- *     q     = clamp(u, 0, 2^b - 1)         (the clamp is this build's reading)
+ *     q     = clamp(u, 0, 2^b - 1)         (the clamp is a reading taken here, not in the paper)
  *     x_hat = s_c * (q - z_c)
  * codes may be NULL.
  */
