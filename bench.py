@@ -384,6 +384,9 @@ def integer_accumulation(wl, bits, device):
         y = torch.empty(shape[0], o, hw, hw, device=device)
         t_fold = _timeit(lambda: G.granq_fold_weights(wt, q.scale, q.zero_point, wq, corr, a, stream))
         t_int = _timeit(lambda: G.granq_conv1x1_int8(codes, wq, corr, a, bits, y, stream))
+        y16 = torch.empty(shape[0], o, hw, hw, dtype=torch.bfloat16, device=device)
+        t_int16 = _timeit(lambda: G.granq_conv1x1_int8_as(codes, wq, corr, a, bits, y16, stream))
+        del y16
         t_f32 = _timeit(lambda: torch.nn.functional.conv2d(xh, wt))
         ref = torch.nn.functional.conv2d(xh, wt)
         rel = float((y - ref).norm() / ref.norm())
@@ -394,7 +397,8 @@ def integer_accumulation(wl, bits, device):
         ops = 2.0 * o * c * shape[0] * hw * hw
         rows["%d->%d@%dx%d" % (c, o, hw, hw)] = {
             "int8_mfma_from_codes_us": round(t_int, 1), "int8_GBs": round((e + y.numel() * 4) / t_int / 1e3, 1),
-            "int8_TOPs": round(ops / t_int / 1e6, 2), "fold_weights_us": round(t_fold, 1),
+            "int8_TOPs": round(ops / t_int / 1e6, 2), "int8_mfma_bf16_output_us": round(t_int16, 1),
+            "fold_weights_us": round(t_fold, 1),
             "quantize_to_codes_only_us": round(t_q, 1), "quantize_GBs": round(e * 5 / t_q / 1e3, 1),
             "torch_f32_conv_on_x_hat_us": round(t_f32, 1), "torch_bf16_conv_on_bf16_x_hat_us": round(t_b16, 1),
             "relative_difference_to_float_conv": round(rel, 5)}

@@ -298,6 +298,16 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
                                   const int8_t *wq, const int32_t *corr, const float *out_scale,
                                   int bits, float *y, void *stream);
 
+/*
+ * The same convolution with y stored as y_dtype: the binary32 result above is narrowed to
+ * bfloat16 or binary16 with round to nearest even on the store (GRANQ_F32: identical to
+ * granq_conv1x1_int8).  The output is what bounds this kernel, so 16-bit storage nearly
+ * halves its time.  The matrix-core path then needs y 8-byte aligned.
+ */
+granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
+                                     const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                     int bits, granq_dtype_t y_dtype, void *y, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,7 @@ EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "gra
            "granq_prescale", "granq_calibrate", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
            "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
-           "granq_fold_weights", "granq_conv1x1_int8")
+           "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_as")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -94,6 +94,7 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_rowwise_fakequant_bwd_multi.argtypes = [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
     lib.granq_fold_weights.argtypes = [_vp, _vp, _vp, ctypes.c_int64, ctypes.c_int64, _vp, _vp, _vp, _vp]
     lib.granq_conv1x1_int8.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, _vp, _vp]
+    lib.granq_conv1x1_int8_as.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int, _vp, _vp]
     lib.granq_distortion_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_distortion.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -345,6 +346,24 @@ def granq_conv1x1_int8(codes: torch.Tensor, wq: torch.Tensor, corr: torch.Tensor
     _check(load().granq_conv1x1_int8(_dev(codes, "codes"), ctypes.byref(d), o, _dev(wq, "wq"),
                                      _dev(corr, "corr"), _vec(out_scale, o, "out_scale"), int(bits),
                                      _dev(y, "y"), _stream(stream)), "granq_conv1x1_int8")
+
+
+def granq_conv1x1_int8_as(codes: torch.Tensor, wq: torch.Tensor, corr: torch.Tensor, out_scale: torch.Tensor,
+                          bits: int, y: torch.Tensor, stream=None) -> None:
+    """granq_conv1x1_int8 with y stored in y's own dtype (float32, bfloat16 or float16)."""
+    if codes.dtype != torch.uint8 or codes.dim() != 4:
+        raise ValueError("codes must be a uint8 (N, C, H, W) tensor")
+    n, c, h, w = (int(v) for v in codes.shape)
+    o = int(wq.shape[0])
+    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int32 or corr.numel() != o:
+        raise ValueError("wq must be int8 (O, C) and corr int32 (O)")
+    if y.numel() != n * o * h * w:
+        raise ValueError("y must have N*O*H*W elements")
+    d = make_desc(n, c, h, w, GRANQ_F32)
+    _check(load().granq_conv1x1_int8_as(_dev(codes, "codes"), ctypes.byref(d), o, _dev(wq, "wq"),
+                                        _dev(corr, "corr"), _vec(out_scale, o, "out_scale"), int(bits),
+                                        dtype_code(y.dtype), _dev(y, "y"), _stream(stream)),
+           "granq_conv1x1_int8_as")
 
 
 def granq_distortion_workspace_bytes(desc: granq_desc_t) -> int:

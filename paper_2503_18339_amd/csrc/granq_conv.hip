@@ -38,6 +38,19 @@ constexpr int kConvKChunk = 512;           // channels staged in LDS at a time
 constexpr int kConvDies = 8;               // XCDs of the chip
 constexpr int kConvPad = 16;               // bytes between LDS rows: 16-byte reads of 32 rows spread over all banks
 
+// Four neighbouring output pixels to y at element index `at` (a multiple of 4).
+template <typename OutT>
+__device__ __forceinline__ void store_pixels4(void *y, int64_t at, const f32x4 &v) {
+    if constexpr (OutT::ESIZE == 4) {
+        __builtin_nontemporal_store(v, (f32x4 *)((float *)y + at));
+    } else {
+        u32x2 w;
+        w.x = OutT::pack2(v.x, v.y);
+        w.y = OutT::pack2(v.z, v.w);
+        __builtin_nontemporal_store(w, (u32x2 *)((uint16_t *)y + at));
+    }
+}
+
 // dword i of `d` holds four neighbouring pixels of channel i; the result's dword q of
 // operand j holds channels 4q .. 4q+3 of pixel j.
 __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&b)[4]) {
@@ -67,9 +80,11 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // re-reads of a tile's codes by its other sweep groups hit that L2.  The channel loop is software-pipelined by hand: the loads of the next 32
 // channels are issued before the matrix instructions of the current ones, and
 // scheduling barriers keep them there.
+// OutT: storage of y (F32, BF16 or F16 traits): the binary32 result is narrowed on the store.
+template <typename OutT>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
-    const float *__restrict__ out_scale, float *__restrict__ y, int64_t c, int64_t hw, int64_t o,
+    const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
     int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_w[];   // kConvRows x lds_stride bytes
@@ -188,16 +203,17 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
                 v.y = sc * (float)(acc[t][1][r] - cz);
                 v.z = sc * (float)(acc[t][2][r] - cz);
                 v.w = sc * (float)(acc[t][3][r] - cz);
-                __builtin_nontemporal_store(v, (f32x4 *)(y + (n * o + oc) * hw + pb));
+                store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
             }
         }
     }
 }
 
 // Any shape: one thread per output element, integer loop over the channels.
+template <typename OutT>
 __global__ __launch_bounds__(kBlock) void conv1x1_i8_plain(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
-    const float *__restrict__ out_scale, float *__restrict__ y, int64_t c, int64_t hw, int64_t o)
+    const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o)
 {
     const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int64_t oc = blockIdx.y;
@@ -206,7 +222,7 @@ __global__ __launch_bounds__(kBlock) void conv1x1_i8_plain(
     int32_t acc = 0;
     for (int64_t ic = 0; ic < c; ++ic)
         acc += (int32_t)wq[oc * c + ic] * (int32_t)codes[(n * c + ic) * hw + k];
-    y[(n * o + oc) * hw + k] = out_scale[oc] * (float)(acc - corr[oc]);
+    OutT::store1(y, (n * o + oc) * hw + k, out_scale[oc] * (float)(acc - corr[oc]));
 }
 
 // One block per output channel: fold the activation scale into the weights and
@@ -271,19 +287,23 @@ granq_status_t granq_fold_weights(const float *w, const float *scale, const floa
     return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
 }
 
-granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
-                                  const int8_t *wq, const int32_t *corr, const float *out_scale,
-                                  int bits, float *y, void *stream) {
+// y_dtype: storage of y; the binary32 result is narrowed (round to nearest even) on the store.
+static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
+                                const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                int bits, granq_dtype_t y_dtype, void *y, void *stream) {
     if (!desc || !codes || !wq || !corr || !out_scale || !y) return GRANQ_ERR_INVALID_ARG;
     if (desc->n <= 0 || desc->c <= 0 || desc->h <= 0 || desc->w <= 0 || o <= 0) return GRANQ_ERR_INVALID_ARG;
     if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (y_dtype != GRANQ_F32 && y_dtype != GRANQ_BF16 && y_dtype != GRANQ_F16) return GRANQ_ERR_UNSUPPORTED;
     const int64_t c = desc->c, hw = desc->h * desc->w, n = desc->n;
     // |sum| <= 127 * 255 * C must stay inside int32
     if (c >= ((int64_t)1 << 16) || o >= 65536 || n >= 65536 || hw >= ((int64_t)1 << 40)) return GRANQ_ERR_UNSUPPORTED;
-    if (((uintptr_t)corr & 3u) || ((uintptr_t)out_scale & 3u) || ((uintptr_t)y & 3u)) return GRANQ_ERR_UNSUPPORTED;
+    const uintptr_t esize = y_dtype == GRANQ_F32 ? 4 : 2;
+    if (((uintptr_t)corr & 3u) || ((uintptr_t)out_scale & 3u) || ((uintptr_t)y & (esize - 1))) return GRANQ_ERR_UNSUPPORTED;
     hipStream_t hs = (hipStream_t)stream;
+    // a lane stores four neighbouring pixels at once
     const bool mfma = bits <= 7 && c % 16 == 0 && o % 32 == 0 && hw % 4 == 0 && c * hw < ((int64_t)1 << 25) &&
-                      ((uintptr_t)codes & 3u) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & 15u) == 0;
+                      ((uintptr_t)codes & 3u) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0;
     if (mfma) {
         const int64_t groups_total = n * (hw / 4);
         const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));
@@ -302,14 +322,38 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
         const int64_t blocks = (gx + kConvDies - 1) / kConvDies * kConvDies * gy;
         if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         dim3 grid((uint32_t)blocks), block(kBlock);
-        hipLaunchKernelGGL(conv1x1_i8_mfma, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                           groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
+        if (y_dtype == GRANQ_F32)
+            hipLaunchKernelGGL(conv1x1_i8_mfma<F32>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
+        else if (y_dtype == GRANQ_BF16)
+            hipLaunchKernelGGL(conv1x1_i8_mfma<BF16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
+        else
+            hipLaunchKernelGGL(conv1x1_i8_mfma<F16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
         return GRANQ_OK;
     }
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)o, (uint32_t)n), block(kBlock);
-    hipLaunchKernelGGL(conv1x1_i8_plain, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+    if (y_dtype == GRANQ_F32)
+        hipLaunchKernelGGL(conv1x1_i8_plain<F32>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+    else if (y_dtype == GRANQ_BF16)
+        hipLaunchKernelGGL(conv1x1_i8_plain<BF16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+    else
+        hipLaunchKernelGGL(conv1x1_i8_plain<F16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
     return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+}
+
+granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
+                                  const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                  int bits, float *y, void *stream) {
+    return conv_impl(codes, desc, o, wq, corr, out_scale, bits, GRANQ_F32, y, stream);
+}
+
+granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
+                                     const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                     int bits, granq_dtype_t y_dtype, void *y, void *stream) {
+    return conv_impl(codes, desc, o, wq, corr, out_scale, bits, y_dtype, y, stream);
 }
 
 }  // extern "C"

@@ -60,6 +60,42 @@ def test_conv_plain_path(shape, o, bits):
     _case(shape, o, bits)
 
 
+@pytest.mark.parametrize("ydtype", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+@pytest.mark.parametrize("shape,o,bits", [((3, 64, 14, 14), 64, 4), ((2, 528, 4, 4), 96, 6), ((2, 7, 5, 5), 3, 4),
+                                          ((2, 16, 8, 8), 32, 8)])
+def test_conv_output_in_16_bits(shape, o, bits, ydtype):
+    """y stored as bfloat16 / binary16: the oracle's binary32 result narrowed with round to nearest
+    even (torch's conversion for bfloat16, the oracle's own for binary16), bit for bit; both kernels."""
+    n, c, h, w = shape
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), 1, DEV)
+    out = gpu_path(x, bits)
+    g = torch.Generator(device=DEV).manual_seed(9)
+    wt = torch.randn(o, c, generator=g, device=DEV) * torch.exp(torch.randn(o, 1, generator=g, device=DEV))
+    s = torch.from_numpy(out["scale"]).to(DEV)
+    z = torch.from_numpy(out["zero_point"]).to(DEV)
+    wq = torch.empty((o, c), dtype=torch.int8, device=DEV)
+    corr = torch.empty((o,), dtype=torch.int32, device=DEV)
+    a = torch.empty((o,), device=DEV)
+    G.granq_fold_weights(wt, s, z, wq, corr, a)
+    codes = torch.from_numpy(out["codes"]).to(DEV)
+    y = torch.full((n, o, h, w), float("nan"), dtype=ydtype, device=DEV)
+    G.granq_conv1x1_int8_as(codes, wq, corr, a, bits, y)
+    torch.cuda.synchronize()
+    want32 = oracle.conv1x1_int8(out["codes"], wq.cpu().numpy(), corr.cpu().numpy(), a.cpu().numpy())
+    if ydtype == torch.float16:
+        want = oracle.f16_narrow(want32)
+    else:
+        want = torch.from_numpy(want32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = y.view(torch.int16).cpu().numpy().view(np.uint16)
+    bad = np.nonzero(got.ravel() != want.ravel())[0]
+    assert bad.size == 0, "y differs at %d of %d" % (bad.size, got.size)
+    # float32 through the same entry point is the plain call
+    y32 = torch.empty((n, o, h, w), device=DEV)
+    G.granq_conv1x1_int8_as(codes, wq, corr, a, bits, y32)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_view(y32.cpu().numpy()), bits_view(want32))
+
+
 def test_conv_approximates_the_float_convolution():
     """Eq. 3 folded into integers against Eq. 6 in binary64: within the rounding of the folded weights."""
     shape, o = (2, 64, 14, 14), 64
