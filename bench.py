@@ -225,8 +225,9 @@ def comparison_points(wl, bits, device):
         "channel_loop_baseline_ms": round(_timeit(channel_loop, 3) / 1e3, 4),
         "granq_vectorized_ms": round(_timeit(vectorized) / 1e3, 4),
         "paper_table5_ms_unknown_hardware": {"layerwise": 0.227, "channel_loop_baseline": 103.671, "granq": 0.236},
-        "note": "19 tensors, 4 launches per tensor (vectorized, layer-wise) or 4 per channel (loop); "
-                "launch-latency-bound at this size",
+        "note": "19 tensors; granq_calibrate_fakequant_fwd takes ONE launch per tensor here (a block per "
+                "channel: a channel holds at most 64 KB at batch 16), the layer-wise view three, the "
+                "channel loop four per channel; launch-latency-bound at this size",
     }
     del tens, outs
 

@@ -144,6 +144,21 @@ granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * granq_calibrate followed by granq_fakequant_fwd in one call: Alg. 1 up to the
+ * accumulation (Eq. 4, 5, 1, 6).  Every output is bit-identical to that of the
+ * separate calls; arguments, workspace and errors as for them (x_hat or codes may
+ * be NULL, not both).  A tensor whose channel holds at most 128 KB (n*h*w
+ * elements: the regime of the paper's own latency table, batch 16 on CIFAR-size
+ * maps) is handled in ONE launch, a block per channel; larger tensors take the
+ * three launches of the two calls.
+ */
+granq_status_t granq_calibrate_fakequant_fwd(const void *x, const granq_desc_t *desc, int bits,
+                                             float *ch_min, float *ch_max,
+                                             float *scale, float *zero_point,
+                                             void *x_hat, uint8_t *codes_or_null,
+                                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Quantize, clamp, dequantize (Eq. 1, then the dequantization of Eq. 6; Alg. 1's
  * "quantize" and "dequantize & pre-scale" steps):
  *     u     = round_half_even(x / scale[c] + zero_point[c])

@@ -11,7 +11,7 @@ from .binding import (GRANQ_BF16, GRANQ_F16, GRANQ_ERR_HIP, GRANQ_ERR_INVALID_AR
 from .binding import granq_fakequant_bwd_mask, granq_fakequant_fwd_mask, granq_mask_bytes
 from .binding import (granq_rowwise_fakequant_bwd_multi, granq_rowwise_fakequant_multi, rowwise_bwd_items,
                       rowwise_items)
-from .binding import granq_calibrate, granq_conv1x1_int8, granq_conv1x1_int8_as, granq_fold_weights
+from .binding import granq_calibrate, granq_calibrate_fakequant_fwd, granq_conv1x1_int8, granq_conv1x1_int8_as, granq_fold_weights
 from .binding import granq_distortion, granq_distortion_workspace_bytes
 from .binding import (granq_cmp_accumulate_inloop, granq_cmp_accumulate_prescaled,
                       granq_cmp_channel_loop_fwd)
@@ -20,7 +20,7 @@ from .quantizer import ActivationQuantizer
 __all__ = [
     "GRANQ_OK", "GRANQ_ERR_INVALID_ARG", "GRANQ_ERR_UNSUPPORTED", "GRANQ_ERR_WORKSPACE",
     "GRANQ_ERR_HIP", "GRANQ_F32", "GRANQ_BF16", "GRANQ_F16", "GranqError", "granq_desc_t", "make_desc", "desc_of",
-    "granq_workspace_bytes", "granq_plan_describe", "granq_range_reduce", "granq_prescale", "granq_calibrate", "granq_conv1x1_int8_as", "granq_fakequant_fwd",
+    "granq_workspace_bytes", "granq_plan_describe", "granq_range_reduce", "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_conv1x1_int8_as", "granq_fakequant_fwd",
     "granq_fakequant_bwd", "load", "library_path", "status_string", "version",
     "granq_fold_weights", "granq_conv1x1_int8",
     "granq_distortion", "granq_distortion_workspace_bytes",

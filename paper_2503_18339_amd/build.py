@@ -13,8 +13,10 @@ LIB = os.path.join(PKG, "libgranq.so")
 SOURCES = [os.path.join(CSRC, "granq_kernels.hip"), os.path.join(CSRC, "granq_compare.hip"),
            os.path.join(CSRC, "granq_rowwise.hip"),
            os.path.join(CSRC, "granq_metrics.hip"),
-           os.path.join(CSRC, "granq_conv.hip")]
+           os.path.join(CSRC, "granq_conv.hip"),
+           os.path.join(CSRC, "granq_fused.hip")]
 HEADERS = [os.path.join(CSRC, "granq_device.h"), os.path.join(CSRC, "granq_plan.h"),
+           os.path.join(CSRC, "granq_block.h"),
            os.path.join(CSRC, "granq_quotient.h"), os.path.join(INCLUDE, "granq.h"),
            os.path.join(INCLUDE, "granq_compare.h")]
 

@@ -9,6 +9,7 @@
 
 #include "granq.h"
 #include "granq_device.h"
+#include "granq_block.h"
 
 namespace granq {
 
@@ -33,25 +34,6 @@ __device__ inline int find_item(const int64_t *first_row, int count, int64_t b) 
     return i;
 }
 
-// Block-wide min and max, result in every thread.
-__device__ inline void block_minmax(float &mn, float &mx, float (*part)[kBlock / kWave]) {
-    mn = wave_min(mn);
-    mx = wave_max(mx);
-    const int wave = threadIdx.x / kWave;
-    if ((threadIdx.x & (kWave - 1)) == 0) {
-        part[0][wave] = mn;
-        part[1][wave] = mx;
-    }
-    __syncthreads();
-    mn = part[0][0];
-    mx = part[1][0];
-#pragma unroll
-    for (int w = 1; w < kBlock / kWave; ++w) {
-        mn = __builtin_fminf(mn, part[0][w]);
-        mx = __builtin_fmaxf(mx, part[1][w]);
-    }
-}
-
 template <typename T>
 __global__ __launch_bounds__(kBlock) void rowq_fwd_kernel(RowqBatch batch, float qmax)
 {
@@ -71,10 +53,8 @@ __global__ __launch_bounds__(kBlock) void rowq_fwd_kernel(RowqBatch batch, float
     block_minmax(mn, mx, part);
 
     // Eq. 2, with the same degenerate-range rule as granq_prescale
-    const float range = mx - mn;
-    float s = range / qmax;
-    if (!(s >= FLT_MIN)) s = 1.0f;
-    const float z = __builtin_rintf((-mn) / s) + 0.0f;
+    float s, z;
+    channel_scale(mn, mx, qmax, s, z);
     if (threadIdx.x == 0) {
         it.scale[row] = s;
         it.zero_point[row] = z;

@@ -51,9 +51,11 @@ class ActivationQuantizer:
 
     def forward(self, x: torch.Tensor, x_hat: torch.Tensor, codes: Optional[torch.Tensor] = None,
                 stream=None, recalibrate: bool = True) -> torch.Tensor:
-        if recalibrate:
-            self.calibrate(x, stream)
-        B.granq_fakequant_fwd(x, self.scale, self.zero_point, self.bits, x_hat, codes, stream, self.desc)
+        if recalibrate:                  # ranges, parameters and the forward in one call
+            B.granq_calibrate_fakequant_fwd(x, self.bits, self.ch_min, self.ch_max, self.scale, self.zero_point,
+                                            x_hat, codes, self.workspace, stream, self.desc)
+        else:
+            B.granq_fakequant_fwd(x, self.scale, self.zero_point, self.bits, x_hat, codes, stream, self.desc)
         return x_hat
 
     def backward(self, x: torch.Tensor, dy: torch.Tensor, dx: torch.Tensor, stream=None) -> torch.Tensor:

@@ -101,6 +101,18 @@ def gpu_path(x: torch.Tensor, bits: int, dy: torch.Tensor = None, want_codes=Tru
     G.granq_fakequant_fwd(x, s, z, bits, x_hat, codes, desc=d)
     out["scale"], out["zero_point"] = s.cpu().numpy(), z.cpu().numpy()
     out["xhat"] = to_numpy(x_hat)
+    if scale is None and want_codes:
+        # ranges, parameters and forward in ONE call (a single launch for small channels) must
+        # write the same six results, bit for bit
+        six = [torch.full((c,), float("nan"), **f32) for _ in range(4)]
+        xh1 = torch.empty_like(x)
+        cd1 = torch.full(x.shape, 253, dtype=torch.uint8, device=dev)
+        G.granq_calibrate_fakequant_fwd(x, bits, six[0], six[1], six[2], six[3], xh1, cd1, ws, desc=d)
+        for got1, ref, name in zip(six, (ch_min, ch_max, s, z), ("min", "max", "scale", "zero_point")):
+            assert torch.equal(got1.view(torch.int32), ref.view(torch.int32)), "one-call forward: " + name
+        assert torch.equal(cd1, codes), "one-call forward: codes"
+        ib = torch.int32 if x.dtype == torch.float32 else torch.int16
+        assert torch.equal(xh1.view(ib), x_hat.view(ib)), "one-call forward: x_hat"
     if want_codes:
         out["codes"] = codes.cpu().numpy()
         # the quantize step alone (no x_hat) must write the same codes

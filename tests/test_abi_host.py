@@ -92,6 +92,21 @@ def test_argument_validation_happens_before_any_gpu_work():
     assert cal(z=18) == G.GRANQ_ERR_UNSUPPORTED
     assert cal(ws=0) == G.GRANQ_ERR_WORKSPACE
     assert cal(nb=need - 1) == G.GRANQ_ERR_WORKSPACE
+    # the one-call forward: small tensors (one launch) and large ones (three) refuse the same things
+    big = G.make_desc(64, 16, 64, 64, G.GRANQ_F32)           # 1 MB per channel: the three-launch path
+    for dsc in (good, big):
+        nb = G.granq_workspace_bytes(dsc)
+        one = lambda x=16, bits=4, mn=16, s=16, xh=16, cd=0, ws=16, n=nb: lib.granq_calibrate_fakequant_fwd(
+            x, ctypes.byref(dsc), bits, mn, 16, s, 16, xh, cd, ws, n, 0)
+        assert one(bits=0) == G.GRANQ_ERR_INVALID_ARG
+        assert one(x=0) == G.GRANQ_ERR_INVALID_ARG
+        assert one(mn=0) == G.GRANQ_ERR_INVALID_ARG
+        assert one(s=0) == G.GRANQ_ERR_INVALID_ARG
+        assert one(xh=0, cd=0) == G.GRANQ_ERR_INVALID_ARG
+        assert one(x=18) == G.GRANQ_ERR_UNSUPPORTED
+        assert one(ws=0) == G.GRANQ_ERR_WORKSPACE
+        assert one(n=nb - 1) == G.GRANQ_ERR_WORKSPACE
+    assert lib.granq_calibrate_fakequant_fwd(16, None, 4, 16, 16, 16, 16, 16, 0, 16, 1 << 20, 0) == G.GRANQ_ERR_INVALID_ARG
     out = ctypes.c_size_t()
     assert lib.granq_workspace_bytes(ctypes.byref(good), None) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_workspace_bytes(None, ctypes.byref(out)) == G.GRANQ_ERR_INVALID_ARG
