@@ -231,6 +231,22 @@ def comparison_points(wl, bits, device):
     }
     del tens, outs
 
+    # (2b) the sweep of the paper's Fig. 4 (latency against batch size; the paper prints no values)
+    sweep = {}
+    for b in (16, 32, 64, 128, 200):
+        tens = [workloads.make_activation(a.shape(b), a.law, r20.sigma, i, device) for i, a in enumerate(acts)]
+        outs = [torch.empty_like(t) for t in tens]
+        qcb = [G.ActivationQuantizer(t.shape, torch.float32, 3, device, view="channel") for t in tens]
+        qlb = [G.ActivationQuantizer(t.shape, torch.float32, 3, device, view="layer") for t in tens]
+
+        def run(qs):
+            for q, t, o in zip(qs, tens, outs):
+                q.forward(t, o, stream=stream)
+        sweep["batch_%d" % b] = {"granq_vectorized_ms": round(_timeit(lambda: run(qcb)) / 1e3, 4),
+                                 "layerwise_ms": round(_timeit(lambda: run(qlb)) / 1e3, 4)}
+        del tens, outs
+    out["fig4_setting_resnet20_cifar_3bit_latency_vs_batch"] = sweep
+
     # (3) accumulation forms on 256x64x56x56: scale inside the loop from 8-bit codes (Eq. 3)
     # vs accumulation of pre-scaled activations (Eq. 6)
     shape = (wl.batch, 64, 56, 56)
