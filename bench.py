@@ -220,7 +220,25 @@ def comparison_points(wl, bits, device):
         for t, o, v in zip(tens, outs, vecs):
             G.granq_cmp_channel_loop_fwd(t, 3, v[0], v[1], v[2], v[3], o, ws, stream)
 
+    # the same 19 calls captured once in a HIP graph and replayed: without the host's per-call cost
+    vectorized()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.stream(side):
+        for q, t, o in zip(qc, tens, outs):
+            q.forward(t, o, stream=side)
+    stream.wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cur = torch.cuda.current_stream()
+        for q, t, o in zip(qc, tens, outs):
+            q.forward(t, o, stream=cur)
+    t_graph = _timeit(graph.replay)
+
     out["table5_setting_resnet20_cifar_b16_3bit"] = {
+        "granq_vectorized_graph_replay_ms": round(t_graph / 1e3, 4),
         "layerwise_ms": round(_timeit(layerwise) / 1e3, 4),
         "channel_loop_baseline_ms": round(_timeit(channel_loop, 3) / 1e3, 4),
         "granq_vectorized_ms": round(_timeit(vectorized) / 1e3, 4),
