@@ -1,5 +1,6 @@
-"""The four calls captured into a HIP graph and replayed: every replay must reproduce
-the eager result, with eager work and synchronisations in between (needs an MI355X)."""
+"""The four calls, the one-call forms and the gate-bit pair captured into a HIP graph and
+replayed: every replay must reproduce the eager result, with eager work and synchronisations
+in between (needs an MI355X)."""
 import numpy as np
 import pytest
 import torch
@@ -11,7 +12,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-@pytest.mark.parametrize("shape,dtype", [((16, 64, 28, 28), torch.float32), ((8, 96, 7, 7), torch.bfloat16)])
+# the last two shapes are small enough for the one-launch path of the one-call forward
+@pytest.mark.parametrize("shape,dtype", [((16, 64, 28, 28), torch.float32), ((8, 96, 7, 7), torch.bfloat16),
+                                         ((16, 16, 32, 32), torch.float32), ((5, 33, 3, 3), torch.float16)])
 def test_graph_replays_match_eager(shape, dtype):
     bits = 4
     x = workloads.make_activation(shape, "linear", (0.05, 20.0), 1, DEV, dtype)
@@ -21,8 +24,10 @@ def test_graph_replays_match_eager(shape, dtype):
     dx = torch.empty_like(x)
     mask = torch.empty(G.granq_mask_bytes(q.desc), dtype=torch.uint8, device=DEV)
     dx_m = torch.empty_like(x)
+    x_hat1 = torch.empty_like(x)
 
     def step(stream):
+        q.forward(x, x_hat1, None, stream)       # ranges, parameters and forward in one call
         q.calibrate(x, stream)
         G.granq_fakequant_fwd_mask(x, q.scale, q.zero_point, bits, x_hat, mask, stream, q.desc)
         G.granq_fakequant_bwd(x, dy, q.scale, q.zero_point, bits, dx, stream, q.desc)
@@ -30,7 +35,7 @@ def test_graph_replays_match_eager(shape, dtype):
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (x_hat, dx, dx_m, q.scale, q.zero_point, q.ch_min, q.ch_max)]
+        return [t.clone() for t in (x_hat, x_hat1, dx, dx_m, q.scale, q.zero_point, q.ch_min, q.ch_max)]
 
     def check(ref):
         for a, b in zip(snapshot(), ref):
@@ -50,11 +55,11 @@ def test_graph_replays_match_eager(shape, dtype):
     for rep in range(4):
         src = x1 if rep % 2 == 0 else x2
         x.copy_(src)                       # eager work between replays: new input in the captured buffer
-        for t in (x_hat, dx, dx_m):
+        for t in (x_hat, x_hat1, dx, dx_m):
             t.fill_(7)                      # clobber the outputs
         step(torch.cuda.current_stream())   # eager reference for this input
         ref = snapshot()
-        for t in (x_hat, dx, dx_m, q.scale, q.zero_point):
+        for t in (x_hat, x_hat1, dx, dx_m, q.scale, q.zero_point):
             t.fill_(3)
         torch.cuda.synchronize()
         graph.replay()
