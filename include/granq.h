@@ -35,9 +35,13 @@
  *      per sample and channel (Alg. 1's
  *      C x H x W tensor with no batch axis)    desc {1, N*C, H, W}
  *      channel-wise weights, OIHW              desc {1, O, 1, I*kh*kw}
- *  - Errors: every function returns a granq_status_t; on any status other than
- *    GRANQ_OK nothing has been enqueued.  Calls are re-entrant; the library has
- *    no global mutable state.  Calls may be captured into a HIP graph.
+ *      channels-last activations (N,H,W,C)     desc {N*H*W, C, 1, 1}
+ *  - Errors: every function returns a granq_status_t.  Arguments are checked on
+ *    the host before anything is launched: on GRANQ_ERR_INVALID_ARG,
+ *    GRANQ_ERR_UNSUPPORTED and GRANQ_ERR_WORKSPACE nothing has been enqueued.
+ *    GRANQ_ERR_HIP (the runtime refused a launch) may follow kernels of the same
+ *    call that were already enqueued.  Calls are re-entrant; the library has no
+ *    global mutable state.  Calls may be captured into a HIP graph.
  */
 #ifndef GRANQ_H
 #define GRANQ_H
