@@ -69,3 +69,13 @@ def test_config4_mobilenetv2(idx):
 @pytest.mark.parametrize("idx", range(len(_distinct(CFG5))))
 def test_config5_resnet50_distinct_shapes(idx):
     _run(CFG5, _distinct(CFG5)[idx], 3, "f32", seed=idx)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_channels_last_view_full_size(dtype):
+    """(256,56,56,64) channels-last = the view {256*56*56, 64, 1, 1}: rows of 64 elements, glued by
+    the plans; full size, against the oracle on the same view."""
+    wl = workloads.Workload("channels_last", 256 * 56 * 56, (workloads.Act(64, 1, "linear", 1, "nhwc"),),
+                            (0.05, 20.0), (4,), (dtype,))
+    got = _run(wl, wl.acts[0], 4, dtype, seed=3)
+    assert np.any(got["zero_point"] != 0)
