@@ -508,7 +508,7 @@ def main():
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--cpu-sample-batch", type=int, default=256,
                     help="batch size of the sample the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--workload", choices=["config2", "config3", "config4", "config5"], default="config3",
+    ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5"], default="config3",
                     help="config3 = ResNet-18 ImageNet set (the metric's workload, default); the others "
                          "(ResNet-20 CIFAR, MobileNetV2, ResNet-50 sets) are timed without the extras")
     ap.add_argument("--no-extras", action="store_true", help="skip breakdown and other dtypes")
