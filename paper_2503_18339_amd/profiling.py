@@ -118,6 +118,33 @@ def load_record():
     return rec if rec.get("source_hash") == source_hash() else None
 
 
+TRACE_HEADER = """Kernel times of the default benchmark run (ResNet-18 ImageNet activation set, batch 256, float32,
+4-bit: range_reduce + prescale + forward per tensor, then backward in reverse; 20 warm-up + 200 timed steps)
+
+command (from /tmp with TMPDIR=/tmp, repository at $R, output under $OUT):
+  rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/trace -o bench -- \\
+      python3 $R/bench.py --no-extras --cpu-sample-batch 0
+summary made with:
+  python -m paper_2503_18339_amd.profiling trace $OUT/trace/bench_kernel_stats.csv
+(avg_us of the dominant kernel is to be compared with roofline.avg_launch_us of bench.py's JSON line)
+"""
+
+COUNTER_HEADER = """HBM traffic of the GranQ kernels on the default benchmark workload, from two rocprofv3 counter runs
+(ResNet-18 ImageNet activation set, batch 256, float32, 4-bit; FETCH_SIZE and WRITE_SIZE in KiB per dispatch)
+
+commands (from /tmp with TMPDIR=/tmp, repository at $R, output under $OUT), one counter per run:
+  rocprofv3 --pmc FETCH_SIZE --output-format csv -d $OUT/fetch -o bench -- \\
+      python3 $R/bench.py --no-extras --cpu-sample-batch 0 --steps 3 --warmup 1 --pmc-calibration
+  rocprofv3 --pmc WRITE_SIZE --output-format csv -d $OUT/write -o bench -- \\
+      python3 $R/bench.py --no-extras --cpu-sample-batch 0 --steps 3 --warmup 1 --pmc-calibration
+summary made with:
+  python -m paper_2503_18339_amd.profiling counters $OUT/fetch/bench_counter_collection.csv \\
+      $OUT/write/bench_counter_collection.csv --copy-bytes 822083584 --write-record
+(--pmc-calibration adds three plain device copies of the 822 MB tensor: what the two counters read for
+a known number of bytes gives the scale factors below)
+"""
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -130,9 +157,11 @@ def main(argv=None):
     c.add_argument("--write-record", action="store_true")
     args = ap.parse_args(argv)
     if args.cmd == "trace":
+        print(TRACE_HEADER)
         print(summarise_trace(args.stats_csv))
     else:
         text, record = summarise_counters(args.fetch_csv, args.write_csv, args.copy_bytes)
+        print(COUNTER_HEADER)
         print(text)
         if args.write_record:
             json.dump(record, open(RECORD, "w"), indent=1)
