@@ -152,6 +152,22 @@ def desc_of(x: torch.Tensor) -> granq_desc_t:
     return make_desc(x.shape[0], x.shape[1], h, hw // h if h else 0, _dtype_code(x))
 
 
+def _desc_for(x: torch.Tensor, desc: Optional[granq_desc_t], name: str = "x", typed: bool = True) -> granq_desc_t:
+    """The caller's descriptor, checked against the tensor it describes, or the tensor's own.
+
+    The C ABI cannot know how large a buffer is: a descriptor naming more elements, or a wider
+    element type, than the tensor holds would make the kernels run past the allocation."""
+    if desc is None:
+        return desc_of(x)
+    want = int(desc.n) * int(desc.c) * int(desc.h) * int(desc.w)
+    if min(int(desc.n), int(desc.c), int(desc.h), int(desc.w)) <= 0 or x.numel() != want:
+        raise ValueError("desc {%d,%d,%d,%d} names %d elements, %s holds %d"
+                         % (desc.n, desc.c, desc.h, desc.w, want, name, x.numel()))
+    if typed and dtype_code(x.dtype) != int(desc.dtype):
+        raise ValueError("desc.dtype is %d, %s is %s" % (desc.dtype, name, x.dtype))
+    return desc
+
+
 def _dev(t: torch.Tensor, name: str) -> int:
     if not t.is_cuda:
         raise ValueError("%s must live on the GPU (the library takes device pointers)" % name)
@@ -191,7 +207,7 @@ def granq_plan_describe(desc: granq_desc_t) -> dict:
 
 def granq_range_reduce(x: torch.Tensor, ch_min: torch.Tensor, ch_max: torch.Tensor,
                        workspace: torch.Tensor, stream=None, desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     _check(load().granq_range_reduce(_dev(x, "x"), ctypes.byref(d), _vec(ch_min, d.c, "ch_min"),
                                      _vec(ch_max, d.c, "ch_max"), _dev(workspace, "workspace"),
                                      workspace.numel() * workspace.element_size(), _stream(stream)),
@@ -209,7 +225,7 @@ def granq_prescale(ch_min: torch.Tensor, ch_max: torch.Tensor, bits: int, scale:
 def granq_calibrate(x: torch.Tensor, bits: int, ch_min: torch.Tensor, ch_max: torch.Tensor,
                     scale: torch.Tensor, zero_point: torch.Tensor, workspace: torch.Tensor,
                     stream=None, desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     _check(load().granq_calibrate(_dev(x, "x"), ctypes.byref(d), int(bits), _vec(ch_min, d.c, "ch_min"),
                                   _vec(ch_max, d.c, "ch_max"), _vec(scale, d.c, "scale"),
                                   _vec(zero_point, d.c, "zero_point"), _dev(workspace, "workspace"),
@@ -221,7 +237,7 @@ def granq_calibrate_fakequant_fwd(x: torch.Tensor, bits: int, ch_min: torch.Tens
                                   scale: torch.Tensor, zero_point: torch.Tensor, x_hat: Optional[torch.Tensor],
                                   codes: Optional[torch.Tensor], workspace: torch.Tensor, stream=None,
                                   desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     if x_hat is None and codes is None:
         raise ValueError("x_hat and codes are both None: nothing to write")
     if x_hat is not None and (x_hat.dtype != x.dtype or x_hat.numel() != x.numel()):
@@ -240,7 +256,7 @@ def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.
                         x_hat: Optional[torch.Tensor], codes: Optional[torch.Tensor] = None, stream=None,
                         desc: Optional[granq_desc_t] = None) -> None:
     """x_hat None: only the codes are written (codes must then be given)."""
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     if x_hat is None and codes is None:
         raise ValueError("x_hat and codes are both None: nothing to write")
     if x_hat is not None and (x_hat.dtype != x.dtype or x_hat.numel() != x.numel()):
@@ -260,7 +276,7 @@ def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.
 def granq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, scale: torch.Tensor,
                         zero_point: torch.Tensor, bits: int, dx: torch.Tensor, stream=None,
                         desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     if dy.dtype != x.dtype or dx.dtype != x.dtype or dy.numel() != x.numel() or dx.numel() != x.numel():
         raise ValueError("dy and dx must match x")
     _check(load().granq_fakequant_bwd(_dev(x, "x"), _dev(dy, "dy"), ctypes.byref(d),
@@ -278,7 +294,7 @@ def granq_mask_bytes(desc: granq_desc_t) -> int:
 def granq_fakequant_fwd_mask(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
                              x_hat: torch.Tensor, mask: torch.Tensor, stream=None,
                              desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     if x_hat.dtype != x.dtype or x_hat.numel() != x.numel():
         raise ValueError("x_hat must match x")
     if mask.dtype != torch.uint8 or mask.numel() < (x.numel() + 7) // 8:
@@ -291,7 +307,7 @@ def granq_fakequant_fwd_mask(x: torch.Tensor, scale: torch.Tensor, zero_point: t
 
 def granq_fakequant_bwd_mask(dy: torch.Tensor, mask: torch.Tensor, dx: torch.Tensor, stream=None,
                              desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(dy)
+    d = _desc_for(dy, desc, "dy")
     if dx.dtype != dy.dtype or dx.numel() != dy.numel():
         raise ValueError("dx must match dy")
     if mask.dtype != torch.uint8 or mask.numel() < (dy.numel() + 7) // 8:
@@ -397,7 +413,7 @@ def granq_distortion_workspace_bytes(desc: granq_desc_t) -> int:
 def granq_distortion(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
                      ch_sums: torch.Tensor, layer: torch.Tensor, workspace: torch.Tensor, stream=None,
                      desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
     if ch_sums.dtype != torch.float64 or ch_sums.numel() != 4 * d.c:
         raise ValueError("ch_sums must be float64 with 4*C entries")
     if layer.dtype != torch.float64 or layer.numel() != 6:
@@ -415,7 +431,9 @@ def granq_cmp_channel_loop_fwd(x: torch.Tensor, bits: int, ch_min: torch.Tensor,
                                scale: torch.Tensor, zero_point: torch.Tensor, x_hat: torch.Tensor,
                                workspace: torch.Tensor, stream=None,
                                desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x)
+    d = _desc_for(x, desc)
+    if x_hat.dtype != x.dtype or x_hat.numel() != x.numel():
+        raise ValueError("x_hat must match x")
     _check(load().granq_cmp_channel_loop_fwd(
         _dev(x, "x"), ctypes.byref(d), int(bits), _vec(ch_min, d.c, "ch_min"), _vec(ch_max, d.c, "ch_max"),
         _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"), _dev(x_hat, "x_hat"),
@@ -426,7 +444,8 @@ def granq_cmp_channel_loop_fwd(x: torch.Tensor, bits: int, ch_min: torch.Tensor,
 def granq_cmp_accumulate_inloop(codes: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor,
                                 weight: torch.Tensor, y: torch.Tensor, stream=None,
                                 desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or make_desc(codes.shape[0], codes.shape[1], codes.shape[2], codes.shape[3], GRANQ_F32)
+    d = _desc_for(codes, desc, "codes", typed=False) if desc is not None else make_desc(
+        codes.shape[0], codes.shape[1], codes.shape[2], codes.shape[3], GRANQ_F32)
     if codes.dtype != torch.uint8 or y.dtype != torch.float32 or y.numel() != d.n * d.h * d.w:
         raise ValueError("codes must be uint8 and y float32 with N*H*W entries")
     _check(load().granq_cmp_accumulate_inloop(
@@ -436,7 +455,7 @@ def granq_cmp_accumulate_inloop(codes: torch.Tensor, scale: torch.Tensor, zero_p
 
 def granq_cmp_accumulate_prescaled(x_hat: torch.Tensor, weight: torch.Tensor, y: torch.Tensor, stream=None,
                                    desc: Optional[granq_desc_t] = None) -> None:
-    d = desc or desc_of(x_hat)
+    d = _desc_for(x_hat, desc, "x_hat")
     if x_hat.dtype != torch.float32 or y.dtype != torch.float32 or y.numel() != d.n * d.h * d.w:
         raise ValueError("x_hat and y must be float32, y with N*H*W entries")
     _check(load().granq_cmp_accumulate_prescaled(

@@ -8,6 +8,7 @@
 
 #include "granq_compare.h"
 #include "granq_device.h"
+#include "granq_launch.h"
 
 namespace granq {
 
@@ -72,7 +73,7 @@ __global__ void cmp_prescale_one_channel(const float *__restrict__ ch_min,
 
 // grid (chunks of hw, n): quantize-dequantize the slab (n, ic).
 __global__ __launch_bounds__(kBlock) void cmp_fwd_one_channel(
-    const float *__restrict__ x, float *__restrict__ x_hat, int64_t c, int64_t hw, int64_t ic,
+    const float *x, float *x_hat, int64_t c, int64_t hw, int64_t ic,
     const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax)
 {
     const int64_t in = blockIdx.y;
@@ -128,8 +129,8 @@ static granq_status_t cmp_check(const granq_desc_t *d) {
     return GRANQ_OK;
 }
 
-static granq_status_t cmp_launched() {
-    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+static granq_status_t cmp_launched() {   // status of this call's own launches
+    return launched();
 }
 
 }  // namespace granq
@@ -154,10 +155,10 @@ granq_status_t granq_cmp_channel_loop_fwd(const float *x, const granq_desc_t *de
     float *ws = (float *)workspace;
     dim3 fgrid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)n);
     for (int64_t ic = 0; ic < c; ++ic) {               // the scalar loop over channels
-        hipLaunchKernelGGL(cmp_range_one_channel, dim3((uint32_t)n), dim3(kBlock), 0, hs, x, c, hw, ic, n, ws);
-        hipLaunchKernelGGL(cmp_finish_one_channel, dim3(1), dim3(kWave), 0, hs, ws, n, ic, ch_min, ch_max);
-        hipLaunchKernelGGL(cmp_prescale_one_channel, dim3(1), dim3(1), 0, hs, ch_min, ch_max, ic, qmax, scale, zero_point);
-        hipLaunchKernelGGL(cmp_fwd_one_channel, fgrid, dim3(kBlock), 0, hs, x, x_hat, c, hw, ic, scale, zero_point, qmax);
+        launch_kernel(cmp_range_one_channel, dim3((uint32_t)n), dim3(kBlock), 0, hs, x, c, hw, ic, n, ws);
+        launch_kernel(cmp_finish_one_channel, dim3(1), dim3(kWave), 0, hs, ws, n, ic, ch_min, ch_max);
+        launch_kernel(cmp_prescale_one_channel, dim3(1), dim3(1), 0, hs, ch_min, ch_max, ic, qmax, scale, zero_point);
+        launch_kernel(cmp_fwd_one_channel, fgrid, dim3(kBlock), 0, hs, x, x_hat, c, hw, ic, scale, zero_point, qmax);
         st = cmp_launched();
         if (st != GRANQ_OK) return st;
     }
@@ -172,7 +173,7 @@ granq_status_t granq_cmp_accumulate_inloop(const uint8_t *codes, const granq_des
     if (!codes || !scale || !zero_point || !weight || !y) return GRANQ_ERR_INVALID_ARG;
     const int64_t hw = desc->h * desc->w;
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)desc->n);
-    hipLaunchKernelGGL(cmp_accumulate_inloop, grid, dim3(kBlock), 0, (hipStream_t)stream, codes, desc->c, hw, scale, zero_point, weight, y);
+    launch_kernel(cmp_accumulate_inloop, grid, dim3(kBlock), 0, (hipStream_t)stream, codes, desc->c, hw, scale, zero_point, weight, y);
     return cmp_launched();
 }
 
@@ -183,7 +184,7 @@ granq_status_t granq_cmp_accumulate_prescaled(const float *x_hat, const granq_de
     if (!x_hat || !weight || !y) return GRANQ_ERR_INVALID_ARG;
     const int64_t hw = desc->h * desc->w;
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)desc->n);
-    hipLaunchKernelGGL(cmp_accumulate_prescaled, grid, dim3(kBlock), 0, (hipStream_t)stream, x_hat, desc->c, hw, weight, y);
+    launch_kernel(cmp_accumulate_prescaled, grid, dim3(kBlock), 0, (hipStream_t)stream, x_hat, desc->c, hw, weight, y);
     return cmp_launched();
 }
 

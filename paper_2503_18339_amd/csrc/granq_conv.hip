@@ -21,6 +21,7 @@
 
 #include "granq.h"
 #include "granq_device.h"
+#include "granq_launch.h"
 
 namespace granq {
 
@@ -282,9 +283,9 @@ granq_status_t granq_fold_weights(const float *w, const float *scale, const floa
     if (((uintptr_t)w & 3u) || ((uintptr_t)scale & 3u) || ((uintptr_t)zero_point & 3u) ||
         ((uintptr_t)corr & 3u) || ((uintptr_t)out_scale & 3u))
         return GRANQ_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(fold_weights_kernel, dim3((uint32_t)o), dim3(kBlock), 0, (hipStream_t)stream,
+    launch_kernel(fold_weights_kernel, dim3((uint32_t)o), dim3(kBlock), 0, (hipStream_t)stream,
                        w, scale, zero_point, c, wq, corr, out_scale);
-    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+    return launched();
 }
 
 // y_dtype: storage of y; the binary32 result is narrowed (round to nearest even) on the store.
@@ -323,25 +324,25 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         dim3 grid((uint32_t)blocks), block(kBlock);
         if (y_dtype == GRANQ_F32)
-            hipLaunchKernelGGL(conv1x1_i8_mfma<F32>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+            launch_kernel(conv1x1_i8_mfma<F32>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
                                groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         else if (y_dtype == GRANQ_BF16)
-            hipLaunchKernelGGL(conv1x1_i8_mfma<BF16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+            launch_kernel(conv1x1_i8_mfma<BF16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
                                groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         else
-            hipLaunchKernelGGL(conv1x1_i8_mfma<F16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+            launch_kernel(conv1x1_i8_mfma<F16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
                                groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
-        if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
+        if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
         return GRANQ_OK;
     }
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)o, (uint32_t)n), block(kBlock);
     if (y_dtype == GRANQ_F32)
-        hipLaunchKernelGGL(conv1x1_i8_plain<F32>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+        launch_kernel(conv1x1_i8_plain<F32>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
     else if (y_dtype == GRANQ_BF16)
-        hipLaunchKernelGGL(conv1x1_i8_plain<BF16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+        launch_kernel(conv1x1_i8_plain<BF16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
     else
-        hipLaunchKernelGGL(conv1x1_i8_plain<F16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
-    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+        launch_kernel(conv1x1_i8_plain<F16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+    return launched();
 }
 
 granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc, int64_t o,

@@ -12,6 +12,7 @@
 
 #include "granq.h"
 #include "granq_device.h"
+#include "granq_launch.h"
 #include "granq_plan.h"
 #include "granq_block.h"
 
@@ -48,7 +49,7 @@ __device__ inline void fused_block_minmax(float &mn, float &mx, float (*part)[kF
 // single elements; `units` = units in the channel, `slab_div` divides by the units per slab.
 template <typename T, bool VECTOR>
 __global__ __launch_bounds__(kFusedBlock) void fq_channel_block(
-    const void *__restrict__ x, void *__restrict__ x_hat, uint8_t *__restrict__ codes,
+    const void *x, void *x_hat, uint8_t *__restrict__ codes,
     float *__restrict__ ch_min, float *__restrict__ ch_max, float *__restrict__ scale,
     float *__restrict__ zero_point, float qmax, uint32_t units, int64_t c, FastDiv slab_div)
 {
@@ -131,10 +132,10 @@ static void launch_channel_block(bool vector, const void *x, void *x_hat, uint8_
                                  int64_t c, FastDiv slab_div, hipStream_t hs) {
     dim3 grid((uint32_t)c), block(kFusedBlock);
     if (vector)
-        hipLaunchKernelGGL((fq_channel_block<T, true>), grid, block, 0, hs, x, x_hat, codes, ch_min, ch_max, scale,
+        launch_kernel((fq_channel_block<T, true>), grid, block, 0, hs, x, x_hat, codes, ch_min, ch_max, scale,
                            zero_point, qmax, units, c, slab_div);
     else
-        hipLaunchKernelGGL((fq_channel_block<T, false>), grid, block, 0, hs, x, x_hat, codes, ch_min, ch_max, scale,
+        launch_kernel((fq_channel_block<T, false>), grid, block, 0, hs, x, x_hat, codes, ch_min, ch_max, scale,
                            zero_point, qmax, units, c, slab_div);
 }
 
@@ -194,7 +195,7 @@ granq_status_t granq_calibrate_fakequant_fwd(const void *x, const granq_desc_t *
     else
         launch_channel_block<F16>(vector, x, x_hat, codes_or_null, ch_min, ch_max, scale, zero_point, qmax,
                                   (uint32_t)units, desc->c, slab_div, hs);
-    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+    return launched();
 }
 
 }  // extern "C"

@@ -21,6 +21,7 @@
 
 #include "granq.h"
 #include "granq_device.h"
+#include "granq_launch.h"
 #include "granq_plan.h"
 #include "granq_quotient.h"
 
@@ -239,8 +240,8 @@ constexpr int kMask = 2;      // one bit per element: 1 where the clamp was inac
 constexpr int kCodesOnly = 3; // the codes, and x_hat is not written at all
 
 template <typename T, int V, int U, int MODE, int EXTRA, bool FAST, bool NT>
-__device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
-                                typename T::vec_t *__restrict__ x_hat, void *__restrict__ extra,
+__device__ inline void fwd_rows(const typename T::vec_t *x,
+                                typename T::vec_t *x_hat, void *__restrict__ extra,
                                 float qmax, int64_t row_vecs, int64_t r, int nrows,
                                 const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
                                 const uint32_t (&split)[V], const uint32_t (&cv)[V],
@@ -293,7 +294,7 @@ __device__ inline void fwd_rows(const typename T::vec_t *__restrict__ x,
 
 template <typename T, int V, int U, int MODE, int EXTRA>
 __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
-    const typename T::vec_t *__restrict__ x, typename T::vec_t *__restrict__ x_hat,
+    const typename T::vec_t *x, typename T::vec_t *x_hat,
     void *__restrict__ extra, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
@@ -329,9 +330,9 @@ __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
 }
 
 template <typename T, int V, int U, int MODE, bool FAST, bool NT>
-__device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
-                                const typename T::vec_t *__restrict__ dy,
-                                typename T::vec_t *__restrict__ dx, float qmax, int64_t row_vecs,
+__device__ inline void bwd_rows(const typename T::vec_t *x,
+                                const typename T::vec_t *dy,
+                                typename T::vec_t *dx, float qmax, int64_t row_vecs,
                                 int64_t r, int nrows, const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
                                 const uint32_t (&split)[V], const uint32_t (&cv)[V],
                                 const bool (&active)[V]) {
@@ -365,8 +366,8 @@ __device__ inline void bwd_rows(const typename T::vec_t *__restrict__ x,
 // vector per lane: what its prologue loads and tests shows in the kernel's time (0.4 % measured).
 template <typename T, int V, int U, bool GLUED, int MODE>
 __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
-    const typename T::vec_t *__restrict__ x, const typename T::vec_t *__restrict__ dy,
-    typename T::vec_t *__restrict__ dx, const float *__restrict__ scale,
+    const typename T::vec_t *x, const typename T::vec_t *dy,
+    typename T::vec_t *dx, const float *__restrict__ scale,
     const float *__restrict__ zero_point, float qmax, ColPlan plan)
 {
     constexpr int NS = Slots<MODE, T::VEC>::N;
@@ -404,8 +405,8 @@ __global__ __launch_bounds__(kEBlock) void fq_bwd_cols(
 // Reads dy and one bit per element instead of x and dy.
 template <typename T, int U, bool NT>
 __global__ __launch_bounds__(kEBlock) void fq_bwd_mask_cols(
-    const typename T::vec_t *__restrict__ dy, const uint8_t *__restrict__ mask,
-    typename T::vec_t *__restrict__ dx, ColPlan plan)
+    const typename T::vec_t *dy, const uint8_t *__restrict__ mask,
+    typename T::vec_t *dx, ColPlan plan)
 {
     constexpr int VEC = T::VEC;
     const int64_t row_vecs = plan.row_len / VEC;
@@ -459,7 +460,7 @@ __global__ __launch_bounds__(kBlock) void mask_from_x_bytes(
 
 template <typename T>
 __global__ __launch_bounds__(kBlock) void bwd_mask_bytes(
-    const void *__restrict__ dy, const uint8_t *__restrict__ mask, int64_t total, void *__restrict__ dx)
+    const void *dy, const uint8_t *__restrict__ mask, int64_t total, void *dx)
 {
     const int64_t nbytes = (total + 7) / 8;
     for (int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x; b < nbytes; b += (int64_t)gridDim.x * kBlock) {
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(kBlock) void bwd_mask_bytes(
 
 template <typename T, int V, int MODE>
 __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
-    const typename T::vec_t *__restrict__ x, float *__restrict__ ws_min,
+    const typename T::vec_t *x, float *__restrict__ ws_min,
     float *__restrict__ ws_max, ColPlan plan)
 {
     constexpr int VEC = T::VEC;
@@ -763,7 +764,7 @@ __global__ __launch_bounds__(kBlock) void range_rows_pass2(
 // wave-uniform.  `slabs` = N*C.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fq_fwd_rows(
-    const void *__restrict__ x, void *__restrict__ x_hat, uint8_t *__restrict__ codes,
+    const void *x, void *x_hat, uint8_t *__restrict__ codes,
     const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax,
     int64_t slabs, int64_t c, int64_t hw)
 {
@@ -784,7 +785,7 @@ __global__ __launch_bounds__(kBlock) void fq_fwd_rows(
 
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fq_bwd_rows(
-    const void *__restrict__ x, const void *__restrict__ dy, void *__restrict__ dx,
+    const void *x, const void *dy, void *dx,
     const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax,
     int64_t slabs, int64_t c, int64_t hw)
 {
@@ -889,10 +890,6 @@ static ColPlan range_plan(const granq_desc_t *d) {
     return p;
 }
 
-static granq_status_t launched() {
-    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
-}
-
 // Grid of the row kernels: enough wavefronts to fill the chip, no more than slabs.
 static uint32_t row_grid(int64_t slabs) {
     int64_t blocks = ceil_div(slabs, kBlock / kWave);
@@ -907,9 +904,9 @@ static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, void 
     dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
-    if (kind == kCodes) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
-    else if (kind == kCodesOnly) hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodesOnly>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
-    else hipLaunchKernelGGL((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    if (kind == kCodes) launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else if (kind == kCodesOnly) launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodesOnly>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
 }
 
 template <typename T, int V, int U>
@@ -919,9 +916,9 @@ static void launch_fwd_mask_cols(const ColPlan &pl, const void *x, void *x_hat, 
     dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kEBlock);
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
-    if (pl.mode == kOne) hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kOne, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
-    else if (pl.mode == kTwo) hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kTwo, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
-    else hipLaunchKernelGGL((fq_fwd_cols<T, V, U, kEach, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
+    if (pl.mode == kOne) launch_kernel((fq_fwd_cols<T, V, U, kOne, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
+    else if (pl.mode == kTwo) launch_kernel((fq_fwd_cols<T, V, U, kTwo, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
+    else launch_kernel((fq_fwd_cols<T, V, U, kEach, kMask>), grid, block, 0, st, xv, yv, mask, s, z, qmax, pl);
 }
 
 // kind: kNoExtra, kCodes (extra = codes) or kCodesOnly (extra = codes, x_hat unused)
@@ -943,17 +940,17 @@ static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, vo
     auto ov = (vec_t *)dx;
     if (pl.fold > 1) {
         if (pl.mode == kOne)
-            hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+            launch_kernel((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
         else if (pl.mode == kTwo)
-            hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+            launch_kernel((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
         else
-            hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+            launch_kernel((fq_bwd_cols<T, V, GRANQ_B_ROWS, true, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
     } else if (pl.mode == kOne)
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        launch_kernel((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kOne>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
     else if (pl.mode == kTwo)
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        launch_kernel((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kTwo>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
     else
-        hipLaunchKernelGGL((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
+        launch_kernel((fq_bwd_cols<T, V, GRANQ_B_ROWS, false, kEach>), grid, block, 0, st, xv, gv, ov, s, z, qmax, pl);
 }
 
 template <typename T, int V>
@@ -964,11 +961,11 @@ static void launch_range_cols(const ColPlan &pl, const void *x, float *ws_min, f
     size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
     auto xv = (const vec_t *)x;
     if (pl.mode == kOne)
-        hipLaunchKernelGGL((range_cols_pass1<T, V, kOne>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+        launch_kernel((range_cols_pass1<T, V, kOne>), grid, block, lds, st, xv, ws_min, ws_max, pl);
     else if (pl.mode == kTwo)
-        hipLaunchKernelGGL((range_cols_pass1<T, V, kTwo>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+        launch_kernel((range_cols_pass1<T, V, kTwo>), grid, block, lds, st, xv, ws_min, ws_max, pl);
     else
-        hipLaunchKernelGGL((range_cols_pass1<T, V, kEach>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+        launch_kernel((range_cols_pass1<T, V, kEach>), grid, block, lds, st, xv, ws_min, ws_max, pl);
 }
 
 static size_t col_ws_floats(const ColPlan &pl) {
@@ -1063,11 +1060,11 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
         const int64_t per_channel = (int64_t)cp.row_groups * ((cp.hw - 1) / cp.span + 2);
         if (per_channel > 512) {
             dim3 grid((uint32_t)cp.channels);
-            hipLaunchKernelGGL(range_cols_pass2<kBlock / kWave>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+            launch_kernel(range_cols_pass2<kBlock / kWave>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
                                qmax, scale, zero_point);
         } else {
             dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave));
-            hipLaunchKernelGGL(range_cols_pass2<1>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+            launch_kernel(range_cols_pass2<1>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
                                qmax, scale, zero_point);
         }
         return launched();
@@ -1078,15 +1075,15 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
     float *ws_max = ws_min + floats;
     dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        hipLaunchKernelGGL(range_rows_pass1<F32>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
+        launch_kernel(range_rows_pass1<F32>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
     else if (desc->dtype == GRANQ_BF16)
-        hipLaunchKernelGGL(range_rows_pass1<BF16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
+        launch_kernel(range_rows_pass1<BF16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
     else
-        hipLaunchKernelGGL(range_rows_pass1<F16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
+        launch_kernel(range_rows_pass1<F16>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
     st = launched();
     if (st != GRANQ_OK) return st;
     dim3 grid2((uint32_t)ceil_div(desc->c, kBlock));
-    hipLaunchKernelGGL(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, rp.row_groups,
+    launch_kernel(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, rp.row_groups,
                        qmax, scale, zero_point);
     return launched();
 }
@@ -1117,7 +1114,7 @@ granq_status_t granq_prescale(const float *ch_min, const float *ch_max, int64_t 
         return GRANQ_ERR_UNSUPPORTED;
     const float qmax = (float)((1 << bits) - 1);
     dim3 grid((uint32_t)ceil_div(c, kBlock)), block(kBlock);
-    hipLaunchKernelGGL(prescale_kernel, grid, block, 0, (hipStream_t)stream, ch_min, ch_max, c, qmax, scale, zero_point);
+    launch_kernel(prescale_kernel, grid, block, 0, (hipStream_t)stream, ch_min, ch_max, c, qmax, scale, zero_point);
     return launched();
 }
 
@@ -1148,11 +1145,11 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
     const int64_t slabs = desc->n * desc->c;
     dim3 grid(row_grid(slabs)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        hipLaunchKernelGGL(fq_fwd_rows<F32>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_fwd_rows<F32>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
     else if (desc->dtype == GRANQ_BF16)
-        hipLaunchKernelGGL(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
     else
-        hipLaunchKernelGGL(fq_fwd_rows<F16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_fwd_rows<F16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
     return launched();
 }
 
@@ -1179,11 +1176,11 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
     const int64_t slabs = desc->n * desc->c;
     dim3 grid(row_grid(slabs)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        hipLaunchKernelGGL(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
     else if (desc->dtype == GRANQ_BF16)
-        hipLaunchKernelGGL(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
     else
-        hipLaunchKernelGGL(fq_bwd_rows<F16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_bwd_rows<F16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
     return launched();
 }
 
@@ -1226,11 +1223,11 @@ granq_status_t granq_fakequant_fwd_mask(const void *x, const granq_desc_t *desc,
     const int64_t want = ceil_div(ceil_div(total, 8), kBlock);
     dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        hipLaunchKernelGGL(mask_from_x_bytes<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
+        launch_kernel(mask_from_x_bytes<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
     else if (desc->dtype == GRANQ_BF16)
-        hipLaunchKernelGGL(mask_from_x_bytes<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
+        launch_kernel(mask_from_x_bytes<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
     else
-        hipLaunchKernelGGL(mask_from_x_bytes<F16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
+        launch_kernel(mask_from_x_bytes<F16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->c, hw, total, mask);
     st = launched();
     if (st != GRANQ_OK) return st;
     return granq_fakequant_fwd(x, desc, scale, zero_point, bits, x_hat, nullptr, stream);
@@ -1249,20 +1246,20 @@ granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask, con
         dim3 grid((uint32_t)cp.col_tiles, (uint32_t)cp.row_groups), block(kEBlock);
         const bool nt = cp.nt_row_end > 0;
         if (desc->dtype == GRANQ_F32) {
-            if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
-            else hipLaunchKernelGGL((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
+            if (nt) launch_kernel((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
+            else launch_kernel((fq_bwd_mask_cols<F32, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const F32::vec_t *)dy, mask, (F32::vec_t *)dx, cp);
         } else {
             // gating moves 16-bit patterns without interpreting them: one kernel for both 16-bit types
-            if (nt) hipLaunchKernelGGL((fq_bwd_mask_cols<Pack16, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const Pack16::vec_t *)dy, mask, (Pack16::vec_t *)dx, cp);
-            else hipLaunchKernelGGL((fq_bwd_mask_cols<Pack16, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const Pack16::vec_t *)dy, mask, (Pack16::vec_t *)dx, cp);
+            if (nt) launch_kernel((fq_bwd_mask_cols<Pack16, GRANQ_B_ROWS, true>), grid, block, 0, hs, (const Pack16::vec_t *)dy, mask, (Pack16::vec_t *)dx, cp);
+            else launch_kernel((fq_bwd_mask_cols<Pack16, GRANQ_B_ROWS, false>), grid, block, 0, hs, (const Pack16::vec_t *)dy, mask, (Pack16::vec_t *)dx, cp);
         }
         return launched();
     }
     const int64_t total = desc->n * desc->c * desc->h * desc->w;
     const int64_t want = ceil_div(ceil_div(total, 8), kBlock);
     dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
-    if (desc->dtype == GRANQ_F32) hipLaunchKernelGGL(bwd_mask_bytes<F32>, grid, block, 0, hs, dy, mask, total, dx);
-    else hipLaunchKernelGGL(bwd_mask_bytes<Pack16>, grid, block, 0, hs, dy, mask, total, dx);
+    if (desc->dtype == GRANQ_F32) launch_kernel(bwd_mask_bytes<F32>, grid, block, 0, hs, dy, mask, total, dx);
+    else launch_kernel(bwd_mask_bytes<Pack16>, grid, block, 0, hs, dy, mask, total, dx);
     return launched();
 }
 

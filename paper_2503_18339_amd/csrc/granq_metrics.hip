@@ -13,6 +13,7 @@
 
 #include "granq.h"
 #include "granq_device.h"
+#include "granq_launch.h"
 #include "granq_plan.h"
 
 namespace granq {
@@ -138,16 +139,16 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc, const f
     double *ws = (double *)workspace;
     dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        hipLaunchKernelGGL(distortion_pass1<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
+        launch_kernel(distortion_pass1<F32>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
     else if (desc->dtype == GRANQ_BF16)
-        hipLaunchKernelGGL(distortion_pass1<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
+        launch_kernel(distortion_pass1<BF16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
     else
-        hipLaunchKernelGGL(distortion_pass1<F16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
-    if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
-    hipLaunchKernelGGL(distortion_pass2, dim3((uint32_t)ceil_div(desc->c * 4, kBlock)), block, 0, hs, ws, desc->c, rp.row_groups, ch_sums);
-    if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
-    hipLaunchKernelGGL(distortion_layer, dim3(1), dim3(kWave), 0, hs, ch_sums, desc->c, layer);
-    return hipGetLastError() == hipSuccess ? GRANQ_OK : GRANQ_ERR_HIP;
+        launch_kernel(distortion_pass1<F16>, grid, block, 0, hs, x, scale, zero_point, qmax, desc->n, desc->c, hw, rp, ws);
+    if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
+    launch_kernel(distortion_pass2, dim3((uint32_t)ceil_div(desc->c * 4, kBlock)), block, 0, hs, ws, desc->c, rp.row_groups, ch_sums);
+    if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
+    launch_kernel(distortion_layer, dim3(1), dim3(kWave), 0, hs, ch_sums, desc->c, layer);
+    return launched();
 }
 
 }  // extern "C"

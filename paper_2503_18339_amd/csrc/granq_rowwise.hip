@@ -9,6 +9,7 @@
 
 #include "granq.h"
 #include "granq_device.h"
+#include "granq_launch.h"
 #include "granq_block.h"
 
 namespace granq {
@@ -117,12 +118,12 @@ granq_status_t granq_rowwise_fakequant_multi(const granq_rowq_item_t *items, int
         for (int i = batch.count; i <= kMaxItems; ++i) batch.first_row[i] = rows;
         if (rows >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         if (dtype == GRANQ_F32)
-            hipLaunchKernelGGL(rowq_fwd_kernel<F32>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+            launch_kernel(rowq_fwd_kernel<F32>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
         else if (dtype == GRANQ_BF16)
-            hipLaunchKernelGGL(rowq_fwd_kernel<BF16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+            launch_kernel(rowq_fwd_kernel<BF16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
         else
-            hipLaunchKernelGGL(rowq_fwd_kernel<F16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
-        if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
+            launch_kernel(rowq_fwd_kernel<F16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+        if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
     }
     return GRANQ_OK;
 }
@@ -154,12 +155,12 @@ granq_status_t granq_rowwise_fakequant_bwd_multi(const granq_rowq_bwd_item_t *it
         for (int i = batch.count; i <= kMaxItems; ++i) batch.first_row[i] = rows;
         if (rows >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         if (dtype == GRANQ_F32)
-            hipLaunchKernelGGL(rowq_bwd_kernel<F32>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+            launch_kernel(rowq_bwd_kernel<F32>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
         else if (dtype == GRANQ_BF16)
-            hipLaunchKernelGGL(rowq_bwd_kernel<BF16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+            launch_kernel(rowq_bwd_kernel<BF16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
         else
-            hipLaunchKernelGGL(rowq_bwd_kernel<F16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
-        if (hipGetLastError() != hipSuccess) return GRANQ_ERR_HIP;
+            launch_kernel(rowq_bwd_kernel<F16>, dim3((uint32_t)rows), dim3(kBlock), 0, (hipStream_t)stream, batch, qmax);
+        if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
     }
     return GRANQ_OK;
 }

@@ -257,3 +257,40 @@ def test_two_pass_reduction_indexing(shape, dtype):
         assert mn[0] == x.min() and mx[0] == x.max() and mn.size == 1
     else:
         assert np.array_equal(mn, x.min(axis=(0, 2, 3))) and np.array_equal(mx, x.max(axis=(0, 2, 3)))
+
+
+def test_binding_refuses_descriptor_that_does_not_fit_the_tensor():
+    """The wrappers compare a caller-supplied descriptor with the tensor before any pointer
+    is handed over: a descriptor naming more elements or a wider type would send the kernels
+    past the allocation.  (CPU tensors: the check comes before the device check.)"""
+    import torch
+    x = torch.zeros(2, 3, 4, 4)
+    v = torch.zeros(3)
+    ws = torch.zeros(64, dtype=torch.uint8)
+    too_big = G.make_desc(4, 3, 4, 4, G.GRANQ_F32)
+    wrong_type = G.make_desc(2, 3, 4, 4, G.GRANQ_BF16)
+    not_positive = G.make_desc(2, 3, 0, 4, G.GRANQ_F32)
+    for d in (too_big, wrong_type, not_positive):
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_range_reduce(x, v, v, ws, desc=d)
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_calibrate(x, 4, v, v, v, v, ws, desc=d)
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_calibrate_fakequant_fwd(x, 4, v, v, v, v, x, None, ws, desc=d)
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_fakequant_fwd(x, v, v, 4, x, desc=d)
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_fakequant_bwd(x, x, v, v, 4, x, desc=d)
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_fakequant_fwd_mask(x, v, v, 4, x, ws, desc=d)
+        with pytest.raises(ValueError, match="desc"):
+            G.granq_fakequant_bwd_mask(x, ws, x, desc=d)
+    # a half-precision tensor under a float32 descriptor of the same element count
+    xh = torch.zeros(2, 3, 4, 4, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="dtype"):
+        G.granq_fakequant_fwd(xh, v, v, 4, xh, desc=G.make_desc(2, 3, 4, 4, G.GRANQ_F32))
+    # the quantizer object passes its own descriptor with whatever tensor it is given
+    q_desc = G.make_desc(2, 3, 4, 4, G.GRANQ_F32)
+    with pytest.raises(ValueError, match="desc"):
+        G.granq_fakequant_bwd(torch.zeros(1, 3, 4, 4), torch.zeros(1, 3, 4, 4), v, v, 4, torch.zeros(1, 3, 4, 4),
+                              desc=q_desc)

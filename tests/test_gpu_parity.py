@@ -155,6 +155,66 @@ def test_in_place_forward_and_gradient():
     assert np.array_equal(dy2.cpu().numpy(), ref["dx"])
 
 
+def _misaligned_like(t, off_elems):
+    """A copy of t that starts off_elems elements into a fresh allocation."""
+    buf = torch.zeros(t.numel() + 16, dtype=t.dtype, device=t.device)
+    v = buf[off_elems:off_elems + t.numel()].view(t.shape)
+    v.copy_(t)
+    return v
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
+@pytest.mark.parametrize("shape,misaligned", [
+    ((4, 16, 14, 14), False),     # every 16-byte vector inside one channel
+    ((5, 24, 7, 7), False),       # H*W = 49: vectors straddle two channels
+    ((64, 96, 1, 1), False),      # H*W = 1: every element its own channel
+    ((3, 8, 8, 8), True),         # pointer aligned to the element only: element-wise kernels
+    ((2, 3, 7, 7), False),        # rows that are no whole number of vectors: element-wise kernels
+    ((1, 1, 1, 4096), False),     # layer-wise view
+], ids=["one", "two", "each", "misaligned", "ragged", "layer"])
+def test_in_place_every_kernel_family(shape, misaligned, dtype):
+    """x_hat == x and dx == dy, which the header allows, in every kernel variant: results equal
+    the oracle's (the out-of-place ones), also for the one-call forward and the gate-bit pair."""
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), seed=11, device=DEV, dtype=dtype)
+    dy = workloads.make_grad(shape, 11, DEV, dtype)
+    ref = workloads.make_activation(shape, "linear", (0.05, 5.0), seed=12, device=DEV, dtype=dtype)
+    off = (1 if dtype == torch.float32 else 2) if misaligned else 0
+    mk = (lambda t: _misaligned_like(t, off)) if misaligned else (lambda t: t.clone())
+    c = G.desc_of(x).c
+    for stale in (False, True):            # stale ranges make the gate and both clamp sides bite
+        src = to_numpy(ref if stale else x)
+        mn, mx = oracle.range_reduce(src)
+        s_np, z_np = oracle.prescale(mn, mx, 4)
+        want = oracle_path(to_numpy(x), 4, to_numpy(dy), scale=s_np, zero_point=z_np)
+        s, z = torch.tensor(s_np, device=DEV), torch.tensor(z_np, device=DEV)
+        x2, dy2 = mk(x), mk(dy)
+        if misaligned:
+            assert x2.data_ptr() % 16 != 0
+        G.granq_fakequant_bwd(x2, dy2, s, z, 4, dy2)
+        G.granq_fakequant_fwd(x2, s, z, 4, x2)
+        torch.cuda.synchronize()
+        got = {"scale": s_np, "zero_point": z_np, "xhat": to_numpy(x2), "dx": to_numpy(dy2)}
+        assert_parity(got, want, "in place %s stale=%s" % (shape, stale))
+        # gate-bit pair, both in place
+        x3, dy3 = mk(x), mk(dy)
+        mask = torch.zeros(G.granq_mask_bytes(G.desc_of(x)), dtype=torch.uint8, device=DEV)
+        G.granq_fakequant_fwd_mask(x3, s, z, 4, x3, mask)
+        G.granq_fakequant_bwd_mask(dy3, mask, dy3)
+        torch.cuda.synchronize()
+        got = {"scale": s_np, "zero_point": z_np, "xhat": to_numpy(x3), "dx": to_numpy(dy3)}
+        assert_parity(got, want, "in place, gate bits %s stale=%s" % (shape, stale))
+    # ranges, parameters and forward in one call, x_hat == x
+    want = oracle_path(to_numpy(x), 4)
+    x4 = mk(x)
+    vec = [torch.full((c,), float("nan"), device=DEV) for _ in range(4)]
+    ws = torch.empty(max(16, G.granq_workspace_bytes(G.desc_of(x))), dtype=torch.uint8, device=DEV)
+    G.granq_calibrate_fakequant_fwd(x4, 4, vec[0], vec[1], vec[2], vec[3], x4, None, ws)
+    torch.cuda.synchronize()
+    got = {"min": vec[0].cpu().numpy(), "max": vec[1].cpu().numpy(), "scale": vec[2].cpu().numpy(),
+           "zero_point": vec[3].cpu().numpy(), "xhat": to_numpy(x4)}
+    assert_parity(got, want, "one-call forward in place %s" % (shape,))
+
+
 def test_misaligned_pointers_take_the_elementwise_path():
     """A tensor that starts 4 bytes into an allocation: same results, no fault."""
     for dtype in (torch.float32, torch.bfloat16, torch.float16):
