@@ -41,7 +41,8 @@
  *    GRANQ_ERR_UNSUPPORTED and GRANQ_ERR_WORKSPACE nothing has been enqueued.
  *    GRANQ_ERR_HIP (the runtime refused a launch) may follow kernels of the same
  *    call that were already enqueued.  Calls are re-entrant; the library has no
- *    global mutable state.  Calls may be captured into a HIP graph.
+ *    global mutable state (the one exception, granq_range_reduce_noalloc, says so).
+ *    Calls may be captured into a HIP graph.
  */
 #ifndef GRANQ_H
 #define GRANQ_H
@@ -118,6 +119,26 @@ granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc,
                                   float *ch_min, float *ch_max,
                                   void *workspace, size_t workspace_bytes,
                                   void *stream);
+
+/*
+ * granq_range_reduce for callers that cannot allocate and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * partials live in a scratch array of GRANQ_STATIC_SCRATCH_BYTES (4 MiB) that the library
+ * owns statically on every GPU it is loaded on (held until the process ends); the call makes
+ * no hipMalloc / hipFree and calls no allocating routine.  Results are bit-identical to
+ * granq_range_reduce.
+ *  - A descriptor whose granq_workspace_bytes() exceeds the array returns
+ *    GRANQ_ERR_WORKSPACE and launches nothing (every activation shape of ResNet-18/-20/-50
+ *    and MobileNetV2 at batch 256 needs less than 1 MiB).
+ *  - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *    (two streams, two threads) race and give garbage ranges; serialise them.  Nothing in
+ *    the array has to be cleared between calls.
+ *  - The first call on a device looks up the array's device address (once per device; the
+ *    device current at the call must be the stream's); make it before a graph capture.
+ */
+#define GRANQ_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+granq_status_t granq_range_reduce_noalloc(const void *x, const granq_desc_t *desc,
+                                          float *ch_min, float *ch_max, void *stream);
 
 /*
  * Vectorized pre-scaling parameters (Eq. 2 per channel = Eq. 5; Alg. 1's two

@@ -6,7 +6,7 @@ The product is ``libgranq.so`` (hand-written HIP for gfx950, built from
 from .binding import (GRANQ_BF16, GRANQ_F16, GRANQ_ERR_HIP, GRANQ_ERR_INVALID_ARG, GRANQ_ERR_UNSUPPORTED,
                       GRANQ_ERR_WORKSPACE, GRANQ_F32, GRANQ_OK, GranqError, desc_of, granq_desc_t,
                       granq_fakequant_bwd, granq_fakequant_fwd, granq_plan_describe, granq_prescale,
-                      granq_range_reduce, granq_workspace_bytes, library_path, load, make_desc,
+                      granq_range_reduce, granq_range_reduce_noalloc, granq_workspace_bytes, library_path, load, make_desc,
                       status_string, version)
 from .binding import granq_fakequant_bwd_mask, granq_fakequant_fwd_mask, granq_mask_bytes
 from .binding import (granq_rowwise_fakequant_bwd_multi, granq_rowwise_fakequant_multi, rowwise_bwd_items,
@@ -20,7 +20,7 @@ from .quantizer import ActivationQuantizer
 __all__ = [
     "GRANQ_OK", "GRANQ_ERR_INVALID_ARG", "GRANQ_ERR_UNSUPPORTED", "GRANQ_ERR_WORKSPACE",
     "GRANQ_ERR_HIP", "GRANQ_F32", "GRANQ_BF16", "GRANQ_F16", "GranqError", "granq_desc_t", "make_desc", "desc_of",
-    "granq_workspace_bytes", "granq_plan_describe", "granq_range_reduce", "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_conv1x1_int8_as", "granq_fakequant_fwd",
+    "granq_workspace_bytes", "granq_plan_describe", "granq_range_reduce", "granq_range_reduce_noalloc", "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_conv1x1_int8_as", "granq_fakequant_fwd",
     "granq_fakequant_bwd", "load", "library_path", "status_string", "version",
     "granq_fold_weights", "granq_conv1x1_int8",
     "granq_distortion", "granq_distortion_workspace_bytes",

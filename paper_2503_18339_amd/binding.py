@@ -27,7 +27,7 @@ GRANQ_BF16 = 1
 GRANQ_F16 = 2
 
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
-           "granq_range_reduce",
+           "granq_range_reduce", "granq_range_reduce_noalloc",
            "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
            "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
@@ -83,6 +83,7 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_plan_describe.argtypes = [dp, ctypes.POINTER(ctypes.c_int64 * 24)]
     lib.granq_range_reduce.argtypes = [_vp, dp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.granq_range_reduce_noalloc.argtypes = [_vp, dp, _vp, _vp, _vp]
     lib.granq_prescale.argtypes = [_vp, _vp, ctypes.c_int64, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_calibrate.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_calibrate_fakequant_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -212,6 +213,15 @@ def granq_range_reduce(x: torch.Tensor, ch_min: torch.Tensor, ch_max: torch.Tens
                                      _vec(ch_max, d.c, "ch_max"), _dev(workspace, "workspace"),
                                      workspace.numel() * workspace.element_size(), _stream(stream)),
            "granq_range_reduce")
+
+
+def granq_range_reduce_noalloc(x: torch.Tensor, ch_min: torch.Tensor, ch_max: torch.Tensor, stream=None,
+                               desc: Optional[granq_desc_t] = None) -> None:
+    """granq_range_reduce on the library's own static scratch (no workspace, no allocation)."""
+    d = _desc_for(x, desc)
+    _check(load().granq_range_reduce_noalloc(_dev(x, "x"), ctypes.byref(d), _vec(ch_min, d.c, "ch_min"),
+                                             _vec(ch_max, d.c, "ch_max"), _stream(stream)),
+           "granq_range_reduce_noalloc")
 
 
 def granq_prescale(ch_min: torch.Tensor, ch_max: torch.Tensor, bits: int, scale: torch.Tensor,

@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 #include <float.h>
 #include <type_traits>
+#include <atomic>
 #include <stdint.h>
 
 #include "granq.h"
@@ -1092,6 +1093,41 @@ granq_status_t granq_range_reduce(const void *x, const granq_desc_t *desc, float
                                   float *ch_max, void *workspace, size_t workspace_bytes,
                                   void *stream) {
     return range_impl(x, desc, ch_min, ch_max, 0.0f, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+// Library-owned scratch for callers that cannot bring a workspace (see granq.h).  One copy of
+// the array lives on every GPU the library is loaded on; in host code its name is only a
+// handle for hipGetSymbolAddress, never an address a kernel could use.
+static __device__ __align__(256) unsigned char scratch[GRANQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> scratch_of_device[kMaxDevices];
+
+// Device address of the current device's copy of `scratch`, resolved once per device.
+static granq_status_t static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GRANQ_ERR_HIP;
+    void *p = scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GRANQ_ERR_HIP;
+        scratch_of_device[dev].store(p, std::memory_order_release);   // same value from every thread
+    }
+    *out = p;
+    return GRANQ_OK;
+}
+
+granq_status_t granq_range_reduce_noalloc(const void *x, const granq_desc_t *desc, float *ch_min,
+                                          float *ch_max, void *stream) {
+    size_t need = 0;
+    granq_status_t st = granq_workspace_bytes(desc, &need);
+    if (st != GRANQ_OK) return st;
+    if (need > GRANQ_STATIC_SCRATCH_BYTES) return GRANQ_ERR_WORKSPACE;
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != GRANQ_OK) return st;
+    // every partial the second pass reads is written by the first pass of the same call:
+    // nothing in the scratch has to start at zero
+    return range_impl(x, desc, ch_min, ch_max, 0.0f, nullptr, nullptr, ws, GRANQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits, float *ch_min,
