@@ -3,11 +3,15 @@
 
 One step = one pass of the whole quantizer path over the batch-256 ResNet-18
 ImageNet activation set (five tensors, synthetic stand-ins, resident in HBM):
-for every tensor range_reduce -> prescale -> fakequant_fwd in network order,
-then fakequant_bwd for every tensor in reverse order, all on one stream with no
-host synchronisation in between.  Throughput is algorithmic bytes per second:
-24 bytes per float32 element and step (x read by the reduction, x read and
-x_hat written by the forward, x and dy read and dx written by the backward).
+for every tensor, in network order, the per-channel ranges (Eq. 4), scale and
+zero-point (Eq. 5) and the quantize-clamp-dequantize forward (Eq. 1, 6) -- one
+granq_calibrate_fakequant_fwd call -- then granq_fakequant_bwd for every tensor
+in reverse order, all on one stream with no host synchronisation in between.
+Throughput is algorithmic bytes per second: 24 bytes per float32 element and
+step (x read by the reduction, x read and x_hat written by the forward, x and
+dy read and dx written by the backward).  The same step issued as the four
+separate calls (range_reduce, prescale, forward, backward) is timed beside it,
+and so are the other four workloads (extra.workloads).
 
 Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
 """
@@ -59,13 +63,21 @@ def build_layers(wl, dtype, bits, device):
     return [Layer(a, wl.batch, wl.sigma, dtype, bits, i, device) for i, a in enumerate(wl.tensors())]
 
 
-def run_step(layers, stream, ev=None, one_call=False):
-    """One pass of the hot path (four calls per tensor; `one_call` swaps the first two for
-    granq_calibrate, same results with one launch fewer).  `ev`, if given, collects one (start, end, bytes,
-    launches) record per step around the consecutive backward launches of the
+FORMS = ("one_call", "calibrate", "four_calls")
+
+
+def run_step(layers, stream, ev=None, form="one_call"):
+    """One pass of the hot path.  form: "one_call" = granq_calibrate_fakequant_fwd per tensor
+    (ranges, parameters and forward; one to three launches), "calibrate" = granq_calibrate +
+    granq_fakequant_fwd, "four_calls" = range_reduce, prescale, forward; the backward follows for
+    every tensor in reverse order.  Same results in every form.  `ev`, if given, collects one
+    (start, end, bytes, launches) record per step around the consecutive backward launches of the
     dominant kernel (the layers are ordered so that those launches are adjacent)."""
     for L in layers:
-        if one_call:
+        if form == "one_call":
+            L.q.forward(L.x, L.x_hat, None, stream)
+            continue
+        if form == "calibrate":
             L.q.calibrate(L.x, stream)
         else:
             G.granq_range_reduce(L.x, L.q.ch_min, L.q.ch_max, L.q.workspace, stream, L.q.desc)
@@ -99,31 +111,31 @@ def run_step(layers, stream, ev=None, one_call=False):
             ev.append((a, b, sum(M.bytes("bwd") for M in doms), len(doms)))
 
 
-def time_steps(layers, steps, warmup, with_events, one_call=False):
+def time_steps(layers, steps, warmup, with_events, form="one_call"):
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
-        run_step(layers, stream, None, one_call)
+        run_step(layers, stream, None, form)
     ev = [] if with_events else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        run_step(layers, stream, ev, one_call)
+        run_step(layers, stream, ev, form)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     return dt, ev
 
 
-def time_graph_steps(layers, steps, warmup, one_call=False):
+def time_graph_steps(layers, steps, warmup, form="one_call"):
     """The same step captured once into a HIP graph and replayed (no per-kernel events)."""
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        run_step(layers, side, None, one_call)
+        run_step(layers, side, None, form)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        run_step(layers, torch.cuda.current_stream(), None, one_call)
+        run_step(layers, torch.cuda.current_stream(), None, form)
     for _ in range(warmup):
         graph.replay()
     torch.cuda.synchronize()
@@ -248,22 +260,6 @@ def comparison_points(wl, bits, device):
                 "channel loop four per channel; launch-latency-bound at this size",
     }
     del tens, outs
-
-    # (2b) the sweep of the paper's Fig. 4 (latency against batch size; the paper prints no values)
-    sweep = {}
-    for b in (16, 32, 64, 128, 200):
-        tens = [workloads.make_activation(a.shape(b), a.law, r20.sigma, i, device) for i, a in enumerate(acts)]
-        outs = [torch.empty_like(t) for t in tens]
-        qcb = [G.ActivationQuantizer(t.shape, torch.float32, 3, device, view="channel") for t in tens]
-        qlb = [G.ActivationQuantizer(t.shape, torch.float32, 3, device, view="layer") for t in tens]
-
-        def run(qs):
-            for q, t, o in zip(qs, tens, outs):
-                q.forward(t, o, stream=stream)
-        sweep["batch_%d" % b] = {"granq_vectorized_ms": round(_timeit(lambda: run(qcb)) / 1e3, 4),
-                                 "layerwise_ms": round(_timeit(lambda: run(qlb)) / 1e3, 4)}
-        del tens, outs
-    out["fig4_setting_resnet20_cifar_3bit_latency_vs_batch"] = sweep
 
     # (3) accumulation forms on 256x64x56x56: scale inside the loop from 8-bit codes (Eq. 3)
     # vs accumulation of pre-scaled activations (Eq. 6)
@@ -444,31 +440,44 @@ def integer_accumulation(wl, bits, device):
     return rows
 
 
-def cpu_baseline(wl, bits, sample_batch, min_seconds=10.0, max_passes=8):
-    """The CPU oracle, as it stands, single thread, on the same tensors at batch
-    `sample_batch` (float32): whole passes (range_reduce+prescale+fwd+bwd) are
-    repeated until `min_seconds` of oracle time have accumulated.  Returns GB/s on
-    the same algorithmic bytes, the oracle seconds and the number of passes."""
+def cpu_baseline(layers, bits, sample_batch, min_seconds=10.0, max_passes=8):
+    """The CPU oracle, as it stands, single thread, on the tensors the GPU was timed on (their
+    first `sample_batch` samples, copied to the host): whole passes (range_reduce + prescale +
+    fwd + bwd) are repeated until `min_seconds` of oracle time have accumulated.  Returns GB/s
+    on the same algorithmic bytes, the oracle seconds, the number of passes, and -- when the
+    sample is the whole batch -- how the buffers the GPU step left behind compare with the
+    oracle's results (every element of every tensor)."""
+    import numpy as np
     import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import to_numpy
     total_bytes = 0
     total_s = 0.0
     passes = 0
-    data = []
-    for i, a in enumerate(wl.tensors()):
-        shape = a.shape(sample_batch)
-        data.append((workloads.make_activation(shape, a.law, wl.sigma, i, "cpu").numpy(),
-                     workloads.make_grad(shape, i, "cpu").numpy()))
+    checked = None
+    whole = all(sample_batch >= L.shape[0] for L in layers) and layers[0].esize == 4
+    data = [(to_numpy(L.x[:sample_batch]), to_numpy(L.dy[:sample_batch])) for L in layers]
     while passes < max_passes and (passes == 0 or total_s < min_seconds):
-        for x, dy in data:
+        if passes == 0 and whole:
+            checked = {"tensors": 0, "elements": 0, "mismatching_elements": 0}
+        for L, (x, dy) in zip(layers, data):
             t0 = time.perf_counter()
             mn, mx = oracle.range_reduce(x)
             s, z = oracle.prescale(mn, mx, bits)
-            oracle.fakequant_fwd(x, s, z, bits)
-            oracle.fakequant_bwd(x, dy, s, z, bits)
+            xh, _ = oracle.fakequant_fwd(x, s, z, bits)
+            dx = oracle.fakequant_bwd(x, dy, s, z, bits)
             total_s += time.perf_counter() - t0
-            total_bytes += x.size * 4 * 6
+            total_bytes += x.size * x.itemsize * 6
+            if passes == 0 and whole:
+                bad = int(np.count_nonzero(to_numpy(L.x_hat) != xh)) + int(np.count_nonzero(to_numpy(L.dx) != dx))
+                for got, want in ((L.q.ch_min, mn), (L.q.ch_max, mx), (L.q.scale, s), (L.q.zero_point, z)):
+                    bad += int(np.count_nonzero(got.cpu().numpy() != want))
+                checked["tensors"] += 1
+                checked["elements"] += 2 * x.size + 4 * mn.size
+                checked["mismatching_elements"] += bad
+            del xh, dx
         passes += 1
-    return total_bytes / total_s / 1e9, total_s, passes
+    return total_bytes / total_s / 1e9, total_s, passes, checked
 
 
 def cpu_baseline_threads(wl, bits, sample_batch, threads):
@@ -499,13 +508,52 @@ def cpu_baseline_threads(wl, bits, sample_batch, threads):
     return total_bytes / total_s / 1e9, total_s
 
 
+def launches_per_tensor(layers):
+    """Kernel launches of one step per tensor, from the library's own plan: the one-call forward
+    (1 to 3) plus the backward."""
+    return [int(G.granq_plan_describe(L.q.desc)["one_call_launches"]) + 1 for L in layers]
+
+
+def other_workloads(device, steps):
+    """The other four workloads, each at its own bit-width(s), float32: the same step (one-call
+    forward per tensor, then the backward in reverse order; one stream, no host synchronisation)
+    and, beside it, the step issued as four separate calls."""
+    out = {}
+    for key, bit_list in (("config1", (3,)), ("config2", (3, 4)), ("config4", (4,)), ("config5", (3,))):
+        wl = workloads.WORKLOADS[key]()
+        for bits in bit_list:
+            layers = build_layers(wl, torch.float32, bits, device)
+            elems = sum(L.numel for L in layers)
+            step_bytes = elems * 4 * 6
+            k = max(5, min(steps, int(2e5 / max(1.0, step_bytes / 6.4e6))))   # about 0.2 s of GPU time
+            dt, _ = time_steps(layers, k, 3, with_events=False, form="one_call")
+            dt4, _ = time_steps(layers, k, 3, with_events=False, form="four_calls")
+            lp = launches_per_tensor(layers)
+            name = key if len(bit_list) == 1 else "%s_b%d" % (key, bits)
+            out[name] = {
+                "workload": wl.name, "bits": bits, "tensors": len(layers), "elements_per_step": elems,
+                "value": round(step_bytes / (dt / k) / 1e9, 1), "unit": "GB/s",
+                "frac_of_hbm_peak": round(step_bytes / (dt / k) / 1e9 / HBM_PEAK_GBS, 4),
+                "ms_per_step": round(dt * 1e3 / k, 4), "steps": k,
+                "launches_per_step": sum(lp), "launches_per_tensor": round(sum(lp) / len(lp), 2),
+                "four_separate_calls": {"value": round(step_bytes / (dt4 / k) / 1e9, 1),
+                                        "ms_per_step": round(dt4 * 1e3 / k, 4), "launches_per_tensor": "4 or 5"},
+            }
+            del layers
+            torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--dtype", choices=["f32", "bf16", "f16"], default="f32")
-    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--bits", type=int, default=None, help="default: the workload's first bit-width")
+    ap.add_argument("--form", choices=list(FORMS), default="one_call",
+                    help="how the step is issued: granq_calibrate_fakequant_fwd per tensor (default), "
+                         "granq_calibrate + forward, or the four separate calls; same results")
     ap.add_argument("--cpu-sample-batch", type=int, default=256,
                     help="batch size of the sample the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--workload", choices=["config1", "config2", "config3", "config4", "config5"], default="config3",
@@ -528,6 +576,8 @@ def main():
 
     device = "cuda"
     wl = workloads.WORKLOADS[args.workload]()
+    if args.bits is None:
+        args.bits = 4 if args.workload == "config3" else wl.bits[0]
     variants_only = args.workload != "config3" and not args.no_extras
     if args.workload != "config3":
         args.no_extras = True
@@ -539,12 +589,13 @@ def main():
     elems = sum(L.numel for L in layers)
     step_bytes = elems * esize * 6
 
-    dt, ev = time_steps(layers, args.steps, args.warmup, with_events=True)
+    dt, ev = time_steps(layers, args.steps, args.warmup, with_events=True, form=args.form)
     ms_per_step = dt * 1e3 / args.steps
     value = step_bytes / (dt / args.steps) / 1e9
 
     from paper_2503_18339_amd import profiling
-    rec = profiling.load_record() if (args.dtype == "f32") else None
+    # counters were taken on one workload and dtype: they describe no other launch
+    rec = profiling.load_record(workload=args.workload, dtype=args.dtype)
     traffic = round(rec["traffic_bytes_per_launch"]) if rec else None
     k_bytes = sum(e[2] for e in ev)
     k_launches = sum(e[3] for e in ev)
@@ -560,20 +611,44 @@ def main():
                 "in the backward sweep; average = span / launches",
     }
 
+    lp = launches_per_tensor(layers)
+    calls = {"one_call": "granq_calibrate_fakequant_fwd per tensor", "calibrate": "granq_calibrate + granq_fakequant_fwd per tensor",
+             "four_calls": "range_reduce + prescale + fwd per tensor"}[args.form]
     out = {
         "metric": "fake-quant fwd+bwd GB/s and % of HBM peak, ResNet-18 ImageNet activations"
                   if args.workload == "config3" else "fake-quant fwd+bwd GB/s and % of HBM peak, " + wl.name,
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %s, %d-bit, range_reduce+prescale+fwd per tensor then bwd in reverse"
+        "config": {"workload": "%s: %s, %d-bit, %s (ranges, scale/zero-point, forward) then bwd in reverse"
                    % (wl.name, ", ".join("%d@%dx%d" % (a.c, a.hw, a.hw) for a in wl.acts[:8])
-                      + (", ... (%d tensors)" % len(wl.tensors()) if len(wl.acts) > 8 else ""), args.bits),
-                   "batch": wl.batch, "elements_per_step": elems, "bytes_per_step": step_bytes},
+                      + (", ... (%d tensors)" % len(wl.tensors()) if len(wl.acts) > 8 else ""), args.bits, calls),
+                   "batch": wl.batch, "elements_per_step": elems, "bytes_per_step": step_bytes,
+                   "launches_per_step": sum(lp) if args.form == "one_call" else None},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "elements_per_s": round(elems / (dt / args.steps), 0),
         "roofline": roofline,
     }
+
+    if args.cpu_sample_batch > 0:
+        # before anything else touches the buffers: the oracle is timed on the very tensors the GPU
+        # was timed on, and what the timed steps left in x_hat, dx and the four vectors is compared
+        gbs, secs, passes, checked = cpu_baseline(layers, args.bits, args.cpu_sample_batch)
+        out["cpu_baseline"] = {
+            "value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "the same five tensors at batch %d of %d, %s, %d-bit, %d whole pass(es) "
+                      "(range_reduce+prescale+fwd+bwd), %.1f s of oracle time"
+                      % (min(args.cpu_sample_batch, wl.batch), wl.batch, args.dtype, args.bits, passes, secs),
+        }
+        if checked is not None:
+            out["timed_buffers_vs_oracle"] = checked
+        threads = min(16, os.cpu_count() or 1)
+        if threads > 1:
+            gbs_t, secs_t = cpu_baseline_threads(wl, args.bits, args.cpu_sample_batch, threads)
+            out["cpu_baseline_all_cores"] = {
+                "value": round(gbs_t, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+                "sample": "one whole pass at batch %d, the batch split over %d threads, %.1f s"
+                          % (args.cpu_sample_batch, threads, secs_t)}
 
     if args.pmc_calibration:
         big = max(layers, key=lambda L: L.numel)
@@ -583,18 +658,19 @@ def main():
         out["pmc_calibration"] = {"kernel": "torch copy_ (elementwise copy)", "launches": 3,
                                   "bytes_read": big.numel * esize, "bytes_written": big.numel * esize}
 
+    def step_forms(ls, sbytes, steps):
+        res = {}
+        for form in FORMS:
+            d, _ = time_steps(ls, steps, 2, with_events=False, form=form)
+            res[form] = {"GBs": round(sbytes / (d / steps) / 1e9, 1), "ms_per_step": round(d * 1e3 / steps, 4)}
+        d = time_graph_steps(ls, steps, 2, form="one_call")
+        res["one_call_hip_graph_replay"] = {"GBs": round(sbytes / (d / steps) / 1e9, 1),
+                                            "ms_per_step": round(d * 1e3 / steps, 4)}
+        return res
+
     if variants_only:
-        # the other workloads: only the step variants (no events, one-call calibration, graph replay)
-        variants = {}
-        dt2, _ = time_steps(layers, args.steps, 2, with_events=False)
-        variants["value_without_kernel_events_GBs"] = round(step_bytes / (dt2 / args.steps) / 1e9, 1)
-        dt4, _ = time_steps(layers, args.steps, 2, with_events=False, one_call=True)
-        variants["value_one_call_calibration_GBs"] = round(step_bytes / (dt4 / args.steps) / 1e9, 1)
-        dt3 = time_graph_steps(layers, args.steps, 2)
-        variants["value_hip_graph_replay_GBs"] = round(step_bytes / (dt3 / args.steps) / 1e9, 1)
-        dt5 = time_graph_steps(layers, args.steps, 2, one_call=True)
-        variants["value_hip_graph_replay_one_call_GBs"] = round(step_bytes / (dt5 / args.steps) / 1e9, 1)
-        out["extra"] = variants
+        # the other workloads run alone: the step in its three forms and as a graph replay
+        out["extra"] = {"step_forms_without_kernel_events": step_forms(layers, step_bytes, args.steps)}
 
     if not args.no_extras:
         extra = {"per_kernel": kernel_breakdown(layers)}
@@ -608,13 +684,8 @@ def main():
             for L in layers}
         fb_us = sum(r["fwd_us"] + r["bwd_us"] for r in extra["per_kernel"])
         extra["fwd_bwd_kernels_only_GBs"] = round(elems * esize * 5 / fb_us / 1e3, 1)
-        # same step without the per-launch events: what the events cost
-        dt2, _ = time_steps(layers, args.steps, 2, with_events=False)
-        extra["value_without_kernel_events_GBs"] = round(step_bytes / (dt2 / args.steps) / 1e9, 1)
-        dt4, _ = time_steps(layers, args.steps, 2, with_events=False, one_call=True)
-        extra["value_one_call_calibration_GBs"] = round(step_bytes / (dt4 / args.steps) / 1e9, 1)
-        dt3 = time_graph_steps(layers, args.steps, 2)
-        extra["value_hip_graph_replay_GBs"] = round(step_bytes / (dt3 / args.steps) / 1e9, 1)
+        # the same step without the per-launch events, in its three forms, and as a graph replay
+        extra["step_forms_without_kernel_events"] = step_forms(layers, step_bytes, args.steps)
         del layers
         torch.cuda.empty_cache()
         others = {}
@@ -622,7 +693,7 @@ def main():
             if dname == args.dtype and bits == args.bits:
                 continue
             ls = build_layers(wl, workloads.torch_dtype(dname), bits, device)
-            d, _ = time_steps(ls, args.steps, args.warmup, with_events=False)
+            d, _ = time_steps(ls, args.steps, args.warmup, with_events=False, form=args.form)
             b = elems * ls[0].esize * 6
             others["%s_b%d" % (dname, bits)] = {"GBs": round(b / (d / args.steps) / 1e9, 1),
                                                 "ms_per_step": round(d * 1e3 / args.steps, 4),
@@ -630,6 +701,7 @@ def main():
             del ls
             torch.cuda.empty_cache()
         extra["other_dtypes_bits"] = others
+        extra["workloads"] = other_workloads(device, args.steps)
         extra["comparison_points"] = comparison_points(wl, args.bits, device)
         extra["integer_accumulation_1x1_batch256"] = integer_accumulation(wl, args.bits, device)
         extra["distortion_3bit"] = distortion_table(wl, device)
@@ -639,23 +711,6 @@ def main():
         extra["gate_bit_variant"]["speedup_vs_x_based_step"] = round(
             ms_per_step / extra["gate_bit_variant"]["ms_per_step"], 3)
         out["extra"] = extra
-
-    if args.cpu_sample_batch > 0:
-        gbs, secs, passes = cpu_baseline(wl, args.bits, args.cpu_sample_batch)
-        out["cpu_baseline"] = {
-            "value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "the same five tensors at batch %d of 256, float32, %d-bit, %d whole pass(es) "
-                      "(range_reduce+prescale+fwd+bwd), %.1f s of oracle time"
-                      % (args.cpu_sample_batch, args.bits, passes, secs),
-        }
-
-        threads = min(16, os.cpu_count() or 1)
-        if threads > 1:
-            gbs_t, secs_t = cpu_baseline_threads(wl, args.bits, args.cpu_sample_batch, threads)
-            out["cpu_baseline_all_cores"] = {
-                "value": round(gbs_t, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
-                "sample": "one whole pass at batch %d, the batch split over %d threads, %.1f s"
-                          % (args.cpu_sample_batch, threads, secs_t)}
 
     print(json.dumps(out))
 

@@ -100,7 +100,10 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
  *        e.g. a channels-last tensor seen as {N*H*W, C, 1, 1}, are glued so that a block's
  *        lanes all have a column; [1], [2] are the glued counts, the channel of a column
  *        follows from the column modulo the true row length)
- *   [17..23] zero, reserved
+ *   [17] launches granq_calibrate_fakequant_fwd makes for this descriptor when every pointer is
+ *        16-byte aligned: 1 (a block per channel), 2 (first pass; forward that finishes the
+ *        reduction) or 3  [18] launches of granq_range_reduce / granq_calibrate: 1 or 2
+ *   [19..23] zero, reserved
  * of the matrix view (rows x row length) the kernels walk; [1]..[12] and [16] describe
  * the reduction.  For tests and tuning.
  */

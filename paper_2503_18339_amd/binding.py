@@ -202,7 +202,7 @@ def granq_plan_describe(desc: granq_desc_t) -> dict:
     _check(load().granq_plan_describe(ctypes.byref(desc), ctypes.byref(out)), "granq_plan_describe")
     keys = ("vector_path", "rows", "row_len", "hw", "span", "col_tiles", "row_groups",
             "rows_per_group", "kmax", "uniform", "div_m", "div_s1", "div_s2", "fwd_rows", "bwd_rows",
-            "elem_span", "fold")
+            "elem_span", "fold", "one_call_launches", "range_launches")
     return dict(zip(keys, [int(v) for v in out]))
 
 

@@ -15,6 +15,7 @@
 #include "granq_launch.h"
 #include "granq_plan.h"
 #include "granq_block.h"
+#include "granq_internal.h"
 
 namespace granq {
 
@@ -24,6 +25,10 @@ namespace granq {
 constexpr int kFusedBlock = 1024;
 constexpr int kFusedVecs = 8;
 constexpr int kFusedScalars = 32;
+// Largest tensor (bytes) handled by one block per channel when the two-launch form is also possible.
+#ifndef GRANQ_ONE_BLOCK_MAX_BYTES
+#define GRANQ_ONE_BLOCK_MAX_BYTES ((int64_t)8 << 20)
+#endif
 
 // Block-wide min and max over kFusedBlock threads, result in every thread.
 __device__ inline void fused_block_minmax(float &mn, float &mx, float (*part)[kFusedBlock / kWave]) {
@@ -139,6 +144,42 @@ static void launch_channel_block(bool vector, const void *x, void *x_hat, uint8_
                            zero_point, qmax, units, c, slab_div);
 }
 
+// How granq_calibrate_fakequant_fwd handles a tensor: one block per channel (one launch) when
+// the channel fits a block's registers and the tensor is small, else the two-launch form where
+// it applies, else granq_calibrate + granq_fakequant_fwd (three launches).
+struct OneCallChoice {
+    int launches;        // 1, 2 or 3
+    bool vector;         // one launch: 16-byte units
+    int64_t units;       // one launch: units per channel
+};
+
+static OneCallChoice one_call_choice(const granq_desc_t *desc, const void *x, const void *x_hat,
+                                     const uint8_t *codes_or_null) {
+    OneCallChoice ch{3, false, 0};
+    const int64_t hw = desc->h > 0 && desc->w > 0 ? desc->h * desc->w : 0;
+    const bool known = desc->dtype == GRANQ_F32 || desc->dtype == GRANQ_BF16 || desc->dtype == GRANQ_F16;
+    const int esize = desc->dtype == GRANQ_F32 ? 4 : 2;
+    const int vec = 16 / esize;
+    const bool sane = known && desc->n > 0 && desc->c > 0 && hw > 0 && desc->c < ((int64_t)1 << 31) &&
+                      hw <= ((int64_t)1 << 20) && desc->n <= ((int64_t)1 << 20);
+    if (!sane) return ch;
+    ch.vector = hw % vec == 0 && ((uintptr_t)x & 15u) == 0 && ((uintptr_t)x_hat & 15u) == 0 &&
+                ((uintptr_t)codes_or_null % (uintptr_t)vec) == 0;
+    ch.units = ch.vector ? desc->n * (hw / vec) : desc->n * hw;
+    const bool fits = ch.units <= (int64_t)kFusedBlock * (ch.vector ? kFusedVecs : kFusedScalars);
+    const bool two = two_launches_apply(x, desc, x_hat, codes_or_null);
+    // C blocks are a good use of the chip only while the tensor is small; beyond that the
+    // two-launch form (all compute units on the reduction, then on the forward) wins
+    const int64_t bytes = desc->n * desc->c * hw * esize;
+    if (fits && (bytes <= GRANQ_ONE_BLOCK_MAX_BYTES || !two)) ch.launches = 1;
+    else ch.launches = two ? 2 : 3;
+    return ch;
+}
+
+int one_call_forward_launches(const granq_desc_t *desc) {
+    return one_call_choice(desc, (const void *)256, (const void *)256, nullptr).launches;
+}
+
 }  // namespace granq
 
 using namespace granq;
@@ -158,20 +199,19 @@ granq_status_t granq_calibrate_fakequant_fwd(const void *x, const granq_desc_t *
     if (!x_hat && !codes_or_null) return GRANQ_ERR_INVALID_ARG;
     if (known && ((uintptr_t)x_hat & ((uintptr_t)esize - 1))) return GRANQ_ERR_UNSUPPORTED;
 
-    // one block per channel when the channel fits its registers
-    const bool sane = known && desc->n > 0 && desc->c > 0 && hw > 0 && desc->c < ((int64_t)1 << 31) &&
-                      hw <= ((int64_t)1 << 20) && desc->n <= ((int64_t)1 << 20);
-    const bool vector = sane && hw % vec == 0 && ((uintptr_t)x & 15u) == 0 && ((uintptr_t)x_hat & 15u) == 0 &&
-                        ((uintptr_t)codes_or_null % (uintptr_t)vec) == 0;
-    const int64_t units = !sane ? 0 : (vector ? desc->n * (hw / vec) : desc->n * hw);
-    const bool small = sane && units <= (int64_t)kFusedBlock * (vector ? kFusedVecs : kFusedScalars);
-    if (!small) {
+    const OneCallChoice choice = one_call_choice(desc, x, x_hat, codes_or_null);
+    if (choice.launches == 2)
+        return calibrate_fwd_two_launches(x, desc, bits, ch_min, ch_max, scale, zero_point, x_hat,
+                                          codes_or_null, workspace, workspace_bytes, stream);
+    if (choice.launches == 3) {
         // every check of the two calls applies
         granq_status_t st = granq_calibrate(x, desc, bits, ch_min, ch_max, scale, zero_point, workspace,
                                             workspace_bytes, stream);
         if (st != GRANQ_OK) return st;
         return granq_fakequant_fwd(x, desc, scale, zero_point, bits, x_hat, codes_or_null, stream);
     }
+    const bool vector = choice.vector;
+    const int64_t units = choice.units;
     // the same argument checks as the two calls make
     if (!x || !ch_min || !ch_max || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
     if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;

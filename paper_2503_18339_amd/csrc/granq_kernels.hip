@@ -16,6 +16,7 @@
 // one wavefront per (n,c) slab, scale and zero-point wave-uniform).
 #include <hip/hip_runtime.h>
 #include <float.h>
+#include <stdlib.h>
 #include <type_traits>
 #include <atomic>
 #include <stdint.h>
@@ -24,6 +25,7 @@
 #include "granq_device.h"
 #include "granq_launch.h"
 #include "granq_plan.h"
+#include "granq_internal.h"
 #include "granq_quotient.h"
 
 namespace granq {
@@ -38,7 +40,7 @@ namespace granq {
 #define GRANQ_E_V_BF16 1
 #endif
 #ifndef GRANQ_R_V_F32
-#define GRANQ_R_V_F32 4
+#define GRANQ_R_V_F32 1
 #endif
 #ifndef GRANQ_R_V_BF16
 #define GRANQ_R_V_BF16 1
@@ -124,6 +126,62 @@ __device__ inline float code_of(float x, const ChanRegs &c) {
     return __builtin_rintf(v);
 }
 
+// Eq. 5 for one channel: step size and zero-point from the channel's range.
+__device__ __forceinline__ void prescale_one(float mn, float mx, float qmax, float &s, float &z) {
+    const float range = mx - mn;
+    s = range / qmax;
+    if (!(s >= FLT_MIN)) s = 1.0f;                     // zero, subnormal or NaN scale
+    z = __builtin_rintf((-mn) / s) + 0.0f;             // "+ 0" turns -0 into +0
+}
+
+// The first pass of the reduction leaves one partial min / max per (row group p, column tile
+// j, channel slot k) at  ws[(p * J + j) * kmax + k],  k = channel - first channel of tile j.
+// Partials of channel c: of all row groups and of the column tiles that overlap the channel.
+// Work item i of them goes to the caller with  i = start, start + stride, ...
+__device__ inline void gather_channel(const float *__restrict__ ws_min, const float *__restrict__ ws_max,
+                                      const ColPlan &plan, int64_t c, uint32_t start, uint32_t stride,
+                                      float &mn, float &mx) {
+    const uint32_t j_lo = (uint32_t)((c * plan.hw) / plan.span);
+    const uint32_t j_hi = (uint32_t)(((c + 1) * plan.hw - 1) / plan.span);
+    const uint32_t nj = j_hi - j_lo + 1;
+    const uint32_t total = nj * (uint32_t)plan.row_groups;     // < 2^31: tiles x 65535 at most
+    for (uint32_t i = start; i < total; i += stride) {
+        const uint32_t pp = i / nj;
+        const uint32_t jj = j_lo + (i - pp * nj);
+        const int64_t k = c - ((int64_t)jj * plan.span) / plan.hw;
+        const int64_t at = ((int64_t)pp * plan.col_tiles + jj) * plan.kmax + k;
+        mn = __builtin_fminf(mn, ws_min[at]);
+        mx = __builtin_fmaxf(mx, ws_max[at]);
+    }
+}
+
+// Hand-over of a channel's parameters inside ONE launch (the forward that also finishes the
+// reduction): scale in the low word, zero-point in the high word of a 64-bit slot per channel,
+// written and read with single 64-bit accesses of device scope, so a reader sees either the
+// marker or both parameters.  The marker is a NaN pattern that Eq. 5 never produces (a NaN
+// scale becomes 1).
+constexpr uint32_t kParamsPending = 0xFFFFFFFFu;
+
+__device__ inline uint64_t pack_params(float s, float z) {
+    return (uint64_t)__float_as_uint(s) | ((uint64_t)__float_as_uint(z) << 32);
+}
+__device__ inline uint64_t load_params(const uint64_t *slot) {
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void publish_params(uint64_t *slot, uint64_t v) {
+    __hip_atomic_store(slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// What the forward needs to finish the reduction itself (granq_calibrate_fakequant_fwd).
+struct FinishArgs {
+    const float *ws_min, *ws_max;    // partials of the first pass
+    uint64_t *params;                // hand-over slots, one per channel; the first pass marked them pending
+    float *ch_min, *ch_max, *scale, *zero_point;   // the caller's four vectors
+    ColPlan rplan;                   // plan of the first pass (layout of the partials)
+    int32_t finisher_rows;           // leading rows of the grid whose blocks finish one channel each
+    int32_t spin_limit;              // polls before a waiting wavefront computes the parameters itself
+};
+
 // ---------------------------------------------------------------------------
 // fake-quant forward and straight-through backward, column kernels
 // ---------------------------------------------------------------------------
@@ -173,34 +231,46 @@ __device__ inline uint32_t vector_channels(uint32_t col, const ColPlan &plan, in
     return split;
 }
 
-// Shared prologue: this lane's vectors within a row and their channels' registers.
-// Returns true when every channel this lane touches admits the fast quotient.
-// GLUED: the plan may have glued rows (column -> column within the true row first).
+// Shared prologue, first half: this lane's vectors within a row and the channels of their
+// element groups.  GLUED: the plan may have glued rows (column -> column within the true row
+// first).
 template <typename T, int V, int MODE, bool GLUED = true>
-__device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *__restrict__ scale,
-                                  const float *__restrict__ zero_point,
-                                  ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N], uint32_t (&split)[V],
-                                  uint32_t (&cv)[V], bool (&active)[V]) {
+__device__ inline void lane_columns(const ColPlan &plan, uint32_t j,
+                                    int32_t (&ch)[V][Slots<MODE, T::VEC>::N], uint32_t (&split)[V],
+                                    uint32_t (&cv)[V], bool (&active)[V]) {
     constexpr int VEC = T::VEC;
     constexpr int NS = Slots<MODE, VEC>::N;
-    bool fast = GRANQ_FAST_QUOTIENT != 0;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const uint32_t col = j * (uint32_t)plan.span + (threadIdx.x + v * kEBlock) * VEC;
         active[v] = col < (uint32_t)plan.row_len;
         cv[v] = col / VEC;
-        int32_t ch[NS];
         const uint32_t tcol = GLUED ? true_column(col, plan) : col;
-        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? tcol : 0u, plan, ch);
+        split[v] = vector_channels<MODE, VEC, NS>(active[v] ? tcol : 0u, plan, ch[v]);
+    }
+}
+
+// Second half: the channels' registers from the scale and zero-point vectors.
+// Returns true when every channel this lane touches admits the fast quotient.
+template <typename T, int V, int MODE, bool GLUED = true>
+__device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *__restrict__ scale,
+                                  const float *__restrict__ zero_point,
+                                  ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N], uint32_t (&split)[V],
+                                  uint32_t (&cv)[V], bool (&active)[V]) {
+    constexpr int NS = Slots<MODE, T::VEC>::N;
+    int32_t ch[V][NS];
+    lane_columns<T, V, MODE, GLUED>(plan, j, ch, split, cv, active);
+    bool fast = GRANQ_FAST_QUOTIENT != 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v)
 #pragma unroll
         for (int e = 0; e < NS; ++e) {
-            const float s = scale[ch[e]], z = zero_point[ch[e]];
+            const float s = scale[ch[v][e]], z = zero_point[ch[v][e]];
             cr[v][e].s = s;
             cr[v][e].z = z;
             cr[v][e].r = 1.0f / s;
             fast = fast && quotient_fast_ok(s, z);
         }
-    }
     return fast;
 }
 
@@ -240,20 +310,26 @@ constexpr int kMask = 2;      // one bit per element: 1 where the clamp was inac
                               // flat NCHW index
 constexpr int kCodesOnly = 3; // the codes, and x_hat is not written at all
 
-template <typename T, int V, int U, int MODE, int EXTRA, bool FAST, bool NT>
-__device__ inline void fwd_rows(const typename T::vec_t *x,
-                                typename T::vec_t *x_hat, void *__restrict__ extra,
-                                float qmax, int64_t row_vecs, int64_t r, int nrows,
-                                const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
-                                const uint32_t (&split)[V], const uint32_t (&cv)[V],
-                                const bool (&active)[V]) {
-    constexpr int VEC = T::VEC;
-    typename T::vec_t in[U][V];
+// Rows r .. r + nrows - 1 of this lane's vectors, all loads issued together.
+template <typename T, int V, int U, bool NT>
+__device__ inline void fwd_load(const typename T::vec_t *x, int64_t row_vecs, int64_t r, int nrows,
+                                const uint32_t (&cv)[V], const bool (&active)[V],
+                                typename T::vec_t (&in)[U][V]) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int v = 0; v < V; ++v)
             if (u < nrows && active[v]) in[u][v] = load_vec<NT>(x + (r + u) * row_vecs + cv[v]);
+}
+
+// Quantize, clamp, dequantize and store what fwd_load fetched.
+template <typename T, int V, int U, int MODE, int EXTRA, bool FAST>
+__device__ inline void fwd_finish_rows(const typename T::vec_t (&in)[U][V], typename T::vec_t *x_hat,
+                                       void *__restrict__ extra, float qmax, int64_t row_vecs, int64_t r,
+                                       int nrows, const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
+                                       const uint32_t (&split)[V], const uint32_t (&cv)[V],
+                                       const bool (&active)[V]) {
+    constexpr int VEC = T::VEC;
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -293,6 +369,18 @@ __device__ inline void fwd_rows(const typename T::vec_t *x,
         }
 }
 
+template <typename T, int V, int U, int MODE, int EXTRA, bool FAST, bool NT>
+__device__ inline void fwd_rows(const typename T::vec_t *x,
+                                typename T::vec_t *x_hat, void *__restrict__ extra,
+                                float qmax, int64_t row_vecs, int64_t r, int nrows,
+                                const ChanRegs (&cr)[V][Slots<MODE, T::VEC>::N],
+                                const uint32_t (&split)[V], const uint32_t (&cv)[V],
+                                const bool (&active)[V]) {
+    typename T::vec_t in[U][V];
+    fwd_load<T, V, U, NT>(x, row_vecs, r, nrows, cv, active, in);
+    fwd_finish_rows<T, V, U, MODE, EXTRA, FAST>(in, x_hat, extra, qmax, row_vecs, r, nrows, cr, split, cv, active);
+}
+
 template <typename T, int V, int U, int MODE, int EXTRA>
 __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const typename T::vec_t *x, typename T::vec_t *x_hat,
@@ -314,6 +402,160 @@ __global__ __launch_bounds__(kEBlock) void fq_fwd_cols(
     const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
     int64_t r = r0;
     const bool nt = r0 < plan.nt_row_end;              // block-uniform
+    if (!fast) {
+        for (; r < r1; ++r)
+            fwd_rows<T, V, 1, MODE, EXTRA, false, false>(x, x_hat, extra, qmax, row_vecs, r, 1, cr, split, cv, active);
+    } else if (nt) {
+        for (; r + U <= r1; r += U)
+            fwd_rows<T, V, U, MODE, EXTRA, true, true>(x, x_hat, extra, qmax, row_vecs, r, U, cr, split, cv, active);
+        if (r < r1)
+            fwd_rows<T, V, U, MODE, EXTRA, true, true>(x, x_hat, extra, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
+    } else {
+        for (; r + U <= r1; r += U)
+            fwd_rows<T, V, U, MODE, EXTRA, true, false>(x, x_hat, extra, qmax, row_vecs, r, U, cr, split, cv, active);
+        if (r < r1)
+            fwd_rows<T, V, U, MODE, EXTRA, true, false>(x, x_hat, extra, qmax, row_vecs, r, (int)(r1 - r), cr, split, cv, active);
+    }
+}
+
+// Prologue of the forward that finishes the reduction: as lane_setup, but the parameters come
+// from the hand-over slots, which the finisher blocks of the same launch fill.
+// params_poll: one look at the slots of this lane's channels; true if any is still pending.
+template <int V, int NS>
+__device__ inline bool params_poll(const FinishArgs &fa, const int32_t (&ch)[V][NS], uint64_t (&pk)[V][NS],
+                                   bool first) {
+    bool pending = false;
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < NS; ++e)
+            if (first || (uint32_t)pk[v][e] == kParamsPending) {
+                pk[v][e] = load_params(fa.params + ch[v][e]);
+                pending = pending || (uint32_t)pk[v][e] == kParamsPending;
+            }
+    return pending;
+}
+
+// params_wait: a wavefront that found a slot pending polls it; after spin_limit polls it stops
+// waiting and derives the parameters from the partials itself (the same operations in the
+// same order, hence the same bits), so no wavefront ever depends on another one being
+// scheduled.  Called by whole wavefronts.
+template <int V, int NS>
+__device__ inline void params_wait(const FinishArgs &fa, float qmax, const int32_t (&ch)[V][NS],
+                                   uint64_t (&pk)[V][NS]) {
+    bool pending = true;
+    for (int32_t spins = 0; spins < fa.spin_limit && __any(pending); ++spins) {
+        __builtin_amdgcn_s_sleep(4);
+        pending = params_poll<V, NS>(fa, ch, pk, false);
+    }
+    if (!__any(pending)) return;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            bool mine = (uint32_t)pk[v][e] == kParamsPending;
+            uint64_t waiting;
+            while ((waiting = __ballot(mine)) != 0) {
+                // one pending channel at a time, all 64 lanes on its partials
+                const int leader = __builtin_ctzll(waiting);
+                const int32_t c = __builtin_amdgcn_readlane(ch[v][e], leader);
+                float mn = __builtin_inff(), mx = -__builtin_inff();
+                gather_channel(fa.ws_min, fa.ws_max, fa.rplan, c, lane, kWave, mn, mx);
+                mn = wave_min(mn);
+                mx = wave_max(mx);
+                float s, z;
+                prescale_one(mn, mx, qmax, s, z);
+                if (mine && ch[v][e] == c) {
+                    pk[v][e] = pack_params(s, z);
+                    mine = false;
+                }
+            }
+        }
+}
+
+template <int V, int NS>
+__device__ inline bool params_unpack(const uint64_t (&pk)[V][NS], ChanRegs (&cr)[V][NS]) {
+    bool fast = GRANQ_FAST_QUOTIENT != 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            const float s = __uint_as_float((uint32_t)pk[v][e]);
+            const float z = __uint_as_float((uint32_t)(pk[v][e] >> 32));
+            cr[v][e].s = s;
+            cr[v][e].z = z;
+            cr[v][e].r = 1.0f / s;
+            fast = fast && quotient_fast_ok(s, z);
+        }
+    return fast;
+}
+
+// granq_calibrate_fakequant_fwd's second launch: the forward, and in its leading
+// `finisher_rows` rows of blocks the end of the reduction.  A finisher wavefront owns one
+// channel: it gathers the channel's partials, applies Eq. 5, writes the caller's four
+// vectors and publishes scale and zero-point in the channel's hand-over slot.  The other
+// blocks are fq_fwd_cols with the prologue above.  Finishers have the lowest block indices,
+// so they are dispatched first; nothing depends on that beyond speed.
+template <typename T, int V, int U, int MODE, int EXTRA>
+__global__ __launch_bounds__(kEBlock) void fq_fwd_finish_cols(
+    const typename T::vec_t *x, typename T::vec_t *x_hat,
+    void *__restrict__ extra, float qmax, ColPlan plan, FinishArgs fa)
+{
+    constexpr int NS = Slots<MODE, T::VEC>::N;
+    if ((int32_t)blockIdx.y < fa.finisher_rows) {
+        const int64_t c = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (kEBlock / kWave) + threadIdx.x / kWave;
+        if (c >= fa.rplan.channels) return;            // wave-uniform
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        gather_channel(fa.ws_min, fa.ws_max, fa.rplan, c, threadIdx.x & (kWave - 1), kWave, mn, mx);
+        mn = wave_min(mn);
+        mx = wave_max(mx);
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+            float s, z;
+            prescale_one(mn, mx, qmax, s, z);
+            publish_params(fa.params + c, pack_params(s, z));
+            fa.ch_min[c] = mn;
+            fa.ch_max[c] = mx;
+            fa.scale[c] = s;
+            fa.zero_point[c] = z;
+        }
+        return;
+    }
+    const uint32_t rows_of_grid = gridDim.y - (uint32_t)fa.finisher_rows;
+    const uint32_t by = blockIdx.y - (uint32_t)fa.finisher_rows;
+    const uint32_t j = GRANQ_FWD_REVERSE ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    const uint32_t p = GRANQ_FWD_REVERSE ? rows_of_grid - 1 - by : by;
+    const int64_t row_vecs = plan.row_len / T::VEC;
+    const int64_t r0 = (int64_t)p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
+    const bool nt = r0 < plan.nt_row_end;              // block-uniform
+
+    int32_t ch[V][NS];
+    ChanRegs cr[V][NS];
+    uint32_t split[V], cv[V];
+    bool active[V];
+    uint64_t pk[V][NS];
+    lane_columns<T, V, MODE, true>(plan, j, ch, split, cv, active);
+    int64_t r = r0;
+    // The blocks that start before the finishers are through (the first wave of the launch) find
+    // their parameters pending: they fetch their first rows before they wait, so that the
+    // finishers' latency hides behind the loads.  Every later block takes the ordinary order,
+    // parameters first (that order streams faster).
+    typename T::vec_t first_rows[U][V];
+    int first_n = 0;
+    if (__any(params_poll<V, NS>(fa, ch, pk, true))) { // wave-uniform
+        first_n = (int)(r1 - r0 < U ? r1 - r0 : U);
+        if (nt) fwd_load<T, V, U, true>(x, row_vecs, r0, first_n, cv, active, first_rows);
+        else fwd_load<T, V, U, false>(x, row_vecs, r0, first_n, cv, active, first_rows);
+        params_wait<V, NS>(fa, qmax, ch, pk);
+    }
+    // wave-uniform: if any lane's channel needs the general division, the whole wavefront takes it
+    const bool fast = __all(params_unpack<V, NS>(pk, cr));
+    if (first_n > 0) {
+        if (fast) fwd_finish_rows<T, V, U, MODE, EXTRA, true>(first_rows, x_hat, extra, qmax, row_vecs, r0, first_n, cr, split, cv, active);
+        else fwd_finish_rows<T, V, U, MODE, EXTRA, false>(first_rows, x_hat, extra, qmax, row_vecs, r0, first_n, cr, split, cv, active);
+        r = r0 + first_n;
+    }
     if (!fast) {
         for (; r < r1; ++r)
             fwd_rows<T, V, 1, MODE, EXTRA, false, false>(x, x_hat, extra, qmax, row_vecs, r, 1, cr, split, cv, active);
@@ -486,10 +728,22 @@ __global__ __launch_bounds__(kBlock) void bwd_mask_bytes(
 // Pass 2: one wavefront per channel gathers the partials of all column tiles
 // that overlap the channel and of all row groups.
 
+// What the first pass does besides writing partials.
+struct Pass1Extra {
+    uint64_t *params;        // non-null: mark every channel's hand-over slot pending for the
+                             // forward that finishes the reduction (row group 0 does it)
+    int32_t direct;          // > 0: there is one row group and every channel lies inside one column
+                             // tile, which holds `direct` channels: the block's results are final and
+                             // go straight to the vectors below (no partials, no second pass)
+    float *ch_min, *ch_max;
+    float *scale, *zero_point;   // null: ranges only
+    float qmax;
+};
+
 template <typename T, int V, int MODE>
 __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
-    const typename T::vec_t *x, float *__restrict__ ws_min,
-    float *__restrict__ ws_max, ColPlan plan)
+    const typename T::vec_t *__restrict__ x, float *__restrict__ ws_min,
+    float *__restrict__ ws_max, ColPlan plan, Pass1Extra px)
 {
     constexpr int VEC = T::VEC;
     constexpr int NS = MODE == kOne ? 1 : VEC;           // running min/max per element position
@@ -622,19 +876,28 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
 
     __syncthreads();
 
+    if (px.direct > 0) {
+        for (int i = threadIdx.x; i < px.direct; i += kRBlock) {
+            const int32_t c = ch_first + i;
+            if (c >= plan.channels) break;
+            const float mn = key_float(lds_keys[i]), mx = key_float(lds_keys[kmax + i]);
+            px.ch_min[c] = mn;
+            px.ch_max[c] = mx;
+            if (px.scale) {
+                float sc, zp;
+                prescale_one(mn, mx, px.qmax, sc, zp);
+                px.scale[c] = sc;
+                px.zero_point[c] = zp;
+            }
+        }
+        return;
+    }
     const int64_t slot = ((int64_t)p * plan.col_tiles + (int64_t)j) * kmax;
     for (int i = threadIdx.x; i < kmax; i += kRBlock) {
         ws_min[slot + i] = key_float(lds_keys[i]);
         ws_max[slot + i] = key_float(lds_keys[kmax + i]);
+        if (px.params && p == 0 && ch_first + i < plan.channels) px.params[ch_first + i] = kParamsPending;
     }
-}
-
-// Eq. 5 for one channel: step size and zero-point from the channel's range.
-__device__ __forceinline__ void prescale_one(float mn, float mx, float qmax, float &s, float &z) {
-    const float range = mx - mn;
-    s = range / qmax;
-    if (!(s >= FLT_MIN)) s = 1.0f;                     // zero, subnormal or NaN scale
-    z = __builtin_rintf((-mn) / s) + 0.0f;             // "+ 0" turns -0 into +0
 }
 
 // `scale` / `zero_point` may be null (ranges only); otherwise Eq. 5 is applied
@@ -655,18 +918,7 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass2(
     const bool live = c < plan.channels;               // wave-uniform
     float mn = __builtin_inff(), mx = -__builtin_inff();
     if (live) {
-        const uint32_t j_lo = (uint32_t)((c * plan.hw) / plan.span);
-        const uint32_t j_hi = (uint32_t)(((c + 1) * plan.hw - 1) / plan.span);
-        const uint32_t nj = j_hi - j_lo + 1;
-        const uint32_t total = nj * (uint32_t)plan.row_groups;     // < 2^31: tiles x 65535 at most
-        for (uint32_t i = (uint32_t)((wave % WPC) * kWave + lane); i < total; i += kWave * WPC) {
-            const uint32_t pp = i / nj;
-            const uint32_t jj = j_lo + (i - pp * nj);
-            const int64_t k = c - ((int64_t)jj * plan.span) / plan.hw;
-            const int64_t at = ((int64_t)pp * plan.col_tiles + jj) * plan.kmax + k;
-            mn = __builtin_fminf(mn, ws_min[at]);
-            mx = __builtin_fmaxf(mx, ws_max[at]);
-        }
+        gather_channel(ws_min, ws_max, plan, c, (uint32_t)((wave % WPC) * kWave + lane), kWave * WPC, mn, mx);
         mn = wave_min(mn);
         mx = wave_max(mx);
     }
@@ -882,13 +1134,33 @@ static ColPlan bwd_plan(const granq_desc_t *d) {
     return p;
 }
 
-// Plan of the reduction; it also fixes the workspace layout.
+// Plan of the reduction; it also fixes the workspace layout.  Blocks of GRANQ_R_MIN_ROWS rows
+// (few partials, cheap epilogue) where that still gives the chip GRANQ_R_WANT_BLOCKS blocks
+// (eight per compute unit); smaller tensors get half as many rows per block.
+#ifndef GRANQ_R_WANT_BLOCKS
+#define GRANQ_R_WANT_BLOCKS 2048
+#endif
 static ColPlan range_plan(const granq_desc_t *d) {
-    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                              d->dtype == GRANQ_F32 ? GRANQ_R_V_F32 : GRANQ_R_V_BF16, kRBlock,
+    const int v = d->dtype == GRANQ_F32 ? GRANQ_R_V_F32 : GRANQ_R_V_BF16;
+    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), v, kRBlock,
                               GRANQ_R_TARGET_BLOCKS, GRANQ_R_MIN_ROWS);
+    // (a tensor of at most 2 * GRANQ_R_MIN_ROWS rows keeps its single or two row groups: with one
+    // group and whole channels per column tile the first pass is the whole reduction)
+    if (p.ok && GRANQ_R_MIN_ROWS > 1 && p.rows > 2 * GRANQ_R_MIN_ROWS &&
+        (int64_t)p.col_tiles * p.row_groups < GRANQ_R_WANT_BLOCKS)
+        p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), v, kRBlock,
+                          GRANQ_R_TARGET_BLOCKS, (GRANQ_R_MIN_ROWS + 1) / 2);
     split_large(p, d);
     return p;
+}
+
+// Channels per column tile if the first pass alone produces final ranges (one row group, and
+// no channel shared between column tiles), else 0.
+static int32_t direct_channels(const ColPlan &p) {
+    if (!p.ok || p.row_groups != 1) return 0;
+    if (p.col_tiles == 1) return p.channels;
+    if (p.channels > 1 && p.span % p.hw == 0) return (int32_t)(p.span / p.hw);
+    return 0;
 }
 
 // Grid of the row kernels: enough wavefronts to fill the chip, no more than slabs.
@@ -956,21 +1228,85 @@ static void launch_bwd_cols(const ColPlan &pl, const void *x, const void *dy, vo
 
 template <typename T, int V>
 static void launch_range_cols(const ColPlan &pl, const void *x, float *ws_min, float *ws_max,
-                              hipStream_t st) {
+                              const Pass1Extra &px, hipStream_t st) {
     using vec_t = typename T::vec_t;
     dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kRBlock);
     size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
     auto xv = (const vec_t *)x;
     if (pl.mode == kOne)
-        launch_kernel((range_cols_pass1<T, V, kOne>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+        launch_kernel((range_cols_pass1<T, V, kOne>), grid, block, lds, st, xv, ws_min, ws_max, pl, px);
     else if (pl.mode == kTwo)
-        launch_kernel((range_cols_pass1<T, V, kTwo>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+        launch_kernel((range_cols_pass1<T, V, kTwo>), grid, block, lds, st, xv, ws_min, ws_max, pl, px);
     else
-        launch_kernel((range_cols_pass1<T, V, kEach>), grid, block, lds, st, xv, ws_min, ws_max, pl);
+        launch_kernel((range_cols_pass1<T, V, kEach>), grid, block, lds, st, xv, ws_min, ws_max, pl, px);
+}
+
+static void launch_range_cols_any(const granq_desc_t *desc, const ColPlan &pl, const void *x, float *ws_min,
+                                  float *ws_max, const Pass1Extra &px, hipStream_t st) {
+    if (desc->dtype == GRANQ_F32) launch_range_cols<F32, GRANQ_R_V_F32>(pl, x, ws_min, ws_max, px, st);
+    else if (desc->dtype == GRANQ_BF16) launch_range_cols<BF16, GRANQ_R_V_BF16>(pl, x, ws_min, ws_max, px, st);
+    else launch_range_cols<F16, GRANQ_R_V_BF16>(pl, x, ws_min, ws_max, px, st);
+}
+
+// The forward that finishes the reduction: grid = finisher rows, then the forward's own rows.
+template <typename T, int V, int MODE>
+static void launch_fwd_finish_mode(const ColPlan &pl, const void *x, void *x_hat, void *extra, int kind,
+                                   float qmax, const FinishArgs &fa, hipStream_t st) {
+    using vec_t = typename T::vec_t;
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)(pl.row_groups + fa.finisher_rows)), block(kEBlock);
+    auto xv = (const vec_t *)x;
+    auto yv = (vec_t *)x_hat;
+    if (kind == kCodes) launch_kernel((fq_fwd_finish_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, qmax, pl, fa);
+    else if (kind == kCodesOnly) launch_kernel((fq_fwd_finish_cols<T, V, GRANQ_F_ROWS, MODE, kCodesOnly>), grid, block, 0, st, xv, yv, extra, qmax, pl, fa);
+    else launch_kernel((fq_fwd_finish_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, qmax, pl, fa);
+}
+
+template <typename T, int V>
+static void launch_fwd_finish(const ColPlan &pl, const void *x, void *x_hat, void *extra, int kind,
+                              float qmax, const FinishArgs &fa, hipStream_t st) {
+    if (pl.mode == kOne) launch_fwd_finish_mode<T, V, kOne>(pl, x, x_hat, extra, kind, qmax, fa, st);
+    else if (pl.mode == kTwo) launch_fwd_finish_mode<T, V, kTwo>(pl, x, x_hat, extra, kind, qmax, fa, st);
+    else launch_fwd_finish_mode<T, V, kEach>(pl, x, x_hat, extra, kind, qmax, fa, st);
 }
 
 static size_t col_ws_floats(const ColPlan &pl) {
     return (size_t)pl.row_groups * pl.col_tiles * pl.kmax;
+}
+
+// Column path: partial minima, partial maxima, then one 8-byte hand-over slot per channel.
+static size_t col_params_offset(const ColPlan &pl) {
+    return (2 * col_ws_floats(pl) * sizeof(float) + 7) & ~(size_t)7;
+}
+static size_t col_ws_bytes(const ColPlan &pl) {
+    return col_params_offset(pl) + (size_t)pl.channels * sizeof(uint64_t);
+}
+
+// Argument checks of the forward; scale / zero_point may be vectors it will be given later.
+static granq_status_t fwd_check(const void *x, const granq_desc_t *desc, const float *scale,
+                                const float *zero_point, int bits, const void *x_hat,
+                                const uint8_t *codes_or_null) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!x || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (!x_hat && !codes_or_null) return GRANQ_ERR_INVALID_ARG;      // nothing to write
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(x, desc->dtype) || (x_hat && !aligned_elem(x_hat, desc->dtype)) ||
+        !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
+        return GRANQ_ERR_UNSUPPORTED;
+    return GRANQ_OK;
+}
+
+// The 128-bit column kernels of the forward apply: plan, pointers, packed-code alignment
+// (codes are stored VEC bytes at a time).
+static bool fwd_cols_ok(const ColPlan &cp, const granq_desc_t *desc, const void *x, const void *x_hat,
+                        const uint8_t *codes_or_null) {
+    const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
+    return cp.ok && aligned16(x) && (!x_hat || aligned16(x_hat)) && codes_ok;
+}
+
+// Partials per channel: row groups x the column tiles a channel can overlap.
+static int64_t partials_per_channel(const ColPlan &pl) {
+    return (int64_t)pl.row_groups * ((pl.hw - 1) / pl.span + 2);
 }
 
 }  // namespace granq
@@ -998,10 +1334,10 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
     if (st != GRANQ_OK) return st;
     const int64_t hw = desc->h * desc->w;
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);
-    size_t floats = (size_t)rp.row_groups * (size_t)desc->c;
+    size_t bytes = 2 * (size_t)rp.row_groups * (size_t)desc->c * sizeof(float);
     ColPlan cp = range_plan(desc);
-    if (cp.ok && col_ws_floats(cp) > floats) floats = col_ws_floats(cp);
-    *bytes_out = 2 * floats * sizeof(float);
+    if (cp.ok && col_ws_bytes(cp) > bytes) bytes = col_ws_bytes(cp);
+    *bytes_out = bytes;
     return GRANQ_OK;
 }
 
@@ -1028,14 +1364,15 @@ granq_status_t granq_plan_describe(const granq_desc_t *desc, int64_t out[24]) {
     out[14] = bp.rows_per_group;
     out[15] = fp.span;
     out[16] = cp.fold;
-    for (int i = 17; i < 24; ++i) out[i] = 0;
+    out[17] = one_call_forward_launches(desc);
+    out[18] = !cp.ok ? 2 : (direct_channels(cp) > 0 ? 1 : 2);
+    for (int i = 19; i < 24; ++i) out[i] = 0;
     return GRANQ_OK;
 }
 
-// Ranges, and with non-null `scale` / `zero_point` also Eq. 5, in two launches.
-static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float *ch_min,
-                                 float *ch_max, float qmax, float *scale, float *zero_point,
-                                 void *workspace, size_t workspace_bytes, void *stream) {
+// Argument checks of the reduction (nothing is launched on a refusal).
+static granq_status_t range_check(const void *x, const granq_desc_t *desc, const float *ch_min,
+                                  const float *ch_max, const void *workspace, size_t workspace_bytes) {
     granq_status_t st = check_desc(desc);
     if (st != GRANQ_OK) return st;
     if (!x || !ch_min || !ch_max) return GRANQ_ERR_INVALID_ARG;
@@ -1044,6 +1381,30 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
     size_t need = 0;
     granq_workspace_bytes(desc, &need);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return GRANQ_ERR_WORKSPACE;
+    return GRANQ_OK;
+}
+
+static void launch_range_pass2(const ColPlan &cp, const float *ws_min, const float *ws_max, float *ch_min,
+                               float *ch_max, float qmax, float *scale, float *zero_point, hipStream_t hs) {
+    dim3 block(kBlock);
+    if (partials_per_channel(cp) > 512) {
+        dim3 grid((uint32_t)cp.channels);
+        launch_kernel(range_cols_pass2<kBlock / kWave>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+                      qmax, scale, zero_point);
+    } else {
+        dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave));
+        launch_kernel(range_cols_pass2<1>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
+                      qmax, scale, zero_point);
+    }
+}
+
+// Ranges, and with non-null `scale` / `zero_point` also Eq. 5: two launches, or one where the
+// first pass already holds every channel whole.
+static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float *ch_min,
+                                 float *ch_max, float qmax, float *scale, float *zero_point,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
+    granq_status_t st = range_check(x, desc, ch_min, ch_max, workspace, workspace_bytes);
+    if (st != GRANQ_OK) return st;
     hipStream_t hs = (hipStream_t)stream;
     const int64_t hw = desc->h * desc->w;
     ColPlan cp = range_plan(desc);
@@ -1051,23 +1412,18 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
         const size_t floats = col_ws_floats(cp);
         float *ws_min = (float *)workspace;
         float *ws_max = ws_min + floats;
-        if (desc->dtype == GRANQ_F32) launch_range_cols<F32, GRANQ_R_V_F32>(cp, x, ws_min, ws_max, hs);
-        else if (desc->dtype == GRANQ_BF16) launch_range_cols<BF16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
-        else launch_range_cols<F16, GRANQ_R_V_BF16>(cp, x, ws_min, ws_max, hs);
+        Pass1Extra px{};
+        px.direct = direct_channels(cp);
+        px.ch_min = ch_min;
+        px.ch_max = ch_max;
+        px.scale = scale;
+        px.zero_point = zero_point;
+        px.qmax = qmax;
+        launch_range_cols_any(desc, cp, x, ws_min, ws_max, px, hs);
+        if (px.direct > 0) return launched();
         st = launched();
         if (st != GRANQ_OK) return st;
-        dim3 block(kBlock);
-        // partials per channel: row groups x the column tiles a channel overlaps
-        const int64_t per_channel = (int64_t)cp.row_groups * ((cp.hw - 1) / cp.span + 2);
-        if (per_channel > 512) {
-            dim3 grid((uint32_t)cp.channels);
-            launch_kernel(range_cols_pass2<kBlock / kWave>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
-                               qmax, scale, zero_point);
-        } else {
-            dim3 grid((uint32_t)ceil_div(cp.channels, kBlock / kWave));
-            launch_kernel(range_cols_pass2<1>, grid, block, 0, hs, ws_min, ws_max, ch_min, ch_max, cp,
-                               qmax, scale, zero_point);
-        }
+        launch_range_pass2(cp, ws_min, ws_max, ch_min, ch_max, qmax, scale, zero_point, hs);
         return launched();
     }
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);
@@ -1140,6 +1496,93 @@ granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits
                       workspace, workspace_bytes, stream);
 }
 
+}  // extern "C"
+
+namespace granq {
+
+// The two-launch form can be compiled out (-DGRANQ_TWO_LAUNCH=0) to measure it against three.
+#ifndef GRANQ_TWO_LAUNCH
+#define GRANQ_TWO_LAUNCH 1
+#endif
+
+// Polls of a hand-over slot before a waiting wavefront of the finishing forward computes the
+// parameters itself (about a microsecond each).  GRANQ_SPIN_LIMIT in the environment
+// overrides it; tests set it to 0 so that every waiting wavefront takes that path.
+static int32_t spin_limit() {
+    const char *e = getenv("GRANQ_SPIN_LIMIT");
+    if (e && *e) {
+        const long v = strtol(e, nullptr, 10);
+        return (int32_t)(v < 0 ? 0 : (v > (1 << 24) ? (1 << 24) : v));
+    }
+    return 20000;
+}
+
+// Channels per finisher block of the finishing forward, and the rows of blocks they take.
+static int64_t finisher_rows_of(const ColPlan &cp, const ColPlan &fp) {
+    return ceil_div(ceil_div(cp.channels, kEBlock / kWave), fp.col_tiles);
+}
+
+bool two_launches_apply(const void *x, const granq_desc_t *desc, const void *x_hat,
+                        const uint8_t *codes_or_null) {
+    if (!GRANQ_TWO_LAUNCH || check_desc(desc) != GRANQ_OK) return false;
+    const ColPlan cp = range_plan(desc), fp = fwd_plan(desc);
+    if (!cp.ok || !x || !aligned16(x) || !fwd_cols_ok(fp, desc, x, x_hat, codes_or_null)) return false;
+    // the first pass alone is final, or a channel has more partials than one wavefront should gather
+    if (direct_channels(cp) > 0 || partials_per_channel(cp) > 512) return false;
+    return fp.row_groups + finisher_rows_of(cp, fp) <= 65535;
+}
+
+// Alg. 1 up to the accumulation in two launches for tensors on the 128-bit column path:
+// the first pass of the reduction, then the forward, whose leading blocks finish the
+// reduction (second pass and Eq. 5) and hand scale and zero-point to the others through the
+// workspace.
+granq_status_t calibrate_fwd_two_launches(const void *x, const granq_desc_t *desc, int bits, float *ch_min,
+                                          float *ch_max, float *scale, float *zero_point, void *x_hat,
+                                          uint8_t *codes_or_null, void *workspace, size_t workspace_bytes,
+                                          void *stream) {
+    const ColPlan cp = range_plan(desc), fp = fwd_plan(desc);
+    const int64_t finisher_rows = finisher_rows_of(cp, fp);
+    // the checks of granq_calibrate and of granq_fakequant_fwd, all before the first launch
+    if (!scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32)) return GRANQ_ERR_UNSUPPORTED;
+    granq_status_t st = range_check(x, desc, ch_min, ch_max, workspace, workspace_bytes);
+    if (st != GRANQ_OK) return st;
+    st = fwd_check(x, desc, scale, zero_point, bits, x_hat, codes_or_null);
+    if (st != GRANQ_OK) return st;
+
+    hipStream_t hs = (hipStream_t)stream;
+    const float qmax = (float)((1 << bits) - 1);
+    float *ws_min = (float *)workspace;
+    float *ws_max = ws_min + col_ws_floats(cp);
+    uint64_t *params = (uint64_t *)((char *)workspace + col_params_offset(cp));
+    Pass1Extra px{};
+    px.params = params;
+    launch_range_cols_any(desc, cp, x, ws_min, ws_max, px, hs);
+    st = launched();
+    if (st != GRANQ_OK) return st;
+    FinishArgs fa{};
+    fa.ws_min = ws_min;
+    fa.ws_max = ws_max;
+    fa.params = params;
+    fa.ch_min = ch_min;
+    fa.ch_max = ch_max;
+    fa.scale = scale;
+    fa.zero_point = zero_point;
+    fa.rplan = cp;
+    fa.finisher_rows = (int32_t)finisher_rows;
+    fa.spin_limit = spin_limit();
+    const int kind = !x_hat ? kCodesOnly : (codes_or_null ? kCodes : kNoExtra);
+    if (desc->dtype == GRANQ_F32) launch_fwd_finish<F32, GRANQ_E_V_F32>(fp, x, x_hat, codes_or_null, kind, qmax, fa, hs);
+    else if (desc->dtype == GRANQ_BF16) launch_fwd_finish<BF16, GRANQ_E_V_BF16>(fp, x, x_hat, codes_or_null, kind, qmax, fa, hs);
+    else launch_fwd_finish<F16, GRANQ_E_V_BF16>(fp, x, x_hat, codes_or_null, kind, qmax, fa, hs);
+    return launched();
+}
+
+}  // namespace granq
+
+extern "C" {
+
 granq_status_t granq_prescale(const float *ch_min, const float *ch_max, int64_t c, int bits,
                               float *scale, float *zero_point, void *stream) {
     if (!ch_min || !ch_max || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
@@ -1157,20 +1600,12 @@ granq_status_t granq_prescale(const float *ch_min, const float *ch_max, int64_t 
 granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, const float *scale,
                                    const float *zero_point, int bits, void *x_hat,
                                    uint8_t *codes_or_null, void *stream) {
-    granq_status_t st = check_desc(desc);
+    granq_status_t st = fwd_check(x, desc, scale, zero_point, bits, x_hat, codes_or_null);
     if (st != GRANQ_OK) return st;
-    if (!x || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
-    if (!x_hat && !codes_or_null) return GRANQ_ERR_INVALID_ARG;      // nothing to write
-    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
-    if (!aligned_elem(x, desc->dtype) || (x_hat && !aligned_elem(x_hat, desc->dtype)) ||
-        !aligned_elem(scale, GRANQ_F32) || !aligned_elem(zero_point, GRANQ_F32))
-        return GRANQ_ERR_UNSUPPORTED;
     const float qmax = (float)((1 << bits) - 1);
     hipStream_t hs = (hipStream_t)stream;
     ColPlan cp = fwd_plan(desc);
-    // packed codes are stored VEC bytes at a time
-    const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
-    if (cp.ok && aligned16(x) && (!x_hat || aligned16(x_hat)) && codes_ok) {
+    if (fwd_cols_ok(cp, desc, x, x_hat, codes_or_null)) {
         const int kind = !x_hat ? kCodesOnly : (codes_or_null ? kCodes : kNoExtra);
         if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);
         else if (desc->dtype == GRANQ_BF16) launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat, codes_or_null, kind, scale, zero_point, qmax, hs);

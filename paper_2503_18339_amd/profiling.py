@@ -34,7 +34,8 @@ def source_hash() -> str:
     """Hash of everything that determines the code of the four-call kernels: their source,
     the device headers it includes and the compiler flags."""
     h = hashlib.sha256()
-    names = ("granq_kernels.hip", "granq_device.h", "granq_plan.h", "granq_quotient.h")
+    names = ("granq_kernels.hip", "granq_device.h", "granq_plan.h", "granq_quotient.h", "granq_launch.h",
+             "granq_internal.h")
     paths = [os.path.join(_build.CSRC, n) for n in names]
     for path in sorted(paths):
         with open(path, "rb") as fh:
@@ -103,19 +104,23 @@ def summarise_counters(fetch_csv: str, write_csv: str, copy_bytes: int, dominant
     name, (fb, wb, shapes) = max(dom, key=lambda kr: kr[1][0] + kr[1][1])
     record = {"kernel": name, "launch_shapes": shapes, "fetch_bytes_per_launch": fb / shapes,
               "write_bytes_per_launch": wb / shapes, "traffic_bytes_per_launch": (fb + wb) / shapes,
-              "fetch_scale": f_scale, "write_scale": w_scale, "source_hash": source_hash()}
+              "fetch_scale": f_scale, "write_scale": w_scale, "source_hash": source_hash(),
+              "workload": "config3", "dtype": "f32"}
     lines += ["", "dominant kernel %s: %.2f MB fetched + %.2f MB written per launch (mean over its %d launch shapes)"
               % (name, fb / shapes / 1e6, wb / shapes / 1e6, shapes)]
     return "\n".join(lines), record
 
 
-def load_record():
-    """The stored traffic figure, or None when it was taken from other kernel sources."""
+def load_record(workload: str = "config3", dtype: str = "f32"):
+    """The stored traffic figure, or None when it was taken from other kernel sources, on
+    another workload or with another storage type than the launch it is to describe."""
     try:
         rec = json.load(open(RECORD))
     except (OSError, ValueError):
         return None
-    return rec if rec.get("source_hash") == source_hash() else None
+    same = (rec.get("source_hash") == source_hash() and rec.get("workload", "config3") == workload
+            and rec.get("dtype", "f32") == dtype)
+    return rec if same else None
 
 
 TRACE_HEADER = """Kernel times of the default benchmark run (ResNet-18 ImageNet activation set, batch 256, float32,

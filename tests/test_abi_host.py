@@ -164,7 +164,9 @@ def test_plan_invariants(shape, dtype):
     assert (pl["col_tiles"] - 1) * pl["span"] < pl["row_len"] <= pl["col_tiles"] * pl["span"]
     assert (pl["row_groups"] - 1) * pl["rows_per_group"] < pl["rows"] <= pl["row_groups"] * pl["rows_per_group"]
     assert pl["uniform"] == (1 if pl["hw"] % vec == 0 else 0)
-    assert 2 * 4 * pl["row_groups"] * pl["col_tiles"] * pl["kmax"] <= need
+    # partial minima and maxima, then one 8-byte hand-over slot per channel
+    channels = pl["row_len"] // f // pl["hw"]
+    assert 2 * 4 * pl["row_groups"] * pl["col_tiles"] * pl["kmax"] + 8 * channels <= need
     # every column tile touches at most kmax channels
     if f == 1:
         j = np.arange(pl["col_tiles"], dtype=np.int64)

@@ -215,6 +215,54 @@ def test_in_place_every_kernel_family(shape, misaligned, dtype):
     assert_parity(got, want, "one-call forward in place %s" % (shape,))
 
 
+# Channels of more than 128 KB: the one-call forward takes two launches, the second one finishing
+# the reduction in its leading blocks while the others wait for their channels' parameters.
+TWO_LAUNCH = [
+    ((64, 24, 28, 28), torch.float32),      # one channel per vector
+    ((700, 100, 7, 7), torch.float32),      # vectors straddle two channels
+    ((40000, 40, 1, 1), torch.float32),     # every element its own channel, glued rows
+    ((96, 16, 32, 32), torch.bfloat16),
+    ((1500, 36, 7, 7), torch.float16),
+    ((1, 1, 1, 1 << 20), torch.float32),    # layer-wise view
+    ((300, 3, 40, 40), torch.float32),      # channels that span many column tiles
+]
+
+
+@pytest.mark.parametrize("spin_limit", [None, "0", "3"], ids=["default", "nowait", "shortwait"])
+@pytest.mark.parametrize("shape,dtype", TWO_LAUNCH, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v)[6:])
+def test_one_call_forward_in_two_launches(shape, dtype, spin_limit, monkeypatch):
+    """All six outputs of granq_calibrate_fakequant_fwd against the oracle, with the default
+    wait, with no wait at all (every wavefront that finds its parameters pending derives them
+    from the partials itself) and with a wait of three polls."""
+    if spin_limit is None:
+        monkeypatch.delenv("GRANQ_SPIN_LIMIT", raising=False)
+    else:
+        monkeypatch.setenv("GRANQ_SPIN_LIMIT", spin_limit)
+    for i, (law, bits) in enumerate([("relu", 4), ("linear", 3)]):
+        x = workloads.make_activation(shape, law, (0.05, 20.0), seed=20 + i, device=DEV, dtype=dtype)
+        d = G.desc_of(x)
+        vec = [torch.full((d.c,), float("nan"), device=DEV) for _ in range(4)]
+        ws = torch.full((max(16, G.granq_workspace_bytes(d)),), 0xA5, dtype=torch.uint8, device=DEV)
+        xh = torch.empty_like(x)
+        codes = torch.full(x.shape, 255, dtype=torch.uint8, device=DEV)
+        for rep in range(2):                 # the second call finds the first one's hand-over slots filled
+            G.granq_calibrate_fakequant_fwd(x, bits, vec[0], vec[1], vec[2], vec[3], xh, codes, ws)
+        torch.cuda.synchronize()
+        got = {"min": vec[0].cpu().numpy(), "max": vec[1].cpu().numpy(), "scale": vec[2].cpu().numpy(),
+               "zero_point": vec[3].cpu().numpy(), "xhat": to_numpy(xh), "codes": codes.cpu().numpy()}
+        want = oracle_path(to_numpy(x), bits)
+        assert_parity(got, want, "two launches %s %s spin=%s" % (shape, law, spin_limit))
+        # codes alone, and x_hat alone
+        only = torch.full(x.shape, 254, dtype=torch.uint8, device=DEV)
+        G.granq_calibrate_fakequant_fwd(x, bits, vec[0], vec[1], vec[2], vec[3], None, only, ws)
+        xh2 = torch.empty_like(x)
+        G.granq_calibrate_fakequant_fwd(x, bits, vec[0], vec[1], vec[2], vec[3], xh2, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(only, codes)
+        ib = torch.int32 if dtype == torch.float32 else torch.int16
+        assert torch.equal(xh2.view(ib), xh.view(ib))
+
+
 def test_misaligned_pointers_take_the_elementwise_path():
     """A tensor that starts 4 bytes into an allocation: same results, no fault."""
     for dtype in (torch.float32, torch.bfloat16, torch.float16):
