@@ -25,26 +25,12 @@
 #include "granq_device.h"
 #include "granq_launch.h"
 #include "granq_plan.h"
+#include "granq_tiling.h"
 #include "granq_internal.h"
 #include "granq_quotient.h"
 
 namespace granq {
 
-// Vectors per lane and row for the element-wise (E: forward, backward) and the
-// reduction (R) column kernels, and rows in flight per lane in the reduction.
-// (Forward and backward keep GRANQ_F_ROWS / GRANQ_B_ROWS rows in flight.)
-#ifndef GRANQ_E_V_F32
-#define GRANQ_E_V_F32 1
-#endif
-#ifndef GRANQ_E_V_BF16
-#define GRANQ_E_V_BF16 1
-#endif
-#ifndef GRANQ_R_V_F32
-#define GRANQ_R_V_F32 1
-#endif
-#ifndef GRANQ_R_V_BF16
-#define GRANQ_R_V_BF16 1
-#endif
 #ifndef GRANQ_R_UNROLL
 #define GRANQ_R_UNROLL 8
 #endif
@@ -61,38 +47,6 @@ namespace granq {
 // Five-operation exact quotient (granq_quotient.h) instead of the general division.
 #ifndef GRANQ_FAST_QUOTIENT
 #define GRANQ_FAST_QUOTIENT 1
-#endif
-
-// Threads per block of the element-wise column kernels (the reduction and the
-// row kernels use kBlock).
-#ifndef GRANQ_E_BLOCK
-#define GRANQ_E_BLOCK 64
-#endif
-constexpr int kEBlock = GRANQ_E_BLOCK;
-// Threads per block of the reduction's first pass.
-#ifndef GRANQ_R_BLOCK
-#define GRANQ_R_BLOCK 256
-#endif
-constexpr int kRBlock = GRANQ_R_BLOCK;
-
-// Streaming policy.  Data that cannot survive in the caches until it is needed
-// again is loaded with non-temporal loads, which on MI355X stream markedly
-// faster than ordinary loads; data that the next kernel re-reads is loaded
-// normally so that it stays resident.
-//   - a tensor of at least GRANQ_STREAM_BYTES is "large": the reduction and the
-//     forward stream all of it except its last GRANQ_KEEP_BYTES, which the
-//     reduction leaves in the memory-side cache and the (reverse-order) forward
-//     picks up from there;
-//   - the backward streams x and dy of any tensor of at least
-//     GRANQ_BWD_STREAM_BYTES.
-#ifndef GRANQ_STREAM_BYTES
-#define GRANQ_STREAM_BYTES ((int64_t)384 << 20)
-#endif
-#ifndef GRANQ_KEEP_BYTES
-#define GRANQ_KEEP_BYTES ((int64_t)160 << 20)
-#endif
-#ifndef GRANQ_BWD_STREAM_BYTES
-#define GRANQ_BWD_STREAM_BYTES ((int64_t)96 << 20)
 #endif
 
 template <bool NT, typename V>
@@ -134,22 +88,14 @@ __device__ __forceinline__ void prescale_one(float mn, float mx, float qmax, flo
     z = __builtin_rintf((-mn) / s) + 0.0f;             // "+ 0" turns -0 into +0
 }
 
-// The first pass of the reduction leaves one partial min / max per (row group p, column tile
-// j, channel slot k) at  ws[(p * J + j) * kmax + k],  k = channel - first channel of tile j.
-// Partials of channel c: of all row groups and of the column tiles that overlap the channel.
-// Work item i of them goes to the caller with  i = start, start + stride, ...
+// Min / max over the partials of channel c that the first pass of the reduction left in the
+// workspace (granq_plan.h: channel_partials); the caller takes items start, start + stride, ...
 __device__ inline void gather_channel(const float *__restrict__ ws_min, const float *__restrict__ ws_max,
                                       const ColPlan &plan, int64_t c, uint32_t start, uint32_t stride,
                                       float &mn, float &mx) {
-    const uint32_t j_lo = (uint32_t)((c * plan.hw) / plan.span);
-    const uint32_t j_hi = (uint32_t)(((c + 1) * plan.hw - 1) / plan.span);
-    const uint32_t nj = j_hi - j_lo + 1;
-    const uint32_t total = nj * (uint32_t)plan.row_groups;     // < 2^31: tiles x 65535 at most
-    for (uint32_t i = start; i < total; i += stride) {
-        const uint32_t pp = i / nj;
-        const uint32_t jj = j_lo + (i - pp * nj);
-        const int64_t k = c - ((int64_t)jj * plan.span) / plan.hw;
-        const int64_t at = ((int64_t)pp * plan.col_tiles + jj) * plan.kmax + k;
+    const ChannelPartials cp = channel_partials(plan, c);
+    for (uint32_t i = start; i < cp.total; i += stride) {
+        const int64_t at = channel_partial_slot(plan, c, cp, i);
         mn = __builtin_fminf(mn, ws_min[at]);
         mx = __builtin_fmaxf(mx, ws_max[at]);
     }
@@ -186,14 +132,6 @@ struct FinishArgs {
 // fake-quant forward and straight-through backward, column kernels
 // ---------------------------------------------------------------------------
 
-// How the elements of one 16-byte vector map to channels (template parameter MODE):
-//   kOne   H*W is a multiple of the vector width: the whole vector is one channel
-//   kTwo   H*W >= vector width: at most two channels, elements [0, split) and [split, VEC)
-//   kEach  H*W < vector width: every element may have its own channel
-constexpr int kOne = 0, kTwo = 1, kEach = 2;
-template <int MODE, int VEC>
-struct Slots { static constexpr int N = MODE == kOne ? 1 : (MODE == kTwo ? 2 : VEC); };
-
 template <int MODE, int NS>
 __device__ inline ChanRegs pick_chan(const ChanRegs (&c)[NS], int e, uint32_t split) {
     if (MODE == kOne) return c[0];
@@ -204,31 +142,6 @@ __device__ inline ChanRegs pick_chan(const ChanRegs (&c)[NS], int e, uint32_t sp
     r.z = first ? c[0].z : c[NS > 1 ? 1 : 0].z;
     r.r = first ? c[0].r : c[NS > 1 ? 1 : 0].r;
     return r;
-}
-
-// Channels of this lane's vector starting at column `col`: ch[] per slot, and the
-// number of leading elements that belong to the first channel.
-template <int MODE, int VEC, int NS>
-__device__ inline uint32_t vector_channels(uint32_t col, const ColPlan &plan, int32_t (&ch)[NS]) {
-    const uint32_t c0 = fastdiv(col, plan.hw_div);
-    const uint32_t rem = col - c0 * plan.hw_div.d;
-    if (MODE == kEach) {
-        uint32_t c = c0, r = rem;
-        ch[0] = (int32_t)c;
-#pragma unroll
-        for (int e = 1; e < NS; ++e) {
-            r += 1;
-            if (r == plan.hw_div.d) { r = 0; c += 1; }
-            ch[e] = (int32_t)c;
-        }
-        return VEC;
-    }
-    ch[0] = (int32_t)c0;
-    if (MODE == kOne) return VEC;
-    const uint32_t left = plan.hw_div.d - rem;           // elements of channel c0 from col on
-    const uint32_t split = left < (uint32_t)VEC ? left : (uint32_t)VEC;
-    ch[NS > 1 ? 1 : 0] = (int32_t)(split < (uint32_t)VEC ? c0 + 1 : c0);
-    return split;
 }
 
 // Shared prologue, first half: this lane's vectors within a row and the channels of their
@@ -276,23 +189,6 @@ __device__ inline bool lane_setup(const ColPlan &plan, uint32_t j, const float *
 
 #ifndef GRANQ_MASK_NT
 #define GRANQ_MASK_NT 0
-#endif
-// Shape of a block of the forward that also writes gate bits: vectors per lane
-// along the row and rows.  A wavefront's bits for one row are contiguous:
-// 32 bytes per float32 vector slot, 64 per bfloat16 one.
-// Measured on the 822 MB tensor: float32 2 x 1 costs 14 us more than the plain
-// forward, 1 x 2 costs 22, 4 x 1 costs 39; bfloat16 1 x 2 and 2 x 1 cost 11-13.
-#ifndef GRANQ_M_V_F32
-#define GRANQ_M_V_F32 2
-#endif
-#ifndef GRANQ_M_ROWS_F32
-#define GRANQ_M_ROWS_F32 1
-#endif
-#ifndef GRANQ_M_V_BF16
-#define GRANQ_M_V_BF16 1
-#endif
-#ifndef GRANQ_M_ROWS_BF16
-#define GRANQ_M_ROWS_BF16 2
 #endif
 __device__ inline void store_mask_byte(uint8_t *p, uint8_t v) {
 #if GRANQ_MASK_NT
@@ -892,7 +788,7 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
         }
         return;
     }
-    const int64_t slot = ((int64_t)p * plan.col_tiles + (int64_t)j) * kmax;
+    const int64_t slot = partial_slot(plan, p, j, 0);
     for (int i = threadIdx.x; i < kmax; i += kRBlock) {
         ws_min[slot + i] = key_float(lds_keys[i]);
         ws_max[slot + i] = key_float(lds_keys[kmax + i]);
@@ -1095,74 +991,6 @@ static bool aligned_elem(const void *p, granq_dtype_t dt) {
     return ((uintptr_t)p & (dt == GRANQ_F32 ? 3u : 1u)) == 0;
 }
 
-static int vec_of(granq_dtype_t dt) { return dt == GRANQ_F32 ? F32::VEC : Pack16::VEC; }
-
-static int64_t tensor_bytes(const granq_desc_t *d) {
-    return d->n * d->c * d->h * d->w * (d->dtype == GRANQ_F32 ? 4 : 2);
-}
-
-// Rows [0, nt_row_end) of a large tensor are streamed, the last GRANQ_KEEP_BYTES stay cached.
-static void split_large(ColPlan &p, const granq_desc_t *d) {
-    p.nt_row_end = 0;
-    if (!p.ok || tensor_bytes(d) < GRANQ_STREAM_BYTES) return;
-    const int64_t row_bytes = tensor_bytes(d) / p.rows;
-    const int64_t keep_rows = GRANQ_KEEP_BYTES / row_bytes;
-    p.nt_row_end = p.rows > keep_rows ? p.rows - keep_rows : 0;
-}
-
-// Plans of the element-wise kernels: rows per block = rows in flight per lane.
-static ColPlan fwd_plan(const granq_desc_t *d) {
-    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                              d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kEBlock,
-                              (int64_t)1 << 40, GRANQ_F_ROWS);
-    split_large(p, d);
-    return p;
-}
-static ColPlan fwd_mask_plan(const granq_desc_t *d) {
-    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                              d->dtype == GRANQ_F32 ? GRANQ_M_V_F32 : GRANQ_M_V_BF16, kEBlock,
-                              (int64_t)1 << 40,
-                              d->dtype == GRANQ_F32 ? GRANQ_M_ROWS_F32 : GRANQ_M_ROWS_BF16);
-    split_large(p, d);
-    return p;
-}
-static ColPlan bwd_plan(const granq_desc_t *d) {
-    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype),
-                              d->dtype == GRANQ_F32 ? GRANQ_E_V_F32 : GRANQ_E_V_BF16, kEBlock,
-                              (int64_t)1 << 40, GRANQ_B_ROWS);
-    p.nt_row_end = (p.ok && tensor_bytes(d) >= GRANQ_BWD_STREAM_BYTES) ? p.rows : 0;
-    return p;
-}
-
-// Plan of the reduction; it also fixes the workspace layout.  Blocks of GRANQ_R_MIN_ROWS rows
-// (few partials, cheap epilogue) where that still gives the chip GRANQ_R_WANT_BLOCKS blocks
-// (eight per compute unit); smaller tensors get half as many rows per block.
-#ifndef GRANQ_R_WANT_BLOCKS
-#define GRANQ_R_WANT_BLOCKS 2048
-#endif
-static ColPlan range_plan(const granq_desc_t *d) {
-    const int v = d->dtype == GRANQ_F32 ? GRANQ_R_V_F32 : GRANQ_R_V_BF16;
-    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), v, kRBlock,
-                              GRANQ_R_TARGET_BLOCKS, GRANQ_R_MIN_ROWS);
-    // (a tensor of at most 2 * GRANQ_R_MIN_ROWS rows keeps its single or two row groups: with one
-    // group and whole channels per column tile the first pass is the whole reduction)
-    if (p.ok && GRANQ_R_MIN_ROWS > 1 && p.rows > 2 * GRANQ_R_MIN_ROWS &&
-        (int64_t)p.col_tiles * p.row_groups < GRANQ_R_WANT_BLOCKS)
-        p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), v, kRBlock,
-                          GRANQ_R_TARGET_BLOCKS, (GRANQ_R_MIN_ROWS + 1) / 2);
-    split_large(p, d);
-    return p;
-}
-
-// Channels per column tile if the first pass alone produces final ranges (one row group, and
-// no channel shared between column tiles), else 0.
-static int32_t direct_channels(const ColPlan &p) {
-    if (!p.ok || p.row_groups != 1) return 0;
-    if (p.col_tiles == 1) return p.channels;
-    if (p.channels > 1 && p.span % p.hw == 0) return (int32_t)(p.span / p.hw);
-    return 0;
-}
-
 // Grid of the row kernels: enough wavefronts to fill the chip, no more than slabs.
 static uint32_t row_grid(int64_t slabs) {
     int64_t blocks = ceil_div(slabs, kBlock / kWave);
@@ -1269,18 +1097,6 @@ static void launch_fwd_finish(const ColPlan &pl, const void *x, void *x_hat, voi
     else launch_fwd_finish_mode<T, V, kEach>(pl, x, x_hat, extra, kind, qmax, fa, st);
 }
 
-static size_t col_ws_floats(const ColPlan &pl) {
-    return (size_t)pl.row_groups * pl.col_tiles * pl.kmax;
-}
-
-// Column path: partial minima, partial maxima, then one 8-byte hand-over slot per channel.
-static size_t col_params_offset(const ColPlan &pl) {
-    return (2 * col_ws_floats(pl) * sizeof(float) + 7) & ~(size_t)7;
-}
-static size_t col_ws_bytes(const ColPlan &pl) {
-    return col_params_offset(pl) + (size_t)pl.channels * sizeof(uint64_t);
-}
-
 // Argument checks of the forward; scale / zero_point may be vectors it will be given later.
 static granq_status_t fwd_check(const void *x, const granq_desc_t *desc, const float *scale,
                                 const float *zero_point, int bits, const void *x_hat,
@@ -1302,11 +1118,6 @@ static bool fwd_cols_ok(const ColPlan &cp, const granq_desc_t *desc, const void 
                         const uint8_t *codes_or_null) {
     const bool codes_ok = !codes_or_null || ((uintptr_t)codes_or_null % (size_t)vec_of(desc->dtype)) == 0;
     return cp.ok && aligned16(x) && (!x_hat || aligned16(x_hat)) && codes_ok;
-}
-
-// Partials per channel: row groups x the column tiles a channel can overlap.
-static int64_t partials_per_channel(const ColPlan &pl) {
-    return (int64_t)pl.row_groups * ((pl.hw - 1) / pl.span + 2);
 }
 
 }  // namespace granq
@@ -1515,11 +1326,6 @@ static int32_t spin_limit() {
         return (int32_t)(v < 0 ? 0 : (v > (1 << 24) ? (1 << 24) : v));
     }
     return 20000;
-}
-
-// Channels per finisher block of the finishing forward, and the rows of blocks they take.
-static int64_t finisher_rows_of(const ColPlan &cp, const ColPlan &fp) {
-    return ceil_div(ceil_div(cp.channels, kEBlock / kWave), fp.col_tiles);
 }
 
 bool two_launches_apply(const void *x, const granq_desc_t *desc, const void *x_hat,

@@ -115,6 +115,66 @@ GRANQ_PLAN_HD inline uint32_t true_column(uint32_t col, const ColPlan &p) {
     return col - fastdiv(col, p.true_len_div) * p.true_len_div.d;
 }
 
+// How the elements of one 16-byte vector map to channels (template parameter MODE):
+//   kOne   H*W is a multiple of the vector width: the whole vector is one channel
+//   kTwo   H*W >= vector width: at most two channels, elements [0, split) and [split, VEC)
+//   kEach  H*W < vector width: every element may have its own channel
+constexpr int kOne = 0, kTwo = 1, kEach = 2;
+template <int MODE, int VEC>
+struct Slots { static constexpr int N = MODE == kOne ? 1 : (MODE == kTwo ? 2 : VEC); };
+
+// Channels of this lane's vector starting at column `col`: ch[] per slot, and the
+// number of leading elements that belong to the first channel.
+template <int MODE, int VEC, int NS>
+GRANQ_PLAN_HD inline uint32_t vector_channels(uint32_t col, const ColPlan &plan, int32_t (&ch)[NS]) {
+    const uint32_t c0 = fastdiv(col, plan.hw_div);
+    const uint32_t rem = col - c0 * plan.hw_div.d;
+    if (MODE == kEach) {
+        uint32_t c = c0, r = rem;
+        ch[0] = (int32_t)c;
+        for (int e = 1; e < NS; ++e) {
+            r += 1;
+            if (r == plan.hw_div.d) { r = 0; c += 1; }
+            ch[e] = (int32_t)c;
+        }
+        return VEC;
+    }
+    ch[0] = (int32_t)c0;
+    if (MODE == kOne) return VEC;
+    const uint32_t left = plan.hw_div.d - rem;           // elements of channel c0 from col on
+    const uint32_t split = left < (uint32_t)VEC ? left : (uint32_t)VEC;
+    ch[NS > 1 ? 1 : 0] = (int32_t)(split < (uint32_t)VEC ? c0 + 1 : c0);
+    return split;
+}
+
+
+// The first pass of the reduction leaves one partial min / max per (row group p, column tile
+// j, channel slot k), k = channel - first channel of tile j, at this index of the workspace.
+GRANQ_PLAN_HD inline int64_t partial_slot(const ColPlan &plan, int64_t p, int64_t j, int64_t k) {
+    return (p * plan.col_tiles + j) * plan.kmax + k;
+}
+
+// The partials of channel c: those of all row groups and of the column tiles j_lo .. j_lo + nj - 1
+// that overlap the channel, `total` in all; item i of them sits at channel_partial_slot().
+struct ChannelPartials {
+    uint32_t j_lo, nj, total;                  // total < 2^31: tiles x 65535 row groups at most
+};
+GRANQ_PLAN_HD inline ChannelPartials channel_partials(const ColPlan &plan, int64_t c) {
+    ChannelPartials cp;
+    cp.j_lo = (uint32_t)((c * plan.hw) / plan.span);
+    const uint32_t j_hi = (uint32_t)(((c + 1) * plan.hw - 1) / plan.span);
+    cp.nj = j_hi - cp.j_lo + 1;
+    cp.total = cp.nj * (uint32_t)plan.row_groups;
+    return cp;
+}
+GRANQ_PLAN_HD inline int64_t channel_partial_slot(const ColPlan &plan, int64_t c, const ChannelPartials &cp,
+                                                  uint32_t i) {
+    const uint32_t pp = i / cp.nj;
+    const uint32_t jj = cp.j_lo + (i - pp * cp.nj);
+    const int64_t k = c - ((int64_t)jj * plan.span) / plan.hw;
+    return partial_slot(plan, pp, jj, k);
+}
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // vec = elements per 16 bytes, v = vectors per lane and row, block = threads.
