@@ -848,8 +848,8 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass2(
 // element-wise fallbacks ("row" kernels): any shape, any element alignment
 // ---------------------------------------------------------------------------
 
-// Block (c, p): channel c, rows [p*rpg, (p+1)*rpg).  Per-lane min/max, DPP
-// within the wavefront, LDS across the four wavefronts, one partial per block.
+// Block (c, p, q): channel c, rows [p*rpg, (p+1)*rpg), piece q of every slab.  Per-lane
+// min/max, DPP within the wavefront, LDS across the four wavefronts, one partial per block.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void range_rows_pass1(
     const void *__restrict__ x, float *__restrict__ ws_min, float *__restrict__ ws_max,
@@ -857,13 +857,16 @@ __global__ __launch_bounds__(kBlock) void range_rows_pass1(
 {
     __shared__ float part[2][kBlock / kWave];
     const int64_t ic = blockIdx.x % c;
-    const int64_t p = blockIdx.x / c;
+    const int64_t pq = blockIdx.x / c;                 // (row group, piece), piece fastest
+    const int64_t p = pq / plan.chunks, q = pq % plan.chunks;
     const int64_t r0 = p * plan.rows_per_group;
     const int64_t r1 = (r0 + plan.rows_per_group < n) ? r0 + plan.rows_per_group : n;
+    const int64_t k0 = q * plan.chunk_len;
+    const int64_t k1 = k0 + plan.chunk_len < hw ? k0 + plan.chunk_len : hw;
     float mn = __builtin_inff(), mx = -__builtin_inff();
     for (int64_t in = r0; in < r1; ++in) {
         const int64_t base = (in * c + ic) * hw;
-        for (int64_t k = threadIdx.x; k < hw; k += kBlock) {
+        for (int64_t k = k0 + threadIdx.x; k < k1; k += kBlock) {
             float v = T::load1(x, base + k);
             mn = __builtin_fminf(mn, v);
             mx = __builtin_fmaxf(mx, v);
@@ -882,11 +885,12 @@ __global__ __launch_bounds__(kBlock) void range_rows_pass1(
             mn = __builtin_fminf(mn, part[0][w]);
             mx = __builtin_fmaxf(mx, part[1][w]);
         }
-        ws_min[p * c + ic] = mn;
-        ws_max[p * c + ic] = mx;
+        ws_min[pq * c + ic] = mn;
+        ws_max[pq * c + ic] = mx;
     }
 }
 
+// `groups`: partials per channel (row groups x pieces).
 __global__ __launch_bounds__(kBlock) void range_rows_pass2(
     const float *__restrict__ ws_min, const float *__restrict__ ws_max,
     float *__restrict__ ch_min, float *__restrict__ ch_max, int64_t c, int32_t groups,
@@ -909,25 +913,27 @@ __global__ __launch_bounds__(kBlock) void range_rows_pass2(
     }
 }
 
-// One wavefront per (n,c) slab at a time; scale and zero-point are
-// wave-uniform.  `slabs` = N*C.
+// One wavefront per piece of an (n,c) slab at a time; scale and zero-point are
+// wave-uniform.  `slabs` = N*C; a slab of hw elements has `chunks` pieces of chunk_len.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fq_fwd_rows(
     const void *x, void *x_hat, uint8_t *__restrict__ codes,
     const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax,
-    int64_t slabs, int64_t c, int64_t hw)
+    int64_t slabs, int64_t c, int64_t hw, int32_t chunks, int64_t chunk_len)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t wave0 = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     const int64_t nwaves = (int64_t)gridDim.x * (kBlock / kWave);
-    for (int64_t slab = wave0; slab < slabs; slab += nwaves) {
+    for (int64_t item = wave0; item < slabs * chunks; item += nwaves) {
+        const int64_t slab = item / chunks, q = item % chunks;
         const int64_t ic = slab % c;
         const float s = scale[ic], z = zero_point[ic];
         const int64_t base = slab * hw;
-        for (int64_t k = lane; k < hw; k += kWave) {
-            float q = clamp_code(raw_code(T::load1(x, base + k), s, z), qmax);
-            if (x_hat) T::store1(x_hat, base + k, dequant(q, s, z));
-            if (codes) codes[base + k] = (uint8_t)q;
+        const int64_t k1 = (q + 1) * chunk_len < hw ? (q + 1) * chunk_len : hw;
+        for (int64_t k = q * chunk_len + lane; k < k1; k += kWave) {
+            float qv = clamp_code(raw_code(T::load1(x, base + k), s, z), qmax);
+            if (x_hat) T::store1(x_hat, base + k, dequant(qv, s, z));
+            if (codes) codes[base + k] = (uint8_t)qv;
         }
     }
 }
@@ -936,16 +942,18 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void fq_bwd_rows(
     const void *x, const void *dy, void *dx,
     const float *__restrict__ scale, const float *__restrict__ zero_point, float qmax,
-    int64_t slabs, int64_t c, int64_t hw)
+    int64_t slabs, int64_t c, int64_t hw, int32_t chunks, int64_t chunk_len)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t wave0 = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     const int64_t nwaves = (int64_t)gridDim.x * (kBlock / kWave);
-    for (int64_t slab = wave0; slab < slabs; slab += nwaves) {
+    for (int64_t item = wave0; item < slabs * chunks; item += nwaves) {
+        const int64_t slab = item / chunks, q = item % chunks;
         const int64_t ic = slab % c;
         const float s = scale[ic], z = zero_point[ic];
         const int64_t base = slab * hw;
-        for (int64_t k = lane; k < hw; k += kWave) {
+        const int64_t k1 = (q + 1) * chunk_len < hw ? (q + 1) * chunk_len : hw;
+        for (int64_t k = q * chunk_len + lane; k < k1; k += kWave) {
             bool keep = in_range(raw_code(T::load1(x, base + k), s, z), qmax);
             T::store_gated1(dx, dy, base + k, keep);
         }
@@ -1145,7 +1153,7 @@ granq_status_t granq_workspace_bytes(const granq_desc_t *desc, size_t *bytes_out
     if (st != GRANQ_OK) return st;
     const int64_t hw = desc->h * desc->w;
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);
-    size_t bytes = 2 * (size_t)rp.row_groups * (size_t)desc->c * sizeof(float);
+    size_t bytes = 2 * (size_t)rp.row_groups * (size_t)rp.chunks * (size_t)desc->c * sizeof(float);
     ColPlan cp = range_plan(desc);
     if (cp.ok && col_ws_bytes(cp) > bytes) bytes = col_ws_bytes(cp);
     *bytes_out = bytes;
@@ -1238,10 +1246,11 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
         return launched();
     }
     RowPlan rp = make_row_plan(desc->n, desc->c, hw);
-    const size_t floats = (size_t)rp.row_groups * (size_t)desc->c;
+    const int64_t per_channel = (int64_t)rp.row_groups * rp.chunks;
+    const size_t floats = (size_t)per_channel * (size_t)desc->c;
     float *ws_min = (float *)workspace;
     float *ws_max = ws_min + floats;
-    dim3 grid((uint32_t)(desc->c * rp.row_groups)), block(kBlock);
+    dim3 grid((uint32_t)(desc->c * per_channel)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
         launch_kernel(range_rows_pass1<F32>, grid, block, 0, hs, x, ws_min, ws_max, desc->n, desc->c, hw, rp);
     else if (desc->dtype == GRANQ_BF16)
@@ -1251,7 +1260,7 @@ static granq_status_t range_impl(const void *x, const granq_desc_t *desc, float 
     st = launched();
     if (st != GRANQ_OK) return st;
     dim3 grid2((uint32_t)ceil_div(desc->c, kBlock));
-    launch_kernel(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, rp.row_groups,
+    launch_kernel(range_rows_pass2, grid2, block, 0, hs, ws_min, ws_max, ch_min, ch_max, desc->c, (int32_t)per_channel,
                        qmax, scale, zero_point);
     return launched();
 }
@@ -1420,13 +1429,14 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
     }
     const int64_t hw = desc->h * desc->w;
     const int64_t slabs = desc->n * desc->c;
-    dim3 grid(row_grid(slabs)), block(kBlock);
+    const RowPlan rp = make_row_plan(desc->n, desc->c, hw);
+    dim3 grid(row_grid(slabs * rp.chunks)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        launch_kernel(fq_fwd_rows<F32>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_fwd_rows<F32>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     else if (desc->dtype == GRANQ_BF16)
-        launch_kernel(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     else
-        launch_kernel(fq_fwd_rows<F16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_fwd_rows<F16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     return launched();
 }
 
@@ -1451,13 +1461,14 @@ granq_status_t granq_fakequant_bwd(const void *x, const void *dy, const granq_de
     }
     const int64_t hw = desc->h * desc->w;
     const int64_t slabs = desc->n * desc->c;
-    dim3 grid(row_grid(slabs)), block(kBlock);
+    const RowPlan rp = make_row_plan(desc->n, desc->c, hw);
+    dim3 grid(row_grid(slabs * rp.chunks)), block(kBlock);
     if (desc->dtype == GRANQ_F32)
-        launch_kernel(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_bwd_rows<F32>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     else if (desc->dtype == GRANQ_BF16)
-        launch_kernel(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_bwd_rows<BF16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     else
-        launch_kernel(fq_bwd_rows<F16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw);
+        launch_kernel(fq_bwd_rows<F16>, grid, block, 0, hs, x, dy, dx, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     return launched();
 }
 

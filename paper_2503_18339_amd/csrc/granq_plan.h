@@ -233,10 +233,14 @@ inline ColPlan make_col_plan(int64_t n, int64_t c, int64_t hw, int vec, int v, i
     return p;
 }
 
-// Fallback ("row") plan: one channel per block, P groups of rows.
+// Fallback ("row") plan: one channel per block, P groups of rows; where the rows alone do not
+// give a channel its share of blocks (few samples, long slabs: the layer-wise view is one
+// slab), every slab of H*W elements is also cut into `chunks` pieces of `chunk_len` elements.
 struct RowPlan {
     int32_t row_groups;
     int32_t rows_per_group;
+    int32_t chunks;
+    int64_t chunk_len;
 };
 
 inline RowPlan make_row_plan(int64_t n, int64_t c, int64_t hw) {
@@ -249,6 +253,12 @@ inline RowPlan make_row_plan(int64_t n, int64_t c, int64_t hw) {
     if (groups < 1) groups = 1;
     p.rows_per_group = (int32_t)ceil_div(n, groups);
     p.row_groups = (int32_t)ceil_div(n, p.rows_per_group);
+    int64_t chunks = ceil_div(want, p.row_groups);
+    const int64_t most_chunks = hw / 4096 > 0 ? hw / 4096 : 1;
+    if (chunks > most_chunks) chunks = most_chunks;
+    if (chunks > 32768) chunks = 32768;
+    p.chunk_len = ceil_div(hw, chunks);
+    p.chunks = (int32_t)ceil_div(hw, p.chunk_len);
     return p;
 }
 

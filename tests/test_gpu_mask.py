@@ -94,19 +94,27 @@ def test_mask_pair_full_size(idx, dtype):
     q = G.ActivationQuantizer(shape, x.dtype, 4, DEV)
     q.calibrate(x)
     x_hat, mask, dx = _run_mask_pair(x, dy, q.scale, q.zero_point, 4)
-    # against the x-based pair of the library (which the workload tests check against the oracle)
-    ref_hat = torch.empty_like(x)
-    ref_dx = torch.empty_like(x)
-    q.forward(x, ref_hat, recalibrate=False)
-    q.backward(x, dy, ref_dx)
-    torch.cuda.synchronize()
-    assert np.array_equal(bits_view(x_hat), bits_view(to_numpy(ref_hat)))
-    assert np.array_equal(bits_view(dx), bits_view(to_numpy(ref_dx)))
-    # and the bits themselves against the oracle on a slice of the batch
-    sl = slice(0, 8)
-    x_np = to_numpy(x[sl])
-    want = oracle.gate_mask(x_np, q.scale.cpu().numpy(), q.zero_point.cpu().numpy(), 4)
-    assert np.array_equal(mask[:want.size], want)
+    # every element of every output against the oracle (its element-wise passes split over the
+    # batch across host threads; a sample holds a whole number of mask bytes)
+    from concurrent.futures import ThreadPoolExecutor
+    from parity import oracle_bwd, oracle_fwd, values
+    s_np, z_np = q.scale.cpu().numpy(), q.zero_point.cpu().numpy()
+    x_np, dy_np = to_numpy(x), to_numpy(dy)
+    mn, mx = oracle.range_reduce(x_np)
+    ws, wz = oracle.prescale(mn, mx, 4)
+    assert np.array_equal(bits_view(s_np), bits_view(ws)) and np.array_equal(bits_view(z_np), bits_view(wz))
+    want_hat, _ = oracle_fwd(x_np, s_np, z_np, 4)
+    assert np.array_equal(values(x_hat), values(want_hat))
+    del want_hat
+    want_dx = oracle_bwd(x_np, dy_np, s_np, z_np, 4)
+    assert np.array_equal(bits_view(dx), bits_view(want_dx))
+    del want_dx
+    per_sample = x_np[0].size
+    assert per_sample % 8 == 0
+    cuts = [(i, min(shape[0], i + 16)) for i in range(0, shape[0], 16)]
+    with ThreadPoolExecutor(8) as ex:
+        parts = list(ex.map(lambda ab: oracle.gate_mask(x_np[ab[0]:ab[1]], s_np, z_np, 4), cuts))
+    assert np.array_equal(mask, np.concatenate(parts)), "gate bits differ from the oracle's"
 
 
 def test_mask_argument_checks():

@@ -263,6 +263,17 @@ def test_one_call_forward_in_two_launches(shape, dtype, spin_limit, monkeypatch)
         assert torch.equal(xh2.view(ib), xh.view(ib))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 10_000_001), (2, 3, 1, 1_000_003), (1, 5, 3, 333_337)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_long_slabs_without_vector_structure(shape, dtype):
+    """Element-wise kernels on slabs of millions of elements (a layer-wise view of odd size, a
+    few long channels): the slabs are cut into pieces so that every compute unit gets work;
+    results as everywhere."""
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), seed=31, device=DEV, dtype=dtype)
+    _check(x, 4, 31, what="long slabs %s" % (shape,))
+
+
 def test_misaligned_pointers_take_the_elementwise_path():
     """A tensor that starts 4 bytes into an allocation: same results, no fault."""
     for dtype in (torch.float32, torch.bfloat16, torch.float16):

@@ -79,3 +79,32 @@ def test_channels_last_view_full_size(dtype):
                             (0.05, 20.0), (4,), (dtype,))
     got = _run(wl, wl.acts[0], 4, dtype, seed=3)
     assert np.any(got["zero_point"] != 0)
+
+
+def test_config5_pass_back_to_back_on_one_stream():
+    """The ResNet-50 pass as the benchmark issues it -- all 49 forwards (ranges, parameters and
+    forward in one call each) in network order, then all 49 backwards in reverse order, one
+    stream, no host synchronisation in between -- at batch 16, every tensor checked afterwards."""
+    wl = CFG5
+    batch = 16
+    st = torch.cuda.Stream()
+    layers = []
+    for i, a in enumerate(wl.tensors()):
+        shape = a.shape(batch)
+        x = workloads.make_activation(shape, a.law, wl.sigma, i, DEV)
+        dy = workloads.make_grad(shape, i, DEV)
+        layers.append((x, dy, torch.empty_like(x), torch.empty_like(x), G.ActivationQuantizer(shape, x.dtype, 3, DEV)))
+    assert len(layers) == 49
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        for rep in range(2):                               # the second pass reuses every workspace
+            for x, dy, xh, dx, q in layers:
+                q.forward(x, xh, None, st)
+            for x, dy, xh, dx, q in reversed(layers):
+                q.backward(x, dy, dx, st)
+    st.synchronize()
+    for i, (x, dy, xh, dx, q) in enumerate(layers):
+        got = {"min": q.ch_min.cpu().numpy(), "max": q.ch_max.cpu().numpy(), "scale": q.scale.cpu().numpy(),
+               "zero_point": q.zero_point.cpu().numpy(), "xhat": to_numpy(xh), "dx": to_numpy(dx)}
+        want = oracle_path(to_numpy(x), 3, to_numpy(dy))
+        assert_parity(got, want, "ResNet-50 pass, tensor %d %s" % (i, tuple(x.shape)))
