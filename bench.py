@@ -303,6 +303,31 @@ def channels_last_view(bits, device):
             "same_tensor_nchw_us": "see per_kernel, layer1 256x64x56x56"}
 
 
+def single_launch_form(bits, device):
+    """Ranges, parameters and forward in ONE launch with the tensor resident in registers
+    (granq_calibrate_fakequant_fwd_resident) against granq_calibrate_fakequant_fwd (one block per
+    channel, or two launches) on tensors that take both: device time per call, relaunched on the
+    same buffers."""
+    stream = torch.cuda.current_stream()
+    rows = []
+    for shape in ((256, 16, 32, 32), (256, 32, 16, 16), (256, 64, 8, 8), (256, 512, 7, 7), (256, 256, 14, 14)):
+        x = workloads.make_activation(shape, "relu", (0.05, 20.0), 0, device)
+        xh = torch.empty_like(x)
+        q = G.ActivationQuantizer(shape, torch.float32, bits, device)
+        qs = G.ActivationQuantizer(shape, torch.float32, bits, device, single_launch=True)
+        assert qs.state is not None
+        t_one = _timeit(lambda: q.forward(x, xh, None, stream), 20)
+        t_res = _timeit(lambda: qs.forward(x, xh, None, stream), 20)
+        rows.append({"tensor": "x".join(map(str, shape)), "MB": round(x.numel() * 4 / 1e6, 1),
+                     "one_call_launches": int(G.granq_plan_describe(q.desc)["one_call_launches"]),
+                     "one_call_us": round(t_one, 2), "single_launch_resident_us": round(t_res, 2)})
+        del x, xh
+    return {"rows": rows,
+            "note": "the resident form reads x once and has no kernel boundary inside, but its blocks meet "
+                    "through device-scope atomics and loads (arrival counters, partials, parameter slots), "
+                    "each a round trip to memory on this multi-die chip"}
+
+
 def gate_bit_variant(wl, dtype, bits, device, steps, warmup):
     """The same step with the forward emitting one gate bit per element and the backward reading
     dy + bits instead of x + dy (granq_fakequant_fwd_mask / granq_fakequant_bwd_mask)."""
@@ -560,6 +585,8 @@ def main():
                     help="config3 = ResNet-18 ImageNet set (the metric's workload, default); the others "
                          "(ResNet-20 CIFAR, MobileNetV2, ResNet-50 sets) are timed without the extras")
     ap.add_argument("--no-extras", action="store_true", help="skip breakdown and other dtypes")
+    ap.add_argument("--section", choices=["gate_bits", "conv", "distortion", "weights", "channels_last", "comparison", "single_launch"],
+                    help="run ONE of the extra sections alone (for a profiler) and print it as JSON")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain device copy of known size (torch copy_ of the largest "
                          "tensor, 3 launches) so that a counter run has a reference kernel")
@@ -576,6 +603,18 @@ def main():
 
     device = "cuda"
     wl = workloads.WORKLOADS[args.workload]()
+    if args.section:
+        bits = args.bits or 4
+        dtype = workloads.torch_dtype(args.dtype)
+        run = {"gate_bits": lambda: gate_bit_variant(wl, dtype, bits, device, min(args.steps, 50), 5),
+               "conv": lambda: integer_accumulation(wl, bits, device),
+               "distortion": lambda: distortion_table(wl, device),
+               "weights": lambda: weight_quantization(bits, device),
+               "channels_last": lambda: channels_last_view(bits, device),
+               "comparison": lambda: comparison_points(wl, bits, device),
+               "single_launch": lambda: single_launch_form(bits, device)}[args.section]
+        print(json.dumps({"section": args.section, "dtype": args.dtype, "result": run()}))
+        return
     if args.bits is None:
         args.bits = 4 if args.workload == "config3" else wl.bits[0]
     variants_only = args.workload != "config3" and not args.no_extras
@@ -707,6 +746,7 @@ def main():
         extra["distortion_3bit"] = distortion_table(wl, device)
         extra["resnet18_weights_channelwise"] = weight_quantization(args.bits, device)
         extra["channels_last_view_256x56x56x64"] = channels_last_view(args.bits, device)
+        extra["single_launch_form"] = single_launch_form(args.bits, device)
         extra["gate_bit_variant"] = gate_bit_variant(wl, dtype, args.bits, device, args.steps, args.warmup)
         extra["gate_bit_variant"]["speedup_vs_x_based_step"] = round(
             ms_per_step / extra["gate_bit_variant"]["ms_per_step"], 3)

@@ -177,14 +177,54 @@ granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits
  * separate calls; arguments, workspace and errors as for them (x_hat or codes may
  * be NULL, not both).  A tensor whose channel holds at most 128 KB (n*h*w
  * elements: the regime of the paper's own latency table, batch 16 on CIFAR-size
- * maps) is handled in ONE launch, a block per channel; larger tensors take the
- * three launches of the two calls.
+ * maps) is handled in ONE launch, a block per channel; larger tensors on the 16-byte
+ * vector path take TWO: the first pass of the reduction, then the forward, whose leading
+ * blocks finish the reduction (second pass, Eq. 5), write the four vectors and hand scale
+ * and zero-point to the other blocks through the workspace (a block that finds them pending
+ * fetches its rows, then polls; after GRANQ_SPIN_LIMIT polls -- environment, default 20000,
+ * tests set 0 -- it derives them from the partials itself, so no block depends on another
+ * one being scheduled); anything else takes the three launches of the two calls.
  */
 granq_status_t granq_calibrate_fakequant_fwd(const void *x, const granq_desc_t *desc, int bits,
                                              float *ch_min, float *ch_max,
                                              float *scale, float *zero_point,
                                              void *x_hat, uint8_t *codes_or_null,
                                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same three steps (Eq. 4, 5, 1, 6: Alg. 1 up to the accumulation) in ONE launch for
+ * tensors of up to 64 MB: every block keeps its slice of x in registers from the min / max
+ * sweep to the quantization, so x is read once (20 instead of 24 bytes per float32 element
+ * and training step) and no kernel boundary separates the steps.  Blocks hand partial ranges
+ * and the finished scale / zero-point to each other through `state`.  Outputs are
+ * bit-identical to granq_calibrate_fakequant_fwd.
+ *
+ * state  [in/out] device, granq_resident_state_bytes(desc) bytes, 16-byte aligned.  It must be
+ *        ZERO before its first use (granq_resident_state_init enqueues a fill kernel, safe to
+ *        capture; hipMemset works too) and then belongs to this descriptor: every completed
+ *        call leaves it ready for the next call with the same descriptor.  Two calls that
+ *        overlap in time must not share a state.  After a failed or aborted launch zero it again.
+ * x_hat  must not be x (a block that stops waiting for the others re-reads x; see below).
+ *
+ * GRANQ_ERR_UNSUPPORTED, with nothing launched, for a tensor this form does not take: larger
+ * than 64 MB, rows that are no whole number of 16-byte vectors, pointers not 16-byte aligned,
+ * x_hat == x, or a grid that would not fit the GPU at once -- use granq_calibrate_fakequant_fwd
+ * then.  granq_resident_state_bytes (host-only) returns the same code for such a descriptor.
+ *
+ * No block depends on another one being scheduled: a wavefront waits for its channels'
+ * parameters for a bounded number of polls (GRANQ_SPIN_LIMIT in the environment, default
+ * 20000, about a microsecond each; tests set 0) and then computes the channels' ranges from x
+ * itself, with the same result.
+ */
+granq_status_t granq_resident_state_bytes(const granq_desc_t *desc, size_t *bytes_out);
+
+granq_status_t granq_resident_state_init(void *state, size_t state_bytes, void *stream);
+
+granq_status_t granq_calibrate_fakequant_fwd_resident(const void *x, const granq_desc_t *desc, int bits,
+                                                      float *ch_min, float *ch_max,
+                                                      float *scale, float *zero_point,
+                                                      void *x_hat, uint8_t *codes_or_null,
+                                                      void *state, size_t state_bytes, void *stream);
 
 /*
  * Quantize, clamp, dequantize (Eq. 1, then the dequantization of Eq. 6; Alg. 1's
@@ -296,8 +336,8 @@ granq_status_t granq_rowwise_fakequant_bwd_multi(const granq_rowq_bwd_item_t *it
  * x_hat is never materialised).  Products and differences are formed and summed
  * in binary64.
  * ch_sums  [out] device, C*4 doubles: per channel  sum x*q, sum x^2, sum q^2, sum (x-q)^2
- * layer    [out] device, 6 doubles: the four sums over all channels (added in
- *                channel order), then cosine similarity and relative error of the
+ * layer    [out] device, 6 doubles: the four sums over all channels (added by a fixed
+ *                tree), then cosine similarity and relative error of the
  *                whole tensor (0/0 gives NaN)
  * workspace [tmp] device, granq_distortion_workspace_bytes() bytes, 16-byte aligned
  * Sums are deterministic (fixed reduction tree); they differ from a sequential

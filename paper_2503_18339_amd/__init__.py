@@ -13,6 +13,8 @@ from .binding import (granq_rowwise_fakequant_bwd_multi, granq_rowwise_fakequant
                       rowwise_items)
 from .binding import granq_calibrate, granq_calibrate_fakequant_fwd, granq_conv1x1_int8, granq_conv1x1_int8_as, granq_fold_weights
 from .binding import granq_distortion, granq_distortion_workspace_bytes
+from .binding import (granq_calibrate_fakequant_fwd_resident, granq_resident_state_bytes,
+                      granq_resident_state_init)
 from .binding import (granq_cmp_accumulate_inloop, granq_cmp_accumulate_prescaled,
                       granq_cmp_channel_loop_fwd)
 from .quantizer import ActivationQuantizer
@@ -24,6 +26,7 @@ __all__ = [
     "granq_fakequant_bwd", "load", "library_path", "status_string", "version",
     "granq_fold_weights", "granq_conv1x1_int8",
     "granq_distortion", "granq_distortion_workspace_bytes",
+    "granq_calibrate_fakequant_fwd_resident", "granq_resident_state_bytes", "granq_resident_state_init",
     "granq_rowwise_fakequant_multi", "granq_rowwise_fakequant_bwd_multi", "rowwise_items",
     "rowwise_bwd_items", "granq_mask_bytes", "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask",
     "ActivationQuantizer", "granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",

@@ -28,7 +28,8 @@ GRANQ_F16 = 2
 
 EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "granq_plan_describe",
            "granq_range_reduce", "granq_range_reduce_noalloc",
-           "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
+           "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_resident_state_bytes", "granq_resident_state_init",
+           "granq_calibrate_fakequant_fwd_resident", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
            "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
            "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_as")
@@ -88,6 +89,10 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_calibrate.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_calibrate_fakequant_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                                   ctypes.c_size_t, _vp]
+    lib.granq_resident_state_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.granq_resident_state_init.argtypes = [_vp, ctypes.c_size_t, _vp]
+    lib.granq_calibrate_fakequant_fwd_resident.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                                           ctypes.c_size_t, _vp]
     lib.granq_fakequant_fwd.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_fakequant_bwd.argtypes = [_vp, _vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp]
     lib.granq_mask_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
@@ -260,6 +265,47 @@ def granq_calibrate_fakequant_fwd(x: torch.Tensor, bits: int, ch_min: torch.Tens
         _dev(x_hat, "x_hat") if x_hat is not None else 0, _dev(codes, "codes") if codes is not None else 0,
         _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream(stream)),
         "granq_calibrate_fakequant_fwd")
+
+
+def granq_resident_state_bytes(desc: granq_desc_t) -> int:
+    """Bytes of state the single-launch forward needs; 0 if it does not take this descriptor."""
+    out = ctypes.c_size_t(0)
+    st = load().granq_resident_state_bytes(ctypes.byref(desc), ctypes.byref(out))
+    if st == GRANQ_ERR_UNSUPPORTED:
+        return 0
+    _check(st, "granq_resident_state_bytes")
+    return int(out.value)
+
+
+def granq_resident_state_init(state: torch.Tensor, stream=None) -> None:
+    _check(load().granq_resident_state_init(_dev(state, "state"), state.numel() * state.element_size(),
+                                            _stream(stream)), "granq_resident_state_init")
+
+
+def granq_calibrate_fakequant_fwd_resident(x: torch.Tensor, bits: int, ch_min: torch.Tensor, ch_max: torch.Tensor,
+                                           scale: torch.Tensor, zero_point: torch.Tensor,
+                                           x_hat: Optional[torch.Tensor], codes: Optional[torch.Tensor],
+                                           state: torch.Tensor, stream=None,
+                                           desc: Optional[granq_desc_t] = None) -> bool:
+    """Ranges, parameters and forward in one launch.  Returns False, with nothing launched, when
+    the library does not take this tensor in that form (the caller then uses
+    granq_calibrate_fakequant_fwd)."""
+    d = _desc_for(x, desc)
+    if x_hat is None and codes is None:
+        raise ValueError("x_hat and codes are both None: nothing to write")
+    if x_hat is not None and (x_hat.dtype != x.dtype or x_hat.numel() != x.numel()):
+        raise ValueError("x_hat must match x")
+    if codes is not None and (codes.dtype != torch.uint8 or codes.numel() != x.numel()):
+        raise ValueError("codes must be uint8 with one entry per element")
+    st = load().granq_calibrate_fakequant_fwd_resident(
+        _dev(x, "x"), ctypes.byref(d), int(bits), _vec(ch_min, d.c, "ch_min"), _vec(ch_max, d.c, "ch_max"),
+        _vec(scale, d.c, "scale"), _vec(zero_point, d.c, "zero_point"),
+        _dev(x_hat, "x_hat") if x_hat is not None else 0, _dev(codes, "codes") if codes is not None else 0,
+        _dev(state, "state"), state.numel() * state.element_size(), _stream(stream))
+    if st == GRANQ_ERR_UNSUPPORTED:
+        return False
+    _check(st, "granq_calibrate_fakequant_fwd_resident")
+    return True
 
 
 def granq_fakequant_fwd(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,

@@ -624,6 +624,82 @@ __global__ __launch_bounds__(kBlock) void bwd_mask_bytes(
 // Pass 2: one wavefront per channel gathers the partials of all column tiles
 // that overlap the channel and of all row groups.
 
+// End of a block's sweep: the lanes' running minima and maxima (one pair per element position of
+// each of their V vectors, or one per vector in mode kOne) are combined per channel in LDS:
+// keys[k] / keys[kmax + k] for channel (first channel of tile j) + k, as order-preserving
+// integer keys.  A wavefront whose lanes all hold the same channel reduces with DPP and issues
+// one LDS atomic, otherwise each lane issues its own.  The keys must have been initialised and a
+// barrier passed; the caller places the barrier that follows.
+template <typename T, int V, int MODE>
+__device__ inline void lanes_to_channel_keys(const ColPlan &plan, uint32_t j, float (&mn)[V][MODE == kOne ? 1 : T::VEC],
+                                             float (&mx)[V][MODE == kOne ? 1 : T::VEC], const uint32_t (&cv)[V],
+                                             const bool (&active)[V], uint32_t *lds_keys) {
+    constexpr int VEC = T::VEC;
+    constexpr int NS = MODE == kOne ? 1 : VEC;
+    const int32_t kmax = plan.kmax;
+    const int32_t ch_first = (int32_t)fastdiv(j * (uint32_t)plan.span, plan.hw_div);
+    constexpr int NG = Slots<MODE, VEC>::N;             // channel groups per vector
+    // glued rows whose length divides the distance between a lane's vectors: all V vectors
+    // belong to the same channels, so they are combined in registers and only the first one
+    // goes to LDS (inactive vectors hold the identities)
+    if (V > 1 && plan.v_same) {
+#pragma unroll
+        for (int v = 1; v < V; ++v)
+#pragma unroll
+            for (int e = 0; e < NS; ++e) {
+                mn[0][e] = __builtin_fminf(mn[0][e], mn[v][e]);
+                mx[0][e] = __builtin_fmaxf(mx[0][e], mx[v][e]);
+            }
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        if (v > 0 && plan.v_same) break;               // block-uniform
+        // inactive lanes hold the identities and point at the tile's first channel; with glued
+        // rows the channel follows from the column within the true row
+        const uint32_t col = true_column(active[v] ? cv[v] * VEC : j * (uint32_t)plan.span, plan);
+        int32_t ch[NG];
+        const uint32_t split = vector_channels<MODE, VEC, NG>(col, plan, ch);
+        float gmn[NG], gmx[NG];
+        if (MODE == kTwo) {
+            // fold the element positions into the (at most) two channels of the vector
+            gmn[0] = gmn[NG - 1] = __builtin_inff();
+            gmx[0] = gmx[NG - 1] = -__builtin_inff();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const bool first = (uint32_t)e < split;
+                const float a = mn[v][e < NS ? e : 0], b = mx[v][e < NS ? e : 0];
+                gmn[0] = __builtin_fminf(gmn[0], first ? a : __builtin_inff());
+                gmx[0] = __builtin_fmaxf(gmx[0], first ? b : -__builtin_inff());
+                gmn[NG - 1] = __builtin_fminf(gmn[NG - 1], first ? __builtin_inff() : a);
+                gmx[NG - 1] = __builtin_fmaxf(gmx[NG - 1], first ? -__builtin_inff() : b);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < NG; ++e) {
+                gmn[e] = mn[v][e < NS ? e : 0];
+                gmx[e] = mx[v][e < NS ? e : 0];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < NG; ++e) {
+            const int32_t k = ch[e] - ch_first;
+            const int32_t k_lead = __builtin_amdgcn_readfirstlane(k);
+            if (__all(k == k_lead)) {
+                float wmn = wave_min(gmn[e]);
+                float wmx = wave_max(gmx[e]);
+                if ((threadIdx.x & (kWave - 1)) == 0) {
+                    atomicMin(&lds_keys[k_lead], float_key(wmn));
+                    atomicMax(&lds_keys[kmax + k_lead], float_key(wmx));
+                }
+            } else {
+                atomicMin(&lds_keys[k], float_key(gmn[e]));
+                atomicMax(&lds_keys[kmax + k], float_key(gmx[e]));
+            }
+        }
+    }
+
+}
+
 // What the first pass does besides writing partials.
 struct Pass1Extra {
     uint64_t *params;        // non-null: mark every channel's hand-over slot pending for the
@@ -709,66 +785,8 @@ __global__ __launch_bounds__(kRBlock) void range_cols_pass1(
 
     __syncthreads();                                   // LDS slots initialised
 
+    lanes_to_channel_keys<T, V, MODE>(plan, j, mn, mx, cv, active, lds_keys);
     const int32_t ch_first = (int32_t)fastdiv(j * (uint32_t)plan.span, plan.hw_div);
-    constexpr int NG = Slots<MODE, VEC>::N;             // channel groups per vector
-    // glued rows whose length divides the distance between a lane's vectors: all V vectors
-    // belong to the same channels, so they are combined in registers and only the first one
-    // goes to LDS (inactive vectors hold the identities)
-    if (V > 1 && plan.v_same) {
-#pragma unroll
-        for (int v = 1; v < V; ++v)
-#pragma unroll
-            for (int e = 0; e < NS; ++e) {
-                mn[0][e] = __builtin_fminf(mn[0][e], mn[v][e]);
-                mx[0][e] = __builtin_fmaxf(mx[0][e], mx[v][e]);
-            }
-    }
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        if (v > 0 && plan.v_same) break;               // block-uniform
-        // inactive lanes hold the identities and point at the tile's first channel; with glued
-        // rows the channel follows from the column within the true row
-        const uint32_t col = true_column(active[v] ? cv[v] * VEC : j * (uint32_t)plan.span, plan);
-        int32_t ch[NG];
-        const uint32_t split = vector_channels<MODE, VEC, NG>(col, plan, ch);
-        float gmn[NG], gmx[NG];
-        if (MODE == kTwo) {
-            // fold the element positions into the (at most) two channels of the vector
-            gmn[0] = gmn[NG - 1] = __builtin_inff();
-            gmx[0] = gmx[NG - 1] = -__builtin_inff();
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const bool first = (uint32_t)e < split;
-                const float a = mn[v][e < NS ? e : 0], b = mx[v][e < NS ? e : 0];
-                gmn[0] = __builtin_fminf(gmn[0], first ? a : __builtin_inff());
-                gmx[0] = __builtin_fmaxf(gmx[0], first ? b : -__builtin_inff());
-                gmn[NG - 1] = __builtin_fminf(gmn[NG - 1], first ? __builtin_inff() : a);
-                gmx[NG - 1] = __builtin_fmaxf(gmx[NG - 1], first ? -__builtin_inff() : b);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < NG; ++e) {
-                gmn[e] = mn[v][e < NS ? e : 0];
-                gmx[e] = mx[v][e < NS ? e : 0];
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < NG; ++e) {
-            const int32_t k = ch[e] - ch_first;
-            const int32_t k_lead = __builtin_amdgcn_readfirstlane(k);
-            if (__all(k == k_lead)) {
-                float wmn = wave_min(gmn[e]);
-                float wmx = wave_max(gmx[e]);
-                if ((threadIdx.x & (kWave - 1)) == 0) {
-                    atomicMin(&lds_keys[k_lead], float_key(wmn));
-                    atomicMax(&lds_keys[kmax + k_lead], float_key(wmx));
-                }
-            } else {
-                atomicMin(&lds_keys[k], float_key(gmn[e]));
-                atomicMax(&lds_keys[kmax + k], float_key(gmx[e]));
-            }
-        }
-    }
 
     __syncthreads();
 
@@ -842,6 +860,254 @@ __global__ __launch_bounds__(kBlock) void range_cols_pass2(
             zero_point[c] = zp;
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// ranges, parameters and forward in ONE launch, the tensor resident in registers
+// ---------------------------------------------------------------------------
+//
+// Every block loads its slice (a column tile x up to R rows, one 16-byte vector per lane and
+// row) once and keeps it in registers.  It reduces the slice to per-channel partial minima
+// and maxima, publishes them, and counts itself in at the channels its tile overlaps (one
+// 64-bit arrival counter per channel, never reset: arrival number a of a call belongs to
+// epoch a / expected).  The block that arrives last at a channel gathers the channel's
+// partials, applies Eq. 5, writes the caller's four vectors and publishes scale and
+// zero-point in the channel's parameter slot, tagged with the epoch's parity in the sign bit of
+// the (always positive) scale.  Every block then waits for the slots of its lanes' channels
+// to carry this epoch's tag and quantizes what it holds.
+//
+// Data crosses blocks only through device-scope accesses: partials and slots are written and
+// read with single atomic stores / loads that bypass the per-die L2, a block's partial stores
+// are complete (s_waitcnt) before it counts itself in, and the last arriver reads the partials
+// only after its own arrival returned.
+//
+// Nothing depends on all blocks being on the chip at once except speed: a wavefront that has
+// polled spin_limit times stops waiting and computes its channels' ranges by scanning the
+// channels itself (x is still intact: this form does not run in place).
+struct ResidentArgs {
+    const void *x;
+    void *x_hat;                     // may be null (codes only)
+    uint8_t *codes;                  // may be null
+    float *ch_min, *ch_max, *scale, *zero_point;
+    float *ws_min, *ws_max;          // partials
+    unsigned long long *arrive;      // arrivals per channel since the state was zeroed
+    uint64_t *params;                // scale (epoch tag in the sign bit) | zero-point << 32
+    ColPlan plan;
+    int64_t n, c, hw;                // the tensor's own dimensions (for the scan of a channel)
+    float qmax;
+    int32_t spin_limit;
+};
+
+__device__ inline void store_agent(float *p, float v) {
+    __hip_atomic_store((uint32_t *)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float load_agent(const float *p) {
+    return __uint_as_float(__hip_atomic_load((const uint32_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// gather_channel with device-scope loads (the partials were written by blocks of this launch).
+__device__ inline void gather_channel_agent(const float *ws_min, const float *ws_max, const ColPlan &plan,
+                                            int64_t c, uint32_t start, uint32_t stride, float &mn, float &mx) {
+    const ChannelPartials cp = channel_partials(plan, c);
+    for (uint32_t i = start; i < cp.total; i += stride) {
+        const int64_t at = channel_partial_slot(plan, c, cp, i);
+        mn = __builtin_fminf(mn, load_agent(ws_min + at));
+        mx = __builtin_fmaxf(mx, load_agent(ws_max + at));
+    }
+}
+
+// Min / max of channel ch straight from the tensor, by one wavefront.
+template <typename T>
+__device__ inline void scan_channel(const void *x, int64_t n, int64_t c, int64_t hw, int64_t ch, float &mn, float &mx) {
+    const int lane = threadIdx.x & (kWave - 1);
+    mn = __builtin_inff();
+    mx = -__builtin_inff();
+    for (int64_t in = 0; in < n; ++in) {
+        const int64_t base = (in * c + ch) * hw;
+        for (int64_t k = lane; k < hw; k += kWave) {
+            const float v = T::load1(x, base + k);
+            mn = __builtin_fminf(mn, v);
+            mx = __builtin_fmaxf(mx, v);
+        }
+    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
+}
+
+template <typename T, int R, int MODE>
+__global__ __launch_bounds__(kResBlock) void fq_resident_cols(ResidentArgs a)
+{
+    constexpr int VEC = T::VEC;
+    constexpr int NR = MODE == kOne ? 1 : VEC;          // running min / max per element position
+    constexpr int NS = Slots<MODE, VEC>::N;             // channel slots of a vector
+    using vec_t = typename T::vec_t;
+    extern __shared__ uint32_t lds_keys[];              // [kmax] min keys, then [kmax] max keys
+    __shared__ uint32_t epoch_tag;
+    const ColPlan &plan = a.plan;
+    const uint32_t j = blockIdx.x, p = blockIdx.y;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row_vecs = plan.row_len / VEC;
+    const int32_t kmax = plan.kmax;
+    for (int i = threadIdx.x; i < kmax; i += kResBlock) {
+        lds_keys[i] = kKeyPosInf;
+        lds_keys[kmax + i] = kKeyNegInf;
+    }
+
+    // 1. the slice, all loads in flight together
+    const uint32_t col = j * (uint32_t)plan.span + threadIdx.x * VEC;
+    const bool active1[1] = {col < (uint32_t)plan.row_len};
+    const uint32_t cv1[1] = {col / VEC};
+    const int64_t r0 = (int64_t)p * plan.rows_per_group;
+    const int64_t r1 = (r0 + plan.rows_per_group < plan.rows) ? r0 + plan.rows_per_group : plan.rows;
+    const int nrows = (int)(r1 - r0);                   // <= R
+    vec_t in[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+        if (u < nrows && active1[0]) in[u] = ((const vec_t *)a.x)[(r0 + u) * row_vecs + cv1[0]];
+    float mn[1][NR], mx[1][NR];
+#pragma unroll
+    for (int e = 0; e < NR; ++e) {
+        mn[0][e] = __builtin_inff();
+        mx[0][e] = -__builtin_inff();
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+        if (u < nrows && active1[0]) {
+            float f[VEC];
+            T::unpack(in[u], f);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                mn[0][MODE == kOne ? 0 : e] = __builtin_fminf(mn[0][MODE == kOne ? 0 : e], f[e]);
+                mx[0][MODE == kOne ? 0 : e] = __builtin_fmaxf(mx[0][MODE == kOne ? 0 : e], f[e]);
+            }
+        }
+
+    // 2. per-channel partials of the block
+    __syncthreads();
+    lanes_to_channel_keys<T, 1, MODE>(plan, j, mn, mx, cv1, active1, lds_keys);
+    __syncthreads();
+
+    // 3. publish, arrive, and finish the channels this block completes (first wavefront)
+    const int32_t ch_first = (int32_t)fastdiv(j * (uint32_t)plan.span, plan.hw_div);
+    if (threadIdx.x < kWave) {
+        const uint32_t tile_end = (j + 1) * (uint32_t)plan.span < (uint32_t)plan.row_len ? (j + 1) * (uint32_t)plan.span
+                                                                                         : (uint32_t)plan.row_len;
+        int32_t ch_last = (int32_t)fastdiv(tile_end - 1, plan.hw_div);
+        if (ch_last > plan.channels - 1) ch_last = plan.channels - 1;     // glued rows: one tile, all channels
+        const int64_t slot = partial_slot(plan, p, j, 0);
+        for (int i = lane; i < kmax; i += kWave) {
+            store_agent(a.ws_min + slot + i, key_float(lds_keys[i]));
+            store_agent(a.ws_max + slot + i, key_float(lds_keys[kmax + i]));
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the partials have reached memory
+        uint32_t tag = 0;
+        for (int base = 0; base < kmax; base += kWave) {          // wave-uniform loop
+            const int32_t c = ch_first + base + lane;
+            const bool valid = c <= ch_last;
+            unsigned long long old = 0;
+            uint32_t expected = 1;
+            if (valid) {
+                expected = channel_partials(plan, c).total;
+                old = __hip_atomic_fetch_add(a.arrive + c, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const unsigned long long epoch = old / expected;
+            bool last = valid && (uint32_t)(old - epoch * expected) == expected - 1;
+            if (base == 0) tag = (uint32_t)((epoch + 1) & 1u);    // lane 0 is valid; every channel is in the same epoch
+            uint64_t todo;
+            while ((todo = __ballot(last)) != 0) {                // one completed channel at a time
+                const int leader = __builtin_ctzll(todo);
+                const int32_t cl = __builtin_amdgcn_readlane(c, leader);
+                float gmn = __builtin_inff(), gmx = -__builtin_inff();
+                gather_channel_agent(a.ws_min, a.ws_max, plan, cl, lane, kWave, gmn, gmx);
+                gmn = wave_min(gmn);
+                gmx = wave_max(gmx);
+                if (lane == leader) {
+                    float sc, zp;
+                    prescale_one(gmn, gmx, a.qmax, sc, zp);
+                    const uint32_t my_tag = (uint32_t)((epoch + 1) & 1u);
+                    publish_params(a.params + cl, (uint64_t)(__float_as_uint(sc) | (my_tag << 31)) |
+                                                      ((uint64_t)__float_as_uint(zp) << 32));
+                    a.ch_min[cl] = gmn;
+                    a.ch_max[cl] = gmx;
+                    a.scale[cl] = sc;
+                    a.zero_point[cl] = zp;
+                    last = false;
+                }
+            }
+        }
+        if (lane == 0) epoch_tag = __builtin_amdgcn_readfirstlane(tag);
+    }
+    __syncthreads();
+    const uint32_t want = epoch_tag;
+
+    // 4. wait for the parameters of this lane's channels
+    int32_t ch[NS];
+    const uint32_t split = vector_channels<MODE, VEC, NS>(active1[0] ? true_column(col, plan) : 0u, plan, ch);
+    uint64_t pk[NS];
+    auto poll = [&]() {
+        bool pending = false;
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            pk[e] = load_params(a.params + ch[e]);
+            pending = pending || (((uint32_t)pk[e]) >> 31) != want;
+        }
+        return pending;
+    };
+    bool pending = poll();
+    for (int32_t spins = 0; spins < a.spin_limit && __any(pending); ++spins) {
+        __builtin_amdgcn_s_sleep(4);
+        pending = poll();
+    }
+    if (__any(pending)) {                               // wave-uniform: scan the pending channels ourselves
+#pragma unroll
+        for (int e = 0; e < NS; ++e) {
+            bool mine = (((uint32_t)pk[e]) >> 31) != want;
+            uint64_t waiting;
+            while ((waiting = __ballot(mine)) != 0) {
+                const int leader = __builtin_ctzll(waiting);
+                const int32_t cl = __builtin_amdgcn_readlane(ch[e], leader);
+                float gmn, gmx, sc, zp;
+                scan_channel<T>(a.x, a.n, a.c, a.hw, cl, gmn, gmx);
+                prescale_one(gmn, gmx, a.qmax, sc, zp);
+                if (mine && ch[e] == cl) {
+                    pk[e] = pack_params(sc, zp) | ((uint64_t)want << 31);
+                    mine = false;
+                }
+            }
+        }
+    }
+    ChanRegs cr[NS];
+    bool fast = GRANQ_FAST_QUOTIENT != 0;
+#pragma unroll
+    for (int e = 0; e < NS; ++e) {
+        cr[e].s = __uint_as_float((uint32_t)pk[e] & 0x7FFFFFFFu);
+        cr[e].z = __uint_as_float((uint32_t)(pk[e] >> 32));
+        cr[e].r = 1.0f / cr[e].s;
+        fast = fast && quotient_fast_ok(cr[e].s, cr[e].z);
+    }
+    fast = __all(fast);
+
+    // 5. quantize, clamp, dequantize what the block holds
+    auto finish = [&](auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+#pragma unroll
+        for (int u = 0; u < R; ++u)
+            if (u < nrows && active1[0]) {
+                float f[VEC], q[VEC];
+                T::unpack(in[u], f);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const ChanRegs cc = pick_chan<MODE>(cr, e, split);
+                    q[e] = clamp_code(code_of<FAST>(f[e], cc), a.qmax);
+                    f[e] = dequant(q[e], cc.s, cc.z);
+                }
+                const int64_t at = (r0 + u) * row_vecs + cv1[0];
+                if (a.x_hat) store_vec((vec_t *)a.x_hat + at, T::pack(f));
+                if (a.codes) store_vec((typename T::code_t *)a.codes + at, T::pack_codes(q));
+            }
+    };
+    if (fast) finish(std::true_type{});
+    else finish(std::false_type{});
 }
 
 // ---------------------------------------------------------------------------
@@ -1548,6 +1814,107 @@ granq_status_t granq_fakequant_bwd_mask(const void *dy, const uint8_t *mask, con
     dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
     if (desc->dtype == GRANQ_F32) launch_kernel(bwd_mask_bytes<F32>, grid, block, 0, hs, dy, mask, total, dx);
     else launch_kernel(bwd_mask_bytes<Pack16>, grid, block, 0, hs, dy, mask, total, dx);
+    return launched();
+}
+
+}  // extern "C"
+
+// ---- single-launch ("resident") form --------------------------------------------------------
+
+namespace granq {
+
+__global__ __launch_bounds__(kBlock) void zero_words(uint32_t *p, size_t words) {
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < words; i += (size_t)gridDim.x * kBlock) p[i] = 0u;
+}
+
+template <typename T, int R>
+static hipError_t launch_resident(const ColPlan &pl, const ResidentArgs &ra, hipStream_t st, int *blocks_per_cu) {
+    dim3 grid((uint32_t)pl.col_tiles, (uint32_t)pl.row_groups), block(kResBlock);
+    const size_t lds = (size_t)2 * pl.kmax * sizeof(uint32_t);
+    void (*kernel)(ResidentArgs) = pl.mode == kOne ? fq_resident_cols<T, R, kOne>
+                                 : (pl.mode == kTwo ? fq_resident_cols<T, R, kTwo> : fq_resident_cols<T, R, kEach>);
+    // all blocks must fit the chip together for this form to be worth taking
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, (const void *)kernel, kResBlock, lds);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((int64_t)pl.col_tiles * pl.row_groups > (int64_t)*blocks_per_cu * cus) {
+        *blocks_per_cu = -1;
+        return hipSuccess;
+    }
+    launch_kernel(kernel, grid, block, lds, st, ra);
+    return hipSuccess;
+}
+
+}  // namespace granq
+
+extern "C" {
+
+granq_status_t granq_resident_state_bytes(const granq_desc_t *desc, size_t *bytes_out) {
+    if (!bytes_out) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    const ResidentPlan rp = resident_plan(desc);
+    if (!rp.ok) return GRANQ_ERR_UNSUPPORTED;
+    *bytes_out = rp.bytes;
+    return GRANQ_OK;
+}
+
+granq_status_t granq_resident_state_init(void *state, size_t state_bytes, void *stream) {
+    if (!state || state_bytes == 0) return GRANQ_ERR_INVALID_ARG;
+    if (!aligned16(state) || state_bytes % 4 != 0) return GRANQ_ERR_UNSUPPORTED;
+    const size_t words = state_bytes / 4;
+    const size_t blocks = (words + kBlock - 1) / kBlock;
+    launch_kernel(zero_words, dim3((uint32_t)(blocks < 4096 ? blocks : 4096)), dim3(kBlock), 0, (hipStream_t)stream,
+                  (uint32_t *)state, words);
+    return launched();
+}
+
+granq_status_t granq_calibrate_fakequant_fwd_resident(const void *x, const granq_desc_t *desc, int bits,
+                                                      float *ch_min, float *ch_max, float *scale,
+                                                      float *zero_point, void *x_hat, uint8_t *codes_or_null,
+                                                      void *state, size_t state_bytes, void *stream) {
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    if (!ch_min || !ch_max || !scale || !zero_point) return GRANQ_ERR_INVALID_ARG;
+    st = fwd_check(x, desc, scale, zero_point, bits, x_hat, codes_or_null);
+    if (st != GRANQ_OK) return st;
+    if (!aligned_elem(ch_min, GRANQ_F32) || !aligned_elem(ch_max, GRANQ_F32)) return GRANQ_ERR_UNSUPPORTED;
+    const ResidentPlan rp = resident_plan(desc);
+    // shapes, sizes and pointers this form does not take (the caller uses granq_calibrate_fakequant_fwd)
+    if (!rp.ok || !fwd_cols_ok(rp.plan, desc, x, x_hat, codes_or_null) || x_hat == x) return GRANQ_ERR_UNSUPPORTED;
+    if (!state || state_bytes < rp.bytes || !aligned16(state)) return GRANQ_ERR_WORKSPACE;
+    ResidentArgs ra{};
+    ra.x = x;
+    ra.x_hat = x_hat;
+    ra.codes = codes_or_null;
+    ra.ch_min = ch_min;
+    ra.ch_max = ch_max;
+    ra.scale = scale;
+    ra.zero_point = zero_point;
+    ra.ws_min = (float *)state;
+    ra.ws_max = (float *)((char *)state + rp.off_max);
+    ra.arrive = (unsigned long long *)((char *)state + rp.off_arrive);
+    ra.params = (uint64_t *)((char *)state + rp.off_params);
+    ra.plan = rp.plan;
+    ra.n = desc->n;
+    ra.c = desc->c;
+    ra.hw = desc->h * desc->w;
+    ra.qmax = (float)((1 << bits) - 1);
+    ra.spin_limit = spin_limit();
+    hipStream_t hs = (hipStream_t)stream;
+    int per_cu = 0;
+    hipError_t e;
+    const bool small = rp.rows_held == kResRowsSmall;
+    if (desc->dtype == GRANQ_F32)
+        e = small ? launch_resident<F32, kResRowsSmall>(rp.plan, ra, hs, &per_cu) : launch_resident<F32, kResRowsLarge>(rp.plan, ra, hs, &per_cu);
+    else if (desc->dtype == GRANQ_BF16)
+        e = small ? launch_resident<BF16, kResRowsSmall>(rp.plan, ra, hs, &per_cu) : launch_resident<BF16, kResRowsLarge>(rp.plan, ra, hs, &per_cu);
+    else
+        e = small ? launch_resident<F16, kResRowsSmall>(rp.plan, ra, hs, &per_cu) : launch_resident<F16, kResRowsLarge>(rp.plan, ra, hs, &per_cu);
+    if (e != hipSuccess) return GRANQ_ERR_HIP;
+    if (per_cu < 0) return GRANQ_ERR_UNSUPPORTED;           // the grid would not fit the chip: nothing launched
     return launched();
 }
 

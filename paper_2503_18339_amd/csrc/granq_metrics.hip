@@ -7,8 +7,9 @@
 // lanes stride over H*W (16-byte vectors, four in flight per lane, where the shape
 // allows); per-lane binary64 accumulators, wavefront tree by
 // shuffles, block tree through LDS, one partial per (p, c).  Pass 2: per channel
-// the partials are added in order of p; one thread then adds the channels in
-// order and forms the two ratios.  Every addition order is fixed.
+// and sum a wavefront adds the partials (lane-strided, then the shuffle tree); a last
+// launch adds the channels the same way and forms the two ratios.  Every addition
+// order is fixed, so the sums are reproducible.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
@@ -125,24 +126,35 @@ static void launch_distortion_pass1(bool vector, bool stream, dim3 grid, hipStre
         launch_kernel((distortion_pass1<T, true, false>), grid, block, 0, hs, x, scale, zero_point, qmax, n, c, hw, rp, ws);
 }
 
+// Pass 2: block = channel, wavefront w = sum w of the four.  A lane adds the partials
+// p = lane, lane + 64, ... in that order; the 64 lane sums then go through the shuffle tree.
 __global__ __launch_bounds__(kBlock) void distortion_pass2(
     const double *__restrict__ ws, int64_t c, int32_t groups, double *__restrict__ ch_sums)
 {
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;     // (channel, which sum)
-    if (i >= c * 4) return;
+    static_assert(kBlock / kWave >= 4, "one wavefront per sum");
+    const int64_t ic = blockIdx.x;
+    const int which = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    if (which >= 4) return;
     double t = 0.0;
-    for (int32_t p = 0; p < groups; ++p) t += ws[(int64_t)p * c * 4 + i];
-    ch_sums[i] = t;
+    for (int32_t p = lane; p < groups; p += kWave) t += ws[((int64_t)p * c + ic) * 4 + which];
+    t = wave_sum(t);
+    if (lane == 0) ch_sums[ic * 4 + which] = t;
 }
 
-__global__ void distortion_layer(const double *__restrict__ ch_sums, int64_t c, double *__restrict__ layer)
+// The whole tensor: wavefront w adds sum w of the channels (lane-strided, then the tree);
+// thread 0 forms the two ratios.
+__global__ __launch_bounds__(kBlock) void distortion_layer(const double *__restrict__ ch_sums, int64_t c,
+                                                           double *__restrict__ layer)
 {
     __shared__ double tot[4];
-    if (threadIdx.x < 4) {
-        double t = 0.0;
-        for (int64_t ic = 0; ic < c; ++ic) t += ch_sums[ic * 4 + threadIdx.x];
-        tot[threadIdx.x] = t;
-        layer[threadIdx.x] = t;
+    const int which = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    double t = 0.0;
+    if (which < 4)
+        for (int64_t ic = lane; ic < c; ic += kWave) t += ch_sums[ic * 4 + which];
+    t = wave_sum(t);
+    if (lane == 0 && which < 4) {
+        tot[which] = t;
+        layer[which] = t;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -220,9 +232,9 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc, const f
     else
         launch_distortion_pass1<F16>(vector, streamed, grid, hs, x, scale, zero_point, qmax, n, desc->c, hw, rp, ws);
     if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
-    launch_kernel(distortion_pass2, dim3((uint32_t)ceil_div(desc->c * 4, kBlock)), block, 0, hs, ws, desc->c, rp.row_groups, ch_sums);
+    launch_kernel(distortion_pass2, dim3((uint32_t)desc->c), block, 0, hs, ws, desc->c, rp.row_groups, ch_sums);
     if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
-    launch_kernel(distortion_layer, dim3(1), dim3(kWave), 0, hs, ch_sums, desc->c, layer);
+    launch_kernel(distortion_layer, dim3(1), block, 0, hs, ch_sums, desc->c, layer);
     return launched();
 }
 

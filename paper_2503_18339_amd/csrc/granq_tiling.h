@@ -167,4 +167,58 @@ inline int64_t finisher_rows_of(const ColPlan &cp, const ColPlan &fp) {
 }
 
 
+// ---------------------------------------------------------------------------
+// The single-launch ("resident") form of ranges + parameters + forward: every block keeps its
+// slice of the tensor in registers from the min / max sweep to the quantization, so the
+// tensor must fit the register files of the blocks that can be on the chip together.
+// ---------------------------------------------------------------------------
+#ifndef GRANQ_RESIDENT_MAX_BYTES
+#define GRANQ_RESIDENT_MAX_BYTES ((int64_t)64 << 20)
+#endif
+constexpr int kResBlock = 256;            // threads per block
+constexpr int kResRowsSmall = 4;          // vectors a lane holds: 4 where that keeps the grid within
+constexpr int kResRowsLarge = 16;         // the limit below, else 16
+// Blocks of one launch: 256 compute units x 4 blocks of 256 threads.  The register files would
+// hold twice as many of the small kind, but measured on MI355X a grid of 1600 such blocks is no
+// longer on the chip all at once (the blocks that start late find the others waiting for them),
+// while 1400 are; half the nominal capacity keeps a margin.
+constexpr int kResBlocksSmall = 1024;
+constexpr int kResBlocksLarge = 1024;
+
+struct ResidentPlan {
+    bool ok;
+    int rows_held;                        // kResRowsSmall or kResRowsLarge
+    ColPlan plan;                         // column tiles of kResBlock lanes x one vector, row groups of rows_held rows
+    size_t off_max, off_arrive, off_params, bytes;   // state layout: partial minima at 0
+};
+
+inline ResidentPlan resident_plan(const granq_desc_t *d) {
+    ResidentPlan r{};
+    r.ok = false;
+    if (tensor_bytes(d) > GRANQ_RESIDENT_MAX_BYTES) return r;
+    ColPlan p = make_col_plan(d->n, d->c, d->h * d->w, vec_of(d->dtype), 1, kResBlock, (int64_t)1 << 40, 1);
+    if (!p.ok) return r;
+    for (int held : {kResRowsSmall, kResRowsLarge}) {
+        const int64_t groups = ceil_div(p.rows, held);
+        const int64_t limit = held == kResRowsSmall ? kResBlocksSmall : kResBlocksLarge;
+        if (groups > 65535 || groups * p.col_tiles > limit) continue;
+        p.rows_per_group = (int32_t)ceil_div(p.rows, groups);
+        p.row_groups = (int32_t)ceil_div(p.rows, p.rows_per_group);
+        r.rows_held = held;
+        r.ok = true;
+        break;
+    }
+    if (!r.ok) return r;
+    p.nt_row_end = 0;
+    // one wavefront gathers a channel's partials; the keys of a tile's channels sit in LDS
+    if (partials_per_channel(p) > 512 || p.kmax > 4096) { r.ok = false; return r; }
+    r.plan = p;
+    const size_t floats = col_ws_floats(p);
+    r.off_max = floats * sizeof(float);
+    r.off_arrive = (2 * floats * sizeof(float) + 15) & ~(size_t)15;
+    r.off_params = r.off_arrive + (size_t)p.channels * 8;
+    r.bytes = r.off_params + (size_t)p.channels * 8;
+    return r;
+}
+
 }  // namespace granq

@@ -124,7 +124,7 @@ def load_record(workload: str = "config3", dtype: str = "f32"):
 
 
 TRACE_HEADER = """Kernel times of the default benchmark run (ResNet-18 ImageNet activation set, batch 256, float32,
-4-bit: range_reduce + prescale + forward per tensor, then backward in reverse; 20 warm-up + 200 timed steps)
+4-bit: granq_calibrate_fakequant_fwd per tensor, then backward in reverse; 20 warm-up + 200 timed steps)
 
 command (from /tmp with TMPDIR=/tmp, repository at $R, output under $OUT):
   rocprofv3 --kernel-trace --stats --output-format csv -d $OUT/trace -o bench -- \\
@@ -135,7 +135,8 @@ summary made with:
 """
 
 COUNTER_HEADER = """HBM traffic of the GranQ kernels on the default benchmark workload, from two rocprofv3 counter runs
-(ResNet-18 ImageNet activation set, batch 256, float32, 4-bit; FETCH_SIZE and WRITE_SIZE in KiB per dispatch)
+(ResNet-18 ImageNet activation set, batch 256, float32, 4-bit, granq_calibrate_fakequant_fwd per tensor then
+backward in reverse; FETCH_SIZE and WRITE_SIZE in KiB per dispatch)
 
 commands (from /tmp with TMPDIR=/tmp, repository at $R, output under $OUT), one counter per run:
   rocprofv3 --pmc FETCH_SIZE --output-format csv -d $OUT/fetch -o bench -- \\
@@ -150,20 +151,56 @@ a known number of bytes gives the scale factors below)
 """
 
 
+def summarise_pmc(counter_csv: str, only: str = "granq") -> str:
+    """Per kernel and counter: mean of the counter over the kernel's dispatches."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(counter_csv)):
+        if only and only not in r["Kernel_Name"]:
+            continue
+        agg[_short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    names = sorted({c for k in agg.values() for c in k})
+    out = ["%-58s %9s " % ("kernel", "launches") + " ".join("%16s" % n for n in names)]
+    for k, cs in sorted(agg.items()):
+        n = max(len(v) for v in cs.values())
+        out.append("%-58s %9d " % (k[:58], n) + " ".join(
+            "%16.2f" % (sum(cs[c]) / len(cs[c])) if c in cs else "%16s" % "-" for c in names))
+    return "\n".join(out)
+
+
+def _header(title: str, command: str, made_with: str) -> str:
+    return "%s\n\ncommand (from /tmp with TMPDIR=/tmp, repository at $R, output under $OUT):\n  %s\nsummary made with:\n  %s\n" % (
+        title, command.replace("\\n", "\n  "), made_with)
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
     t = sub.add_parser("trace")
     t.add_argument("stats_csv")
+    t.add_argument("--title", help="what was run (default: the default benchmark run)")
+    t.add_argument("--command", help="the rocprofv3 command that made the file")
     c = sub.add_parser("counters")
     c.add_argument("fetch_csv")
     c.add_argument("write_csv")
     c.add_argument("--copy-bytes", type=int, required=True)
     c.add_argument("--write-record", action="store_true")
+    m = sub.add_parser("pmc")
+    m.add_argument("counter_csv")
+    m.add_argument("--title", required=True)
+    m.add_argument("--command", required=True)
+    m.add_argument("--only", default="granq", help="substring a kernel name must contain")
     args = ap.parse_args(argv)
     if args.cmd == "trace":
-        print(TRACE_HEADER)
+        if args.title:
+            print(_header(args.title, args.command or "", "python -m paper_2503_18339_amd.profiling trace "
+                          "<stats csv> --title ... --command ..."))
+        else:
+            print(TRACE_HEADER)
         print(summarise_trace(args.stats_csv))
+    elif args.cmd == "pmc":
+        print(_header(args.title, args.command, "python -m paper_2503_18339_amd.profiling pmc "
+                      "<counter_collection csv> --title ... --command ..."))
+        print(summarise_pmc(args.counter_csv, args.only))
     else:
         text, record = summarise_counters(args.fetch_csv, args.write_csv, args.copy_bytes)
         print(COUNTER_HEADER)

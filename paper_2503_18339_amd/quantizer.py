@@ -1,8 +1,8 @@
 """Buffer management for one activation tensor: the four calls in sequence.
 
-Holds the caller-side buffers (ranges, scale, zero-point, workspace) that the
-C ABI expects the caller to own, and issues range_reduce -> prescale -> forward
-(and backward) on the current stream.  No arithmetic happens here.
+Holds the caller-side buffers (ranges, scale, zero-point, workspace, and the state
+of the single-launch forward where the tensor takes it) that the C ABI expects the
+caller to own, and issues the calls on the current stream.  No arithmetic happens here.
 """
 from __future__ import annotations
 
@@ -16,7 +16,8 @@ from . import binding as B
 class ActivationQuantizer:
     """Per-channel fake-quantizer for tensors of one fixed shape and dtype."""
 
-    def __init__(self, shape, dtype: torch.dtype, bits: int, device="cuda", view: str = "channel"):
+    def __init__(self, shape, dtype: torch.dtype, bits: int, device="cuda", view: str = "channel",
+                 single_launch: bool = False):
         n, c = int(shape[0]), int(shape[1])
         hw = 1
         for d in shape[2:]:
@@ -43,6 +44,10 @@ class ActivationQuantizer:
         self.zero_point = torch.empty(cc, **f32)
         self.workspace = torch.empty(max(16, B.granq_workspace_bytes(self.desc)), dtype=torch.uint8,
                                      device=device)
+        # on request, tensors the single-launch forward takes get its state (zero before the first
+        # use); measured on MI355X that form is slower than the two-launch one, so it is not the default
+        nbytes = B.granq_resident_state_bytes(self.desc) if single_launch else 0
+        self.state = torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes > 0 else None
 
     def calibrate(self, x: torch.Tensor, stream=None) -> None:
         """range_reduce + prescale (the two in one call): refresh scale / zero-point from x."""
@@ -52,6 +57,11 @@ class ActivationQuantizer:
     def forward(self, x: torch.Tensor, x_hat: torch.Tensor, codes: Optional[torch.Tensor] = None,
                 stream=None, recalibrate: bool = True) -> torch.Tensor:
         if recalibrate:                  # ranges, parameters and the forward in one call
+            if self.state is not None and (x_hat is None or x_hat.data_ptr() != x.data_ptr()):
+                if B.granq_calibrate_fakequant_fwd_resident(x, self.bits, self.ch_min, self.ch_max, self.scale,
+                                                            self.zero_point, x_hat, codes, self.state, stream,
+                                                            self.desc):
+                    return x_hat
             B.granq_calibrate_fakequant_fwd(x, self.bits, self.ch_min, self.ch_max, self.scale, self.zero_point,
                                             x_hat, codes, self.workspace, stream, self.desc)
         else:

@@ -186,6 +186,37 @@ static void check_shape(const granq_desc_t &d) {
     // the finishing forward's grid
     const int64_t fin = finisher_rows_of(rp, fp);
     CHECK(fin * fp.col_tiles * (kEBlock / 64) >= channels, "finisher rows do not cover the channels");
+
+    // the single-launch form: its walk, its state layout, and its arrival counts -- a channel
+    // completes when exactly channel_partials().total blocks have counted themselves in, and a block
+    // counts itself in at the channels first .. last of its tile
+    const ResidentPlan res = resident_plan(&d);
+    if (res.ok) {
+        const ColPlan &qp = res.plan;
+        CHECK(qp.rows_per_group <= res.rows_held, "a block holds %d rows, its lanes %d", qp.rows_per_group, res.rows_held);
+        CHECK((int64_t)qp.col_tiles * qp.row_groups <= (res.rows_held == kResRowsSmall ? kResBlocksSmall : kResBlocksLarge),
+              "resident grid of %lld blocks", (long long)qp.col_tiles * qp.row_groups);
+        walk<VEC>(qp, kResBlock, 1, t, d, "resident forward", true);
+        const size_t qfloats = col_ws_floats(qp);
+        CHECK(res.off_max == qfloats * 4 && res.off_arrive >= 2 * qfloats * 4 && res.off_arrive % 8 == 0 &&
+              res.off_params == res.off_arrive + (size_t)qp.channels * 8 && res.bytes == res.off_params + (size_t)qp.channels * 8,
+              "resident state layout");
+        std::vector<int64_t> arrivals((size_t)qp.channels, 0);
+        for (int64_t j = 0; j < qp.col_tiles; ++j) {
+            const int64_t first = fastdiv((uint32_t)(j * qp.span), qp.hw_div);
+            const int64_t end = (j + 1) * qp.span < qp.row_len ? (j + 1) * qp.span : qp.row_len;
+            int64_t last = fastdiv((uint32_t)(end - 1), qp.hw_div);
+            if (last > qp.channels - 1) last = qp.channels - 1;
+            CHECK(last - first < qp.kmax, "tile %lld arrives at %lld channels, %d slots", (long long)j, (long long)(last - first + 1), qp.kmax);
+            for (int64_t c = first; c <= last; ++c) arrivals[(size_t)c] += qp.row_groups;
+        }
+        for (int64_t c = 0; c < qp.channels; ++c)
+            CHECK(arrivals[(size_t)c] == (int64_t)channel_partials(qp, c).total,
+                  "channel %lld: %lld blocks arrive, %u are expected", (long long)c, (long long)arrivals[(size_t)c],
+                  channel_partials(qp, c).total);
+    } else {
+        CHECK(e * esize > GRANQ_RESIDENT_MAX_BYTES || rp.rows > 0, "resident plan refused");
+    }
 }
 
 int main(int argc, char **argv) {
