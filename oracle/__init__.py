@@ -67,6 +67,8 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.granq_oracle_distortion.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr, _ptr]
     lib.granq_oracle_fold_weights.argtypes = [_ptr, _ptr, _ptr, _i64, _i64, _ptr, _ptr, _ptr]
     lib.granq_oracle_conv1x1_int8.argtypes = [_ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
+    lib.granq_oracle_pack4.argtypes = [_ptr, _i64, _ptr]
+    lib.granq_oracle_unpack4.argtypes = [_ptr, _i64, _ptr]
     lib.granq_oracle_accumulate_inloop.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
     lib.granq_oracle_accumulate_prescaled.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr]
     lib.granq_oracle_f16_widen.argtypes = [_ptr, _i64, _ptr]
@@ -205,13 +207,13 @@ def fakequant(x: np.ndarray, bits: int, lib=None):
 
 
 def fold_weights(w: np.ndarray, scale, zero_point, lib=None):
-    """Eq. 3's w_c * s_c folded into int8 rows.  Returns (wq int8[O,C], corr int32[O], out_scale f32[O])."""
+    """Eq. 3's w_c * s_c folded into int8 rows.  Returns (wq int8[O,C], corr int64[O], out_scale f32[O])."""
     lib = lib or load()
     w = np.ascontiguousarray(w, np.float32)
     o, c = w.shape
     s, z = _f32vec(scale, c), _f32vec(zero_point, c)
     wq = np.empty((o, c), np.int8)
-    corr = np.empty(o, np.int32)
+    corr = np.empty(o, np.int64)
     a = np.empty(o, np.float32)
     lib.granq_oracle_fold_weights(_p(w), _p(s), _p(z), o, c, _p(wq), _p(corr), _p(a))
     return wq, corr, a
@@ -225,11 +227,32 @@ def conv1x1_int8(codes: np.ndarray, wq: np.ndarray, corr: np.ndarray, out_scale:
         raise TypeError("codes must be uint8 (N,C,...), wq int8 (O,C)")
     o = wq.shape[0]
     wq = np.ascontiguousarray(wq)
-    corr = np.ascontiguousarray(corr, np.int32)
+    corr = np.ascontiguousarray(corr, np.int64)
     a = np.ascontiguousarray(out_scale, np.float32)
     y = np.empty((n, o) + codes.shape[2:], np.float32)
     lib.granq_oracle_conv1x1_int8(_p(codes), n, c, hw, o, _p(wq), _p(corr), _p(a), _p(y))
     return y
+
+
+def pack4(codes: np.ndarray, lib=None) -> np.ndarray:
+    """Two codes (each below 16) per byte: element 2i in the low nibble of byte i."""
+    lib = lib or load()
+    codes = np.ascontiguousarray(codes, np.uint8)
+    if codes.size and codes.max() > 15:
+        raise ValueError("codes of more than four bits cannot be packed two per byte")
+    out = np.empty((codes.size + 1) // 2, np.uint8)
+    lib.granq_oracle_pack4(_p(codes), codes.size, _p(out))
+    return out
+
+
+def unpack4(packed: np.ndarray, total: int, lib=None) -> np.ndarray:
+    lib = lib or load()
+    packed = np.ascontiguousarray(packed, np.uint8)
+    if packed.size != (total + 1) // 2:
+        raise ValueError("packed codes of %d elements take %d bytes" % (total, (total + 1) // 2))
+    out = np.empty(total, np.uint8)
+    lib.granq_oracle_unpack4(_p(packed), int(total), _p(out))
+    return out
 
 
 def accumulate_inloop(codes: np.ndarray, scale, zero_point, weight, lib=None):

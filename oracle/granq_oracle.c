@@ -423,10 +423,12 @@ void granq_oracle_accumulate_prescaled(const float *x_hat,
  * Fold: w'[o,c] = w[o,c] * s_c; the row is quantized symmetrically to int8 with
  * step a_o = max_c |w'[o,c]| / 127 (1 for an all-zero row):
  *     wq[o,c] = clamp(round(w'[o,c] / a_o), -127, 127),   corr[o] = sum_c wq[o,c] * z_c
- * (z_c is an integer held in a float).  binary32 operations, one rounding each.
+ * (z_c is an integer held in a float).  binary32 operations, one rounding each; the
+ * zero-point term is an exact integer sum, kept in 64 bits (|wq| <= 127, |z_c| < 2^24
+ * and up to 65535 channels do not fit 32).
  */
 void granq_oracle_fold_weights(const float *w, const float *scale, const float *zero_point,
-                               int64_t o, int64_t c, int8_t *wq, int32_t *corr, float *out_scale)
+                               int64_t o, int64_t c, int8_t *wq, int64_t *corr, float *out_scale)
 {
     for (int64_t io = 0; io < o; ++io) {
         float amax = 0.0f;
@@ -437,13 +439,13 @@ void granq_oracle_fold_weights(const float *w, const float *scale, const float *
         float a = amax / 127.0f;
         if (!(a > 0.0f))
             a = 1.0f;
-        int32_t cz = 0;
+        int64_t cz = 0;
         for (int64_t ic = 0; ic < c; ++ic) {
             float ws = w[io * c + ic] * scale[ic];
             float q = rintf(ws / a);
             q = fminf(fmaxf(q, -127.0f), 127.0f);
             wq[io * c + ic] = (int8_t)q;
-            cz += (int32_t)q * (int32_t)zero_point[ic];
+            cz += (int64_t)q * (int64_t)zero_point[ic];
         }
         corr[io] = cz;
         out_scale[io] = a;
@@ -453,20 +455,45 @@ void granq_oracle_fold_weights(const float *w, const float *scale, const float *
 /*
  * The 1x1 convolution on the codes:
  *     y[n,o,k] = out_scale[o] * (float)( sum_c wq[o,c] * code[n,c,k]  -  corr[o] )
- * The sum is exact in int32; the conversion to float and the product round once each.
+ * The integer expression is exact (64-bit); the conversion to float and the product round
+ * once each.
  */
 void granq_oracle_conv1x1_int8(const uint8_t *codes, int64_t n, int64_t c, int64_t hw, int64_t o,
-                               const int8_t *wq, const int32_t *corr, const float *out_scale,
+                               const int8_t *wq, const int64_t *corr, const float *out_scale,
                                float *y)
 {
     for (int64_t in = 0; in < n; ++in) {
         for (int64_t io = 0; io < o; ++io) {
             for (int64_t k = 0; k < hw; ++k) {
-                int32_t acc = 0;
+                int64_t acc = 0;
                 for (int64_t ic = 0; ic < c; ++ic)
-                    acc += (int32_t)wq[io * c + ic] * (int32_t)codes[(in * c + ic) * hw + k];
+                    acc += (int64_t)wq[io * c + ic] * (int64_t)codes[(in * c + ic) * hw + k];
                 y[(in * o + io) * hw + k] = out_scale[io] * (float)(acc - corr[io]);
             }
         }
+    }
+}
+
+/*
+ * Codes of at most four bits, two per byte (the integer operands of Eq. 3 stored at their own
+ * width): byte i holds the code q of Eq. 1 of the element with flat index 2i in its low
+ * nibble and that of element 2i + 1 in its high nibble; an odd element count leaves the last
+ * high nibble 0.  `codes` are the one-byte codes of the forward, each below 16.
+ */
+void granq_oracle_pack4(const uint8_t *codes, int64_t total, uint8_t *packed)
+{
+    for (int64_t i = 0; i < (total + 1) / 2; ++i) {
+        uint8_t lo = codes[2 * i];
+        uint8_t hi = 2 * i + 1 < total ? codes[2 * i + 1] : 0;
+        packed[i] = (uint8_t)(lo | (hi << 4));
+    }
+}
+
+/* The inverse: one byte per code again. */
+void granq_oracle_unpack4(const uint8_t *packed, int64_t total, uint8_t *codes)
+{
+    for (int64_t i = 0; i < total; ++i) {
+        uint8_t byte = packed[i / 2];
+        codes[i] = (i % 2 == 0) ? (uint8_t)(byte & 0x0F) : (uint8_t)(byte >> 4);
     }
 }

@@ -567,6 +567,44 @@ def check_integer_accumulation(lib=None):
     _eq(y2, want2.astype(np.float32), "exact integer case")
 
 
+def check_large_zero_point_term(lib=None):
+    """A channel range far from zero ([1000, 1001] at 4 bits: z = -15000) over many channels:
+    the zero-point term of Eq. 3 exceeds 32 bits and must still be exact."""
+    c = 2048
+    s = np.full(c, 1.0 / 15.0, np.float32)
+    z = np.full(c, -15000.0, np.float32)
+    w = np.full((2, c), 1.0, np.float32)
+    w[1] = -1.0
+    wq, corr, a = oracle.fold_weights(w, s, z, lib)
+    assert np.all(wq[0] == 127) and np.all(wq[1] == -127)
+    assert corr[0] == 127 * -15000 * c and corr[1] == -127 * -15000 * c and abs(int(corr[0])) > 2 ** 31
+    codes = np.full((1, c, 1, 2), 3, np.uint8)
+    codes[0, :, 0, 1] = 12
+    y = oracle.conv1x1_int8(codes, wq, corr, a, lib)
+    exact = np.array([[127 * c * (3 + 15000), 127 * c * (12 + 15000)], [-127 * c * (3 + 15000), -127 * c * (12 + 15000)]], np.int64)
+    _eq(y.reshape(2, 2), (a.reshape(2, 1) * exact.astype(np.float32)).astype(np.float32), "zero-point term beyond 32 bits")
+
+
+def check_packed_codes(lib=None):
+    """Two codes per byte: a hand-written example, the round trip on random codes of every
+    width up to four bits and odd counts, and the layout against numpy bit operations."""
+    _eq(oracle.pack4(np.array([0, 7, 3, 5, 1], np.uint8), lib), np.array([0x70, 0x53, 0x01], np.uint8), "hand-packed example")
+    _eq(oracle.unpack4(np.array([0x70, 0x53, 0x01], np.uint8), 5, lib), np.array([0, 7, 3, 5, 1], np.uint8), "hand-unpacked example")
+    rng = np.random.default_rng(5)
+    for bits in (1, 2, 3, 4):
+        for total in (1, 2, 7, 64, 1001):
+            codes = rng.integers(0, 2 ** bits, size=total).astype(np.uint8)
+            packed = oracle.pack4(codes, lib)
+            assert packed.size == (total + 1) // 2
+            padded = np.concatenate([codes, np.zeros(total % 2, np.uint8)])
+            _eq(packed, padded[0::2] | (padded[1::2] << 4), "nibble layout")
+            _eq(oracle.unpack4(packed, total, lib), codes, "round trip")
+    # on a quantized tensor: the packed codes are the forward's codes, nothing else
+    x = _workload_tensor("linear", (2, 5, 3, 3), seed=9)
+    _, codes, _, _ = oracle.fakequant(x, 4, lib)
+    _eq(oracle.unpack4(oracle.pack4(codes, lib), codes.size, lib), codes.ravel(), "codes of a tensor")
+
+
 ALL_CHECKS = [
     check_golden,
     check_dyadic_grid_exhaustive,
@@ -585,4 +623,6 @@ ALL_CHECKS = [
     check_accumulation_forms,
     check_distortion_metrics,
     check_integer_accumulation,
+    check_large_zero_point_term,
+    check_packed_codes,
 ]

@@ -49,9 +49,13 @@ MUTANTS = [
     ("distortion_single_precision_sums", "double xq = 0.0, xx = 0.0, qq = 0.0, dd = 0.0;", "float xq = 0.0, xx = 0.0, qq = 0.0, dd = 0.0;", 1),
     ("fold_forgets_activation_scale", "float ws = w[io * c + ic] * scale[ic];\n            if (fabsf(ws) > amax)", "float ws = w[io * c + ic];\n            if (fabsf(ws) > amax)", 1),
     ("fold_step_over_128", "float a = amax / 127.0f;", "float a = amax / 128.0f;", 1),
-    ("fold_correction_sign", "cz += (int32_t)q * (int32_t)zero_point[ic];", "cz -= (int32_t)q * (int32_t)zero_point[ic];", 1),
+    ("fold_correction_sign", "cz += (int64_t)q * (int64_t)zero_point[ic];", "cz -= (int64_t)q * (int64_t)zero_point[ic];", 1),
+    ("fold_correction_in_32_bits", "cz += (int64_t)q * (int64_t)zero_point[ic];", "cz = (int64_t)(int32_t)(uint32_t)(cz + (int64_t)q * (int64_t)zero_point[ic]);", 1),
+    ("pack4_high_nibble_first", "packed[i] = (uint8_t)(lo | (hi << 4));", "packed[i] = (uint8_t)(hi | (lo << 4));", 1),
+    ("pack4_odd_tail_repeats_last", "uint8_t hi = 2 * i + 1 < total ? codes[2 * i + 1] : 0;", "uint8_t hi = 2 * i + 1 < total ? codes[2 * i + 1] : codes[2 * i];", 1),
+    ("unpack4_nibbles_swapped", "codes[i] = (i % 2 == 0) ? (uint8_t)(byte & 0x0F) : (uint8_t)(byte >> 4);", "codes[i] = (i % 2 == 1) ? (uint8_t)(byte & 0x0F) : (uint8_t)(byte >> 4);", 1),
     ("conv_correction_added", "(float)(acc - corr[io])", "(float)(acc + corr[io])", 1),
-    ("conv_weights_transposed", "acc += (int32_t)wq[io * c + ic] * (int32_t)codes[(in * c + ic) * hw + k];", "acc += (int32_t)wq[ic * o + io] * (int32_t)codes[(in * c + ic) * hw + k];", 1),
+    ("conv_weights_transposed", "acc += (int64_t)wq[io * c + ic] * (int64_t)codes[(in * c + ic) * hw + k];", "acc += (int64_t)wq[ic * o + io] * (int64_t)codes[(in * c + ic) * hw + k];", 1),
     ("bf16_ties_round_up", "(dropped == 0x8000u && (kept & 1u))", "(dropped == 0x8000u)", 1),
     ("bf16_truncates", "if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))", "if (0)", 1),
     ("f16_ties_round_up", "double steps = rint(ldexp((double)a, 10 - e));", "double steps = floor(ldexp((double)a, 10 - e) + 0.5);", 1),
