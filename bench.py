@@ -432,10 +432,11 @@ def integer_accumulation(wl, bits, device):
         codes = torch.empty(shape, dtype=torch.uint8, device=device)
         q.forward(x, xh, codes, stream)
         t_q = _timeit(lambda: G.granq_fakequant_fwd(x, q.scale, q.zero_point, bits, None, codes, stream, q.desc))
+        x_keep = x
         del x
         wt = workloads.make_weight((o, c, 1, 1), 3, device)
         wq = torch.empty(o, c, dtype=torch.int8, device=device)
-        corr = torch.empty(o, dtype=torch.int32, device=device)
+        corr = torch.empty(o, dtype=torch.int64, device=device)
         a = torch.empty(o, device=device)
         y = torch.empty(shape[0], o, hw, hw, device=device)
         t_fold = _timeit(lambda: G.granq_fold_weights(wt, q.scale, q.zero_point, wq, corr, a, stream))
@@ -443,6 +444,14 @@ def integer_accumulation(wl, bits, device):
         y16 = torch.empty(shape[0], o, hw, hw, dtype=torch.bfloat16, device=device)
         t_int16 = _timeit(lambda: G.granq_conv1x1_int8_as(codes, wq, corr, a, bits, y16, stream))
         del y16
+        # codes two per byte (4-bit and below): half a byte per element written and read
+        packed = torch.empty(G.granq_packed4_bytes(q.desc), dtype=torch.uint8, device=device)
+        t_qp = t_intp = None
+        if bits <= 4:
+            t_qp = _timeit(lambda: G.granq_fakequant_fwd_packed4(x_keep, q.scale, q.zero_point, bits, None, packed, stream, q.desc))
+            t_intp = _timeit(lambda: G.granq_conv1x1_int8_packed4(packed, shape, wq, corr, a, bits, y, stream))
+            G.granq_conv1x1_int8(codes, wq, corr, a, bits, y, stream)
+        del x_keep, packed
         t_f32 = _timeit(lambda: torch.nn.functional.conv2d(xh, wt))
         ref = torch.nn.functional.conv2d(xh, wt)
         rel = float((y - ref).norm() / ref.norm())
@@ -456,6 +465,8 @@ def integer_accumulation(wl, bits, device):
             "int8_TOPs": round(ops / t_int / 1e6, 2), "int8_mfma_bf16_output_us": round(t_int16, 1),
             "fold_weights_us": round(t_fold, 1),
             "quantize_to_codes_only_us": round(t_q, 1), "quantize_GBs": round(e * 5 / t_q / 1e3, 1),
+            "quantize_to_packed_codes_only_us": round(t_qp, 1) if t_qp else None,
+            "int8_mfma_from_packed_codes_us": round(t_intp, 1) if t_intp else None,
             "torch_f32_conv_on_x_hat_us": round(t_f32, 1), "torch_bf16_conv_on_bf16_x_hat_us": round(t_b16, 1),
             "relative_difference_to_float_conv": round(rel, 5)}
         del xh, xh16, codes, y

@@ -363,22 +363,27 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc,
  *     out_scale[o] = max_c |w'[o,c]| / 127                  (1 if the row is all zero)
  *     wq[o,c]      = clamp(round_half_even(w'[o,c] / out_scale[o]), -127, 127)
  *     corr[o]      = sum_c wq[o,c] * (int) zero_point[c]    (Eq. 3's - z_c, summed once)
- * so that y approximates sum_c w[o,c] * x_hat[n,c,k] (Eq. 6) up to the rounding of w'.
+ * so that y approximates sum_c w[o,c] * x_hat[n,c,k] (Eq. 6) up to the rounding of w'.  (The
+ * symmetric int8 rounding of a whole row is this library's construction, not the paper's: a
+ * channel whose scale is far below the row's largest folds to small or zero weights.)
  *   w [in] o*c floats; scale, zero_point [in] c floats; wq [out] o*c int8; corr [out] o
- *   int32; out_scale [out] o floats.  zero_point must hold integers of magnitude < 2^23.
+ *   int64, 8-byte aligned (an exact integer sum: with zero-points of magnitude up to 2^24 and
+ *   up to 65535 channels it does not fit 32 bits); out_scale [out] o floats.
+ *   zero_point must hold integers of magnitude < 2^24, c < 65536.
  *
  * granq_conv1x1_int8: codes [in] N*C*H*W bytes as written by granq_fakequant_fwd (desc
  * gives n, c, h, w; its dtype is ignored); y [out] N*O*H*W floats, NCHW with O channels.
+ * The integer expression sum - corr is exact; it is rounded to binary32 once, then scaled.
  * The matrix-core kernel needs codes <= 127 (bits <= 7), C a multiple of 16, O a multiple
  * of 32, H*W a multiple of 4, C*H*W < 2^25, 4-byte aligned codes and 16-byte aligned wq
  * and y; anything else runs a plain integer kernel with identical results.
  */
 granq_status_t granq_fold_weights(const float *w, const float *scale, const float *zero_point,
-                                  int64_t o, int64_t c, int8_t *wq, int32_t *corr,
+                                  int64_t o, int64_t c, int8_t *wq, int64_t *corr,
                                   float *out_scale, void *stream);
 
 granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
-                                  const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                  const int8_t *wq, const int64_t *corr, const float *out_scale,
                                   int bits, float *y, void *stream);
 
 /*
@@ -388,8 +393,34 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
  * halves its time.  The matrix-core path then needs y 8-byte aligned.
  */
 granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
-                                     const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                     const int8_t *wq, const int64_t *corr, const float *out_scale,
                                      int bits, granq_dtype_t y_dtype, void *y, void *stream);
+
+/*
+ * Codes at their own width: for bits <= 4 the code q of Eq. 1 fits a nibble, and the integer
+ * operands of Eq. 3 can be stored two per byte -- half a byte per element written by the
+ * quantize step and read by the convolution.
+ * Layout: byte i holds the code of the element with flat NCHW index 2i in its low nibble and
+ * that of element 2i + 1 in its high nibble; with an odd element count the last high nibble
+ * is 0.  granq_packed4_bytes (host-only) returns ceil(N*C*H*W / 2).
+ *
+ * granq_fakequant_fwd_packed4 = granq_fakequant_fwd with the codes stored that way
+ * (bits in 1..4, else GRANQ_ERR_INVALID_ARG).  x_hat may be NULL (codes only: the quantize
+ * step alone, 4.5 bytes moved per float32 element) or alias x.  The vectorised kernels need
+ * `packed` 2-byte aligned for float32 and 4-byte aligned for 16-bit tensors.
+ *
+ * granq_conv1x1_int8_packed4 = granq_conv1x1_int8_as reading such codes; identical results.
+ * Its matrix-core path needs 2-byte aligned codes besides the conditions above.
+ */
+granq_status_t granq_packed4_bytes(const granq_desc_t *desc, size_t *bytes_out);
+
+granq_status_t granq_fakequant_fwd_packed4(const void *x, const granq_desc_t *desc,
+                                           const float *scale, const float *zero_point, int bits,
+                                           void *x_hat_or_null, uint8_t *packed, void *stream);
+
+granq_status_t granq_conv1x1_int8_packed4(const uint8_t *packed, const granq_desc_t *desc, int64_t o,
+                                          const int8_t *wq, const int64_t *corr, const float *out_scale,
+                                          int bits, granq_dtype_t y_dtype, void *y, void *stream);
 
 #ifdef __cplusplus
 }

@@ -32,7 +32,8 @@ EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "gra
            "granq_calibrate_fakequant_fwd_resident", "granq_fakequant_fwd", "granq_fakequant_bwd", "granq_mask_bytes",
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
            "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
-           "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_as")
+           "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_as", "granq_packed4_bytes",
+           "granq_fakequant_fwd_packed4", "granq_conv1x1_int8_packed4")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -103,6 +104,9 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_fold_weights.argtypes = [_vp, _vp, _vp, ctypes.c_int64, ctypes.c_int64, _vp, _vp, _vp, _vp]
     lib.granq_conv1x1_int8.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, _vp, _vp]
     lib.granq_conv1x1_int8_as.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int, _vp, _vp]
+    lib.granq_packed4_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.granq_fakequant_fwd_packed4.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
+    lib.granq_conv1x1_int8_packed4.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int, _vp, _vp]
     lib.granq_distortion_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_distortion.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -418,8 +422,8 @@ def granq_fold_weights(w: torch.Tensor, scale: torch.Tensor, zero_point: torch.T
     o, c = int(w.shape[0]), w.numel() // int(w.shape[0])
     if w.dtype != torch.float32 or wq.dtype != torch.int8 or wq.numel() != o * c:
         raise ValueError("w must be float32 (O, C) and wq int8 of the same size")
-    if corr.dtype != torch.int32 or corr.numel() != o:
-        raise ValueError("corr must be int32 with O entries")
+    if corr.dtype != torch.int64 or corr.numel() != o:
+        raise ValueError("corr must be int64 with O entries")
     _check(load().granq_fold_weights(_dev(w, "w"), _vec(scale, c, "scale"), _vec(zero_point, c, "zero_point"),
                                      o, c, _dev(wq, "wq"), _dev(corr, "corr"), _vec(out_scale, o, "out_scale"),
                                      _stream(stream)), "granq_fold_weights")
@@ -431,8 +435,8 @@ def granq_conv1x1_int8(codes: torch.Tensor, wq: torch.Tensor, corr: torch.Tensor
         raise ValueError("codes must be a uint8 (N, C, H, W) tensor")
     n, c, h, w = (int(v) for v in codes.shape)
     o = int(wq.shape[0])
-    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int32 or corr.numel() != o:
-        raise ValueError("wq must be int8 (O, C) and corr int32 (O)")
+    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int64 or corr.numel() != o:
+        raise ValueError("wq must be int8 (O, C) and corr int64 (O)")
     if y.dtype != torch.float32 or y.numel() != n * o * h * w:
         raise ValueError("y must be float32 (N, O, H, W)")
     d = make_desc(n, c, h, w, GRANQ_F32)
@@ -448,8 +452,8 @@ def granq_conv1x1_int8_as(codes: torch.Tensor, wq: torch.Tensor, corr: torch.Ten
         raise ValueError("codes must be a uint8 (N, C, H, W) tensor")
     n, c, h, w = (int(v) for v in codes.shape)
     o = int(wq.shape[0])
-    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int32 or corr.numel() != o:
-        raise ValueError("wq must be int8 (O, C) and corr int32 (O)")
+    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int64 or corr.numel() != o:
+        raise ValueError("wq must be int8 (O, C) and corr int64 (O)")
     if y.numel() != n * o * h * w:
         raise ValueError("y must have N*O*H*W elements")
     d = make_desc(n, c, h, w, GRANQ_F32)
@@ -457,6 +461,46 @@ def granq_conv1x1_int8_as(codes: torch.Tensor, wq: torch.Tensor, corr: torch.Ten
                                         _dev(corr, "corr"), _vec(out_scale, o, "out_scale"), int(bits),
                                         dtype_code(y.dtype), _dev(y, "y"), _stream(stream)),
            "granq_conv1x1_int8_as")
+
+
+def granq_packed4_bytes(desc: granq_desc_t) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().granq_packed4_bytes(ctypes.byref(desc), ctypes.byref(out)), "granq_packed4_bytes")
+    return int(out.value)
+
+
+def granq_fakequant_fwd_packed4(x: torch.Tensor, scale: torch.Tensor, zero_point: torch.Tensor, bits: int,
+                                x_hat: Optional[torch.Tensor], packed: torch.Tensor, stream=None,
+                                desc: Optional[granq_desc_t] = None) -> None:
+    """The forward with its codes stored two per byte (bits <= 4); x_hat None: codes only."""
+    d = _desc_for(x, desc)
+    if x_hat is not None and (x_hat.dtype != x.dtype or x_hat.numel() != x.numel()):
+        raise ValueError("x_hat must match x")
+    if packed.dtype != torch.uint8 or packed.numel() < (x.numel() + 1) // 2:
+        raise ValueError("packed must be uint8 with at least ceil(numel / 2) entries")
+    _check(load().granq_fakequant_fwd_packed4(_dev(x, "x"), ctypes.byref(d), _vec(scale, d.c, "scale"),
+                                              _vec(zero_point, d.c, "zero_point"), int(bits),
+                                              _dev(x_hat, "x_hat") if x_hat is not None else 0,
+                                              _dev(packed, "packed"), _stream(stream)),
+           "granq_fakequant_fwd_packed4")
+
+
+def granq_conv1x1_int8_packed4(packed: torch.Tensor, shape, wq: torch.Tensor, corr: torch.Tensor,
+                               out_scale: torch.Tensor, bits: int, y: torch.Tensor, stream=None) -> None:
+    """granq_conv1x1_int8_as on codes stored two per byte; `shape` = (N, C, H, W) of the codes."""
+    n, c, h, w = (int(v) for v in shape)
+    o = int(wq.shape[0])
+    if packed.dtype != torch.uint8 or packed.numel() < (n * c * h * w + 1) // 2:
+        raise ValueError("packed must be uint8 with at least ceil(N*C*H*W / 2) entries")
+    if wq.dtype != torch.int8 or wq.numel() != o * c or corr.dtype != torch.int64 or corr.numel() != o:
+        raise ValueError("wq must be int8 (O, C) and corr int64 (O)")
+    if y.numel() != n * o * h * w:
+        raise ValueError("y must have N*O*H*W elements")
+    d = make_desc(n, c, h, w, GRANQ_F32)
+    _check(load().granq_conv1x1_int8_packed4(_dev(packed, "packed"), ctypes.byref(d), o, _dev(wq, "wq"),
+                                             _dev(corr, "corr"), _vec(out_scale, o, "out_scale"), int(bits),
+                                             dtype_code(y.dtype), _dev(y, "y"), _stream(stream)),
+           "granq_conv1x1_int8_packed4")
 
 
 def granq_distortion_workspace_bytes(desc: granq_desc_t) -> int:

@@ -82,9 +82,11 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // channels are issued before the matrix instructions of the current ones, and
 // scheduling barriers keep them there.
 // OutT: storage of y (F32, BF16 or F16 traits): the binary32 result is narrowed on the store.
-template <typename OutT>
+// PACKED: the codes are two per byte; a lane then fetches its four pixels of a channel as one
+// 16-bit load and spreads the nibbles into bytes (six integer operations) before the transpose.
+template <typename OutT, bool PACKED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
-    const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
+    const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
     int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride)
 {
@@ -109,9 +111,11 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const int64_t n_first = g_first < groups_total ? g_first / hw4 : 0;
     // raw buffer over the codes from the wavefront's first sample on: loads take the form
     // resource (scalar) + channel offset (scalar) + lane offset (one vector register)
+    // (two codes per byte: every offset below is even, since hw is a multiple of 4)
+    constexpr int kPerByte = PACKED ? 2 : 1;
     const __amdgpu_buffer_rsrc_t code_buf = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(codes + n_first * c * hw), 0, 0x7fffffff, 0x00020000);
-    const uint32_t lane_off = live ? (uint32_t)((n - n_first) * c * hw + pb + 16 * half * hw) : 0u;
+        (void *)(codes + n_first * c * hw / kPerByte), 0, 0x7fffffff, 0x00020000);
+    const uint32_t lane_off = live ? (uint32_t)(((n - n_first) * c * hw + pb + 16 * half * hw) / kPerByte) : 0u;
 
     const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
     const int64_t s0 = (int64_t)split * sweeps_per_block;
@@ -158,14 +162,22 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
                 const int off = (int)(ok ? lane_off : 0u);                                   \
                 const int64_t ch0c = ch0 < c - 16 ? ch0 : c - 16;                            \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i)                               \
-                    d[i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(                   \
-                        code_buf, off, (int)((ch0c + i) * hw), 0);                           \
+                    d[i] = PACKED ? (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(    \
+                                        code_buf, off, (int)((ch0c + i) * hw / 2), 0)        \
+                                  : (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(          \
+                                        code_buf, off, (int)((ch0c + i) * hw), 0);           \
             }
 #define GRANQ_CONV_MULTIPLY(d, k)                                                            \
             {                                                                                \
                 const bool ok = live && kc0 + (k) + 16 * half < c;                           \
-                _Pragma("unroll") for (int i = 0; i < 16; ++i)                               \
-                    d[i] = ok ? d[i] : 0u;                                                   \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) {                             \
+                    uint32_t t = ok ? d[i] : 0u;                                             \
+                    if (PACKED) {                      /* nibble i -> byte i */              \
+                        t = (t | (t << 8)) & 0x00FF00FFu;                                    \
+                        t = (t | (t << 4)) & 0x0F0F0F0Fu;                                    \
+                    }                                                                        \
+                    d[i] = t;                                                                \
+                }                                                                            \
                 i32x4 b[4];                                                                  \
                 transpose_16x4(d, b);                                                        \
                 const i32x4 a0 = *(const i32x4 *)(a_row0 + (k));                             \
@@ -197,13 +209,15 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
-                const int32_t cz = corr[oc];
+                // the difference is exact in binary64 (|corr| < 2^48), so narrowing it rounds once:
+                // the same value as the conversion of the 64-bit integer difference
+                const double cz = (double)corr[oc];
                 const float sc = out_scale[oc];
                 f32x4 v;
-                v.x = sc * (float)(acc[t][0][r] - cz);
-                v.y = sc * (float)(acc[t][1][r] - cz);
-                v.z = sc * (float)(acc[t][2][r] - cz);
-                v.w = sc * (float)(acc[t][3][r] - cz);
+                v.x = sc * (float)((double)acc[t][0][r] - cz);
+                v.y = sc * (float)((double)acc[t][1][r] - cz);
+                v.z = sc * (float)((double)acc[t][2][r] - cz);
+                v.w = sc * (float)((double)acc[t][3][r] - cz);
                 store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
             }
         }
@@ -211,18 +225,22 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
 }
 
 // Any shape: one thread per output element, integer loop over the channels.
-template <typename OutT>
+// PACKED: the codes are two per byte (element i in nibble i & 1 of byte i >> 1).
+template <typename OutT, bool PACKED>
 __global__ __launch_bounds__(kBlock) void conv1x1_i8_plain(
-    const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int32_t *__restrict__ corr,
+    const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o)
 {
     const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int64_t oc = blockIdx.y;
     const int64_t n = blockIdx.z;
     if (k >= hw) return;
-    int32_t acc = 0;
-    for (int64_t ic = 0; ic < c; ++ic)
-        acc += (int32_t)wq[oc * c + ic] * (int32_t)codes[(n * c + ic) * hw + k];
+    int64_t acc = 0;
+    for (int64_t ic = 0; ic < c; ++ic) {
+        const int64_t at = (n * c + ic) * hw + k;
+        const int32_t code = PACKED ? ((codes[at >> 1] >> (4 * (at & 1))) & 15) : codes[at];
+        acc += (int64_t)((int32_t)wq[oc * c + ic] * code);
+    }
     OutT::store1(y, (n * o + oc) * hw + k, out_scale[oc] * (float)(acc - corr[oc]));
 }
 
@@ -230,10 +248,10 @@ __global__ __launch_bounds__(kBlock) void conv1x1_i8_plain(
 // quantize the row to int8 (symmetric), sum the zero-point term.
 __global__ __launch_bounds__(kBlock) void fold_weights_kernel(
     const float *__restrict__ w, const float *__restrict__ scale, const float *__restrict__ zero_point,
-    int64_t c, int8_t *__restrict__ wq, int32_t *__restrict__ corr, float *__restrict__ out_scale)
+    int64_t c, int8_t *__restrict__ wq, int64_t *__restrict__ corr, float *__restrict__ out_scale)
 {
     __shared__ float part[kBlock / kWave];
-    __shared__ int32_t ipart[kBlock / kWave];
+    __shared__ int64_t ipart[kBlock / kWave];
     const int64_t oc = blockIdx.x;
     float amax = 0.0f;
     for (int64_t ic = threadIdx.x; ic < c; ic += kBlock) {
@@ -247,21 +265,21 @@ __global__ __launch_bounds__(kBlock) void fold_weights_kernel(
     for (int i = 1; i < kBlock / kWave; ++i) amax = __builtin_fmaxf(amax, part[i]);
     float a = amax / 127.0f;
     if (!(a > 0.0f)) a = 1.0f;
-    int32_t cz = 0;
+    int64_t cz = 0;                                    // exact: |wq| <= 127, |z| < 2^24, c < 2^16
     for (int64_t ic = threadIdx.x; ic < c; ic += kBlock) {
         const float ws = w[oc * c + ic] * scale[ic];
         float q = __builtin_rintf(ws / a);
         q = __builtin_fminf(__builtin_fmaxf(q, -127.0f), 127.0f);
         const int32_t qi = (int32_t)q;
         wq[oc * c + ic] = (int8_t)qi;
-        cz += qi * (int32_t)zero_point[ic];
+        cz += (int64_t)qi * (int64_t)zero_point[ic];
     }
 #pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) cz += __shfl_xor(cz, off, kWave);
+    for (int off = kWave / 2; off > 0; off >>= 1) cz += (int64_t)__shfl_xor((long long)cz, off, kWave);
     if ((threadIdx.x & (kWave - 1)) == 0) ipart[threadIdx.x / kWave] = cz;
     __syncthreads();
     if (threadIdx.x == 0) {
-        int32_t t = 0;
+        int64_t t = 0;
         for (int i = 0; i < kBlock / kWave; ++i) t += ipart[i];
         corr[oc] = t;
         out_scale[oc] = a;
@@ -272,39 +290,24 @@ __global__ __launch_bounds__(kBlock) void fold_weights_kernel(
 
 using namespace granq;
 
-extern "C" {
-
-granq_status_t granq_fold_weights(const float *w, const float *scale, const float *zero_point,
-                                  int64_t o, int64_t c, int8_t *wq, int32_t *corr, float *out_scale,
-                                  void *stream) {
-    if (!w || !scale || !zero_point || !wq || !corr || !out_scale) return GRANQ_ERR_INVALID_ARG;
-    if (o <= 0 || c <= 0) return GRANQ_ERR_INVALID_ARG;
-    if (o >= ((int64_t)1 << 31) || c >= ((int64_t)1 << 24)) return GRANQ_ERR_UNSUPPORTED;
-    if (((uintptr_t)w & 3u) || ((uintptr_t)scale & 3u) || ((uintptr_t)zero_point & 3u) ||
-        ((uintptr_t)corr & 3u) || ((uintptr_t)out_scale & 3u))
-        return GRANQ_ERR_UNSUPPORTED;
-    launch_kernel(fold_weights_kernel, dim3((uint32_t)o), dim3(kBlock), 0, (hipStream_t)stream,
-                       w, scale, zero_point, c, wq, corr, out_scale);
-    return launched();
-}
-
 // y_dtype: storage of y; the binary32 result is narrowed (round to nearest even) on the store.
+template <bool PACKED>
 static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
-                                const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                const int8_t *wq, const int64_t *corr, const float *out_scale,
                                 int bits, granq_dtype_t y_dtype, void *y, void *stream) {
     if (!desc || !codes || !wq || !corr || !out_scale || !y) return GRANQ_ERR_INVALID_ARG;
     if (desc->n <= 0 || desc->c <= 0 || desc->h <= 0 || desc->w <= 0 || o <= 0) return GRANQ_ERR_INVALID_ARG;
-    if (bits < 1 || bits > 8) return GRANQ_ERR_INVALID_ARG;
+    if (bits < 1 || bits > (PACKED ? 4 : 8)) return GRANQ_ERR_INVALID_ARG;
     if (y_dtype != GRANQ_F32 && y_dtype != GRANQ_BF16 && y_dtype != GRANQ_F16) return GRANQ_ERR_UNSUPPORTED;
     const int64_t c = desc->c, hw = desc->h * desc->w, n = desc->n;
     // |sum| <= 127 * 255 * C must stay inside int32
     if (c >= ((int64_t)1 << 16) || o >= 65536 || n >= 65536 || hw >= ((int64_t)1 << 40)) return GRANQ_ERR_UNSUPPORTED;
     const uintptr_t esize = y_dtype == GRANQ_F32 ? 4 : 2;
-    if (((uintptr_t)corr & 3u) || ((uintptr_t)out_scale & 3u) || ((uintptr_t)y & (esize - 1))) return GRANQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)corr & 7u) || ((uintptr_t)out_scale & 3u) || ((uintptr_t)y & (esize - 1))) return GRANQ_ERR_UNSUPPORTED;
     hipStream_t hs = (hipStream_t)stream;
     // a lane stores four neighbouring pixels at once
     const bool mfma = bits <= 7 && c % 16 == 0 && o % 32 == 0 && hw % 4 == 0 && c * hw < ((int64_t)1 << 25) &&
-                      ((uintptr_t)codes & 3u) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0;
+                      ((uintptr_t)codes & (PACKED ? 1u : 3u)) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0;
     if (mfma) {
         const int64_t groups_total = n * (hw / 4);
         const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));
@@ -324,37 +327,59 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         dim3 grid((uint32_t)blocks), block(kBlock);
         if (y_dtype == GRANQ_F32)
-            launch_kernel(conv1x1_i8_mfma<F32>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+            launch_kernel((conv1x1_i8_mfma<F32, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
                                groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         else if (y_dtype == GRANQ_BF16)
-            launch_kernel(conv1x1_i8_mfma<BF16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+            launch_kernel((conv1x1_i8_mfma<BF16, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
                                groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         else
-            launch_kernel(conv1x1_i8_mfma<F16>, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
+            launch_kernel((conv1x1_i8_mfma<F16, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
                                groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
         if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
         return GRANQ_OK;
     }
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)o, (uint32_t)n), block(kBlock);
     if (y_dtype == GRANQ_F32)
-        launch_kernel(conv1x1_i8_plain<F32>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+        launch_kernel((conv1x1_i8_plain<F32, PACKED>), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
     else if (y_dtype == GRANQ_BF16)
-        launch_kernel(conv1x1_i8_plain<BF16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+        launch_kernel((conv1x1_i8_plain<BF16, PACKED>), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
     else
-        launch_kernel(conv1x1_i8_plain<F16>, grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+        launch_kernel((conv1x1_i8_plain<F16, PACKED>), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+    return launched();
+}
+
+extern "C" {
+
+granq_status_t granq_fold_weights(const float *w, const float *scale, const float *zero_point,
+                                  int64_t o, int64_t c, int8_t *wq, int64_t *corr, float *out_scale,
+                                  void *stream) {
+    if (!w || !scale || !zero_point || !wq || !corr || !out_scale) return GRANQ_ERR_INVALID_ARG;
+    if (o <= 0 || c <= 0) return GRANQ_ERR_INVALID_ARG;
+    if (o >= ((int64_t)1 << 31) || c >= ((int64_t)1 << 16)) return GRANQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)w & 3u) || ((uintptr_t)scale & 3u) || ((uintptr_t)zero_point & 3u) ||
+        ((uintptr_t)corr & 7u) || ((uintptr_t)out_scale & 3u))
+        return GRANQ_ERR_UNSUPPORTED;
+    launch_kernel(fold_weights_kernel, dim3((uint32_t)o), dim3(kBlock), 0, (hipStream_t)stream,
+                       w, scale, zero_point, c, wq, corr, out_scale);
     return launched();
 }
 
 granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
-                                  const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                  const int8_t *wq, const int64_t *corr, const float *out_scale,
                                   int bits, float *y, void *stream) {
-    return conv_impl(codes, desc, o, wq, corr, out_scale, bits, GRANQ_F32, y, stream);
+    return conv_impl<false>(codes, desc, o, wq, corr, out_scale, bits, GRANQ_F32, y, stream);
 }
 
 granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
-                                     const int8_t *wq, const int32_t *corr, const float *out_scale,
+                                     const int8_t *wq, const int64_t *corr, const float *out_scale,
                                      int bits, granq_dtype_t y_dtype, void *y, void *stream) {
-    return conv_impl(codes, desc, o, wq, corr, out_scale, bits, y_dtype, y, stream);
+    return conv_impl<false>(codes, desc, o, wq, corr, out_scale, bits, y_dtype, y, stream);
+}
+
+granq_status_t granq_conv1x1_int8_packed4(const uint8_t *packed, const granq_desc_t *desc, int64_t o,
+                                          const int8_t *wq, const int64_t *corr, const float *out_scale,
+                                          int bits, granq_dtype_t y_dtype, void *y, void *stream) {
+    return conv_impl<true>(packed, desc, o, wq, corr, out_scale, bits, y_dtype, y, stream);
 }
 
 }  // extern "C"

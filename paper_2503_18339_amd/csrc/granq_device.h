@@ -46,6 +46,11 @@ struct F32 {
     __device__ static inline code_t pack_codes(const float (&q)[VEC]) {
         return (uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) | ((uint32_t)q[3] << 24);
     }
+    // codes below 16, two per byte, element i in nibble i
+    using code4_t = uint16_t;
+    __device__ static inline code4_t pack_codes4(const float (&q)[VEC]) {
+        return (uint16_t)((uint32_t)q[0] | ((uint32_t)q[1] << 4) | ((uint32_t)q[2] << 8) | ((uint32_t)q[3] << 12));
+    }
     // keep element i of g where keep[i], else +0
     __device__ static inline vec_t gate(const vec_t &g, const bool (&keep)[VEC]) {
         vec_t r;
@@ -82,6 +87,13 @@ struct Pack16 {
         code_t c;
         c.x = (uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) | ((uint32_t)q[3] << 24);
         c.y = (uint32_t)q[4] | ((uint32_t)q[5] << 8) | ((uint32_t)q[6] << 16) | ((uint32_t)q[7] << 24);
+        return c;
+    }
+    using code4_t = uint32_t;       // 8 packed 4-bit codes, element i in nibble i
+    __device__ static inline code4_t pack_codes4(const float (&q)[VEC]) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) c |= (uint32_t)q[e] << (4 * e);
         return c;
     }
     __device__ static inline vec_t gate(const vec_t &g, const bool (&keep)[VEC]) {

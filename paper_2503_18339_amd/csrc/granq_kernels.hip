@@ -205,6 +205,8 @@ constexpr int kMask = 2;      // one bit per element: 1 where the clamp was inac
                               // straight-through gate), bit (i & 7) of byte (i >> 3), i the
                               // flat NCHW index
 constexpr int kCodesOnly = 3; // the codes, and x_hat is not written at all
+constexpr int kPacked = 4;    // codes of at most four bits, two per byte: element i in nibble (i & 1) of byte i >> 1
+constexpr int kPackedOnly = 5;// those, and x_hat is not written at all
 
 // Rows r .. r + nrows - 1 of this lane's vectors, all loads issued together.
 template <typename T, int V, int U, bool NT>
@@ -241,12 +243,14 @@ __device__ inline void fwd_finish_rows(const typename T::vec_t (&in)[U][V], type
                     q[e] = clamp_code(code, qmax);
                     // the clamp left the code alone <=> 0 <= code <= qmax (-0 == +0; NaN fails)
                     if (EXTRA == kMask) gate_bits |= (code == q[e] ? 1u : 0u) << e;
-                    if (EXTRA != kCodesOnly) f[e] = dequant(q[e], c.s, c.z);
+                    if (EXTRA != kCodesOnly && EXTRA != kPackedOnly) f[e] = dequant(q[e], c.s, c.z);
                 }
                 const int64_t at = (r + u) * row_vecs + cv[v];
-                if (EXTRA != kCodesOnly) store_vec(x_hat + at, T::pack(f));
+                if (EXTRA != kCodesOnly && EXTRA != kPackedOnly) store_vec(x_hat + at, T::pack(f));
                 if (EXTRA == kCodes || EXTRA == kCodesOnly)
                     store_vec((typename T::code_t *)extra + at, T::pack_codes(q));
+                if (EXTRA == kPacked || EXTRA == kPackedOnly)
+                    store_vec((typename T::code4_t *)extra + at, T::pack_codes4(q));
             }
             if (EXTRA == kMask && u < nrows) {         // wave-uniform condition: all lanes take part
                 // byte index of this lane's vector; VEC == 8: one byte per lane, VEC == 4: two
@@ -594,6 +598,40 @@ __global__ __launch_bounds__(kBlock) void mask_from_x_bytes(
             }
         }
         mask[b] = (uint8_t)bits;
+    }
+}
+
+// Any shape: one thread per packed byte (two consecutive elements): codes two per byte, and
+// x_hat where asked for (it may alias x: a thread reads its elements before it writes them).
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fwd_packed_bytes(
+    const void *x, void *x_hat, const float *__restrict__ scale, const float *__restrict__ zero_point,
+    float qmax, int64_t c, int64_t hw, int64_t total, uint8_t *__restrict__ packed)
+{
+    const int64_t nbytes = (total + 1) / 2;
+    for (int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x; b < nbytes; b += (int64_t)gridDim.x * kBlock) {
+        float xv[2], sv[2], zv[2];
+        uint32_t byte = 0;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int64_t i = b * 2 + k;
+            if (i < total) {
+                const int64_t ic = (i / hw) % c;
+                xv[k] = T::load1(x, i);
+                sv[k] = scale[ic];
+                zv[k] = zero_point[ic];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int64_t i = b * 2 + k;
+            if (i < total) {
+                const float q = clamp_code(raw_code(xv[k], sv[k], zv[k]), qmax);
+                byte |= (uint32_t)q << (4 * k);
+                if (x_hat) T::store1(x_hat, i, dequant(q, sv[k], zv[k]));
+            }
+        }
+        packed[b] = (uint8_t)byte;
     }
 }
 
@@ -1280,6 +1318,8 @@ static void launch_fwd_mode(const ColPlan &pl, const void *x, void *x_hat, void 
     auto xv = (const vec_t *)x;
     auto yv = (vec_t *)x_hat;
     if (kind == kCodes) launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodes>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else if (kind == kPacked) launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kPacked>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
+    else if (kind == kPackedOnly) launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kPackedOnly>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
     else if (kind == kCodesOnly) launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kCodesOnly>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
     else launch_kernel((fq_fwd_cols<T, V, GRANQ_F_ROWS, MODE, kNoExtra>), grid, block, 0, st, xv, yv, extra, s, z, qmax, pl);
 }
@@ -1703,6 +1743,46 @@ granq_status_t granq_fakequant_fwd(const void *x, const granq_desc_t *desc, cons
         launch_kernel(fq_fwd_rows<BF16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
     else
         launch_kernel(fq_fwd_rows<F16>, grid, block, 0, hs, x, x_hat, codes_or_null, scale, zero_point, qmax, slabs, desc->c, hw, rp.chunks, rp.chunk_len);
+    return launched();
+}
+
+granq_status_t granq_packed4_bytes(const granq_desc_t *desc, size_t *bytes_out) {
+    if (!bytes_out) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = check_desc(desc);
+    if (st != GRANQ_OK) return st;
+    *bytes_out = (size_t)((desc->n * desc->c * desc->h * desc->w + 1) / 2);
+    return GRANQ_OK;
+}
+
+granq_status_t granq_fakequant_fwd_packed4(const void *x, const granq_desc_t *desc, const float *scale,
+                                           const float *zero_point, int bits, void *x_hat_or_null,
+                                           uint8_t *packed, void *stream) {
+    if (!packed) return GRANQ_ERR_INVALID_ARG;
+    granq_status_t st = fwd_check(x, desc, scale, zero_point, bits, x_hat_or_null, packed);
+    if (st != GRANQ_OK) return st;
+    if (bits > 4) return GRANQ_ERR_INVALID_ARG;                     // a code must fit a nibble
+    const float qmax = (float)((1 << bits) - 1);
+    hipStream_t hs = (hipStream_t)stream;
+    ColPlan cp = fwd_plan(desc);
+    // a lane stores the nibbles of one vector at once: 2 bytes (float32) or 4 (16-bit types)
+    const bool packed_ok = ((uintptr_t)packed % (size_t)(vec_of(desc->dtype) / 2)) == 0;
+    if (cp.ok && aligned16(x) && (!x_hat_or_null || aligned16(x_hat_or_null)) && packed_ok) {
+        const int kind = x_hat_or_null ? kPacked : kPackedOnly;
+        if (desc->dtype == GRANQ_F32) launch_fwd_cols<F32, GRANQ_E_V_F32>(cp, x, x_hat_or_null, packed, kind, scale, zero_point, qmax, hs);
+        else if (desc->dtype == GRANQ_BF16) launch_fwd_cols<BF16, GRANQ_E_V_BF16>(cp, x, x_hat_or_null, packed, kind, scale, zero_point, qmax, hs);
+        else launch_fwd_cols<F16, GRANQ_E_V_BF16>(cp, x, x_hat_or_null, packed, kind, scale, zero_point, qmax, hs);
+        return launched();
+    }
+    const int64_t hw = desc->h * desc->w;
+    const int64_t total = desc->n * desc->c * hw;
+    const int64_t want = ceil_div(ceil_div(total, 2), kBlock);
+    dim3 grid((uint32_t)(want < GRANQ_ROW_TARGET_BLOCKS * 4 ? want : GRANQ_ROW_TARGET_BLOCKS * 4)), block(kBlock);
+    if (desc->dtype == GRANQ_F32)
+        launch_kernel(fwd_packed_bytes<F32>, grid, block, 0, hs, x, x_hat_or_null, scale, zero_point, qmax, desc->c, hw, total, packed);
+    else if (desc->dtype == GRANQ_BF16)
+        launch_kernel(fwd_packed_bytes<BF16>, grid, block, 0, hs, x, x_hat_or_null, scale, zero_point, qmax, desc->c, hw, total, packed);
+    else
+        launch_kernel(fwd_packed_bytes<F16>, grid, block, 0, hs, x, x_hat_or_null, scale, zero_point, qmax, desc->c, hw, total, packed);
     return launched();
 }
 

@@ -22,7 +22,7 @@ def _case(shape, o, bits, law="linear", seed=0):
     s = torch.from_numpy(out["scale"]).to(DEV)
     z = torch.from_numpy(out["zero_point"]).to(DEV)
     wq = torch.full((o, c), 99, dtype=torch.int8, device=DEV)
-    corr = torch.full((o,), 12345, dtype=torch.int32, device=DEV)
+    corr = torch.full((o,), 12345, dtype=torch.int64, device=DEV)
     a = torch.full((o,), float("nan"), device=DEV)
     G.granq_fold_weights(wt, s, z, wq, corr, a)
     codes = torch.from_numpy(out["codes"]).to(DEV)
@@ -74,7 +74,7 @@ def test_conv_output_in_16_bits(shape, o, bits, ydtype):
     s = torch.from_numpy(out["scale"]).to(DEV)
     z = torch.from_numpy(out["zero_point"]).to(DEV)
     wq = torch.empty((o, c), dtype=torch.int8, device=DEV)
-    corr = torch.empty((o,), dtype=torch.int32, device=DEV)
+    corr = torch.empty((o,), dtype=torch.int64, device=DEV)
     a = torch.empty((o,), device=DEV)
     G.granq_fold_weights(wt, s, z, wq, corr, a)
     codes = torch.from_numpy(out["codes"]).to(DEV)
@@ -119,3 +119,108 @@ def test_conv_argument_checks():
     assert lib.granq_conv1x1_int8(16, ctypes.byref(d), 32, 16, 18, 16, 4, 16, 0) == G.GRANQ_ERR_UNSUPPORTED
     assert lib.granq_fold_weights(16, 16, 16, 0, 4, 16, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_fold_weights(16, 16, 0, 4, 4, 16, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+
+
+def test_zero_point_term_beyond_32_bits():
+    """A range far from zero on every channel ([1000, 1001] at 4 bits: z = -15000) over 2048
+    channels: the zero-point term of Eq. 3 needs more than 32 bits; fold and both kernels exact."""
+    n, c, h, w, o = 2, 2048, 2, 4, 32
+    g = torch.Generator(device=DEV).manual_seed(3)
+    x = 1000.0 + torch.rand((n, c, h, w), generator=g, device=DEV)
+    x[0, :, 0, 0] = 1000.0
+    x[1, :, 1, 3] = 1001.0
+    out = gpu_path(x, 4)
+    assert np.all(out["zero_point"] <= -14000)
+    wt = torch.ones(o, c, device=DEV)
+    wt[1::2] = -1.0
+    s = torch.from_numpy(out["scale"]).to(DEV)
+    z = torch.from_numpy(out["zero_point"]).to(DEV)
+    wq = torch.empty((o, c), dtype=torch.int8, device=DEV)
+    corr = torch.empty((o,), dtype=torch.int64, device=DEV)
+    a = torch.empty((o,), device=DEV)
+    G.granq_fold_weights(wt, s, z, wq, corr, a)
+    codes = torch.from_numpy(out["codes"]).to(DEV)
+    ewq, ecorr, ea = oracle.fold_weights(wt.cpu().numpy(), out["scale"], out["zero_point"])
+    torch.cuda.synchronize()
+    assert np.array_equal(corr.cpu().numpy(), ecorr) and np.abs(ecorr).max() > 2 ** 31
+    want = oracle.conv1x1_int8(out["codes"], ewq, ecorr, ea)
+    for shape_ok in (True, False):                     # matrix-core kernel, then the plain one (misaligned y)
+        ybuf = torch.full((n * o * h * w + 4,), float("nan"), device=DEV)
+        y = (ybuf[:-4] if shape_ok else ybuf[1:-3]).view(n, o, h, w)
+        G.granq_conv1x1_int8(codes, wq, corr, a, 4, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_view(y.cpu().numpy()), bits_view(want))
+
+
+PACKED_SHAPES = [
+    ((2, 16, 8, 8), 32), ((3, 64, 14, 14), 64), ((2, 32, 7, 12), 96), ((2, 1040, 2, 4), 96), ((70, 32, 1, 4), 32),
+    ((3, 1024, 14, 14), 256),                                   # matrix cores
+    ((2, 7, 5, 5), 3), ((1, 16, 7, 7), 32), ((1, 3, 3, 3), 2), ((1, 1, 1, 1), 1),     # plain kernel, odd counts
+]
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("shape,o", PACKED_SHAPES, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_packed_codes_forward_and_convolution(shape, o, bits):
+    """Codes two per byte: the forward's packed output against the oracle's packing of the
+    oracle's codes (with and without x_hat), and the convolution on them against the
+    oracle's convolution on the unpacked codes, bit for bit, float32 and bfloat16 outputs."""
+    n, c, h, w = shape
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), 11, DEV)
+    out = gpu_path(x, bits)
+    s = torch.from_numpy(out["scale"]).to(DEV)
+    z = torch.from_numpy(out["zero_point"]).to(DEV)
+    nbytes = G.granq_packed4_bytes(G.desc_of(x))
+    assert nbytes == (x.numel() + 1) // 2
+    want_packed = oracle.pack4(out["codes"])
+    for with_xhat in (True, False):
+        packed = torch.full((nbytes,), 0xEE, dtype=torch.uint8, device=DEV)
+        xh = torch.empty_like(x) if with_xhat else None
+        G.granq_fakequant_fwd_packed4(x, s, z, bits, xh, packed)
+        torch.cuda.synchronize()
+        assert np.array_equal(packed.cpu().numpy(), want_packed), "packed codes differ (x_hat %s)" % with_xhat
+        if with_xhat:
+            assert np.array_equal(xh.cpu().numpy(), out["xhat"])
+    g = torch.Generator(device=DEV).manual_seed(5)
+    wt = torch.randn(o, c, generator=g, device=DEV)
+    wq = torch.empty((o, c), dtype=torch.int8, device=DEV)
+    corr = torch.empty((o,), dtype=torch.int64, device=DEV)
+    a = torch.empty((o,), device=DEV)
+    G.granq_fold_weights(wt, s, z, wq, corr, a)
+    torch.cuda.synchronize()
+    codes_again = oracle.unpack4(want_packed, x.numel()).reshape(shape)
+    assert np.array_equal(codes_again, out["codes"])
+    want = oracle.conv1x1_int8(codes_again, wq.cpu().numpy(), corr.cpu().numpy(), a.cpu().numpy())
+    y = torch.full((n, o, h, w), float("nan"), device=DEV)
+    G.granq_conv1x1_int8_packed4(packed, shape, wq, corr, a, bits, y)
+    y16 = torch.empty((n, o, h, w), dtype=torch.bfloat16, device=DEV)
+    G.granq_conv1x1_int8_packed4(packed, shape, wq, corr, a, bits, y16)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_view(y.cpu().numpy()), bits_view(want))
+    want16 = torch.from_numpy(want).to(torch.bfloat16)
+    assert torch.equal(y16.cpu().view(torch.int16), want16.view(torch.int16))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+def test_packed_codes_from_16_bit_tensors(dtype):
+    for shape in [(4, 24, 14, 14), (3, 10, 7, 7), (2, 3, 3, 3)]:
+        x = workloads.make_activation(shape, "relu", (0.05, 20.0), 2, DEV, dtype)
+        out = gpu_path(x, 3)
+        s = torch.from_numpy(out["scale"]).to(DEV)
+        z = torch.from_numpy(out["zero_point"]).to(DEV)
+        packed = torch.full(((x.numel() + 1) // 2,), 0xEE, dtype=torch.uint8, device=DEV)
+        xh = torch.empty_like(x)
+        G.granq_fakequant_fwd_packed4(x, s, z, 3, xh, packed)
+        torch.cuda.synchronize()
+        assert np.array_equal(packed.cpu().numpy(), oracle.pack4(out["codes"]))
+        assert np.array_equal(to_numpy(xh), out["xhat"])
+
+
+def test_packed_codes_argument_checks():
+    import ctypes
+    lib = G.load()
+    d = G.make_desc(2, 16, 4, 4, 0)
+    assert lib.granq_fakequant_fwd_packed4(16, ctypes.byref(d), 16, 16, 5, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_fakequant_fwd_packed4(16, ctypes.byref(d), 16, 16, 4, 16, 0, 0) == G.GRANQ_ERR_INVALID_ARG
+    assert lib.granq_conv1x1_int8_packed4(16, ctypes.byref(d), 32, 16, 16, 16, 5, 0, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+    assert G.granq_packed4_bytes(G.make_desc(1, 1, 1, 9, 0)) == 5
