@@ -37,6 +37,16 @@ constexpr int kConvKChunk = 512;           // channels staged in LDS at a time
 #define GRANQ_CONV_TARGET_BLOCKS 6000
 #endif
 constexpr int kConvDies = 8;               // XCDs of the chip
+// The shared-tile variant below is taken from this many output and input channels on.
+#ifndef GRANQ_CONV_SHARED
+#define GRANQ_CONV_SHARED 1
+#endif
+#ifndef GRANQ_CONV_SHARED_MIN_O
+#define GRANQ_CONV_SHARED_MIN_O 192
+#endif
+#ifndef GRANQ_CONV_SHARED_MIN_C
+#define GRANQ_CONV_SHARED_MIN_C 128
+#endif
 constexpr int kConvPad = 16;               // bytes between LDS rows: 16-byte reads of 32 rows spread over all banks
 
 // Four neighbouring output pixels to y at element index `at` (a multiple of 4).
@@ -224,6 +234,159 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     }
 }
 
+// Variant for many output channels and many input channels (the weight-heavy 1x1 convolutions
+// of the later stages): the four wavefronts of a block work on the SAME 128 pixels, each on
+// its own 64 of 256 output channels, and share the transposed code tiles through LDS, so the
+// codes are fetched and transposed once per 256 output channels instead of once per 64.
+// Channels go in chunks of 128 (four 32-channel steps; 256 with two blocks' worth of LDS measured
+// slower: 52 against 39 us on 1024 -> 256 channels at 14 x 14, batch 256): wavefront w fetches and
+// transposes step w (w + 4, ... with longer chunks) and writes its four B operands to LDS in exactly the lane order in which every
+// wavefront then reads them back; the chunk's weights (256 rows x 128 bytes) are staged beside
+// them.  The fetches of the next chunk (codes and weights, into registers) are in flight
+// during the multiplies of the current one.
+#ifndef GRANQ_CONV_SHARED_CHUNK
+#define GRANQ_CONV_SHARED_CHUNK 128
+#endif
+constexpr int kShChunk = GRANQ_CONV_SHARED_CHUNK;          // channels per chunk: a multiple of 128
+constexpr int kShRows = 4 * kConvRows;         // output channels per block
+constexpr int kShTile = kWave * 4 * 16;        // bytes of one step's four B operands (64 lanes x 4 x 16)
+constexpr int kShSteps = kShChunk / 32;        // 32-channel steps per chunk
+constexpr int kShMine = kShSteps / 4;          // steps a wavefront fetches and transposes per chunk
+
+template <typename OutT, bool PACKED>
+__global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
+    const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
+    const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
+    int64_t groups_total, int32_t supers)
+{
+    static_assert(kShChunk % 128 == 0, "four wavefronts share the steps of a chunk evenly");
+    constexpr int kStride = kShChunk + kConvPad;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_all[];
+    uint8_t *lds_w = lds_all;                              // kShRows x kStride
+    uint8_t *lds_b = lds_all + kShRows * kStride;          // kShSteps x kShTile
+    const int lane = threadIdx.x & (kWave - 1);
+    const int half = lane / 32, col = lane % 32;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const int64_t tile = blockIdx.x / (uint32_t)supers;
+    const int64_t super = blockIdx.x % (uint32_t)supers;
+    const int64_t g_first = tile * 32;                     // all four wavefronts: the same 32 pixel groups
+    const int64_t g = g_first + col;
+    const bool live = g < groups_total;
+    const int64_t hw4 = hw / 4;
+    const int64_t n = live ? g / hw4 : 0;
+    const int64_t pb = live ? 4 * (g - n * hw4) : 0;
+    const int64_t n_first = g_first / hw4;                 // g_first < groups_total for every launched block
+    constexpr int kPerByte = PACKED ? 2 : 1;
+    const __amdgpu_buffer_rsrc_t code_buf = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(codes + n_first * c * hw / kPerByte), 0, 0x7fffffff, 0x00020000);
+    const uint32_t lane_off = live ? (uint32_t)(((n - n_first) * c * hw + pb + 16 * half * hw) / kPerByte) : 0u;
+    const int64_t o_base = super * kShRows + wave * kConvRows;       // this wavefront's 64 output channels
+
+    i32x16 acc[kConvOT][4];
+#pragma unroll
+    for (int t = 0; t < kConvOT; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][j][r] = 0;
+
+    // this wavefront's steps of the chunk that starts at channel kc: steps wave, wave + 4, ...
+    uint32_t d[kShMine][16];
+    auto fetch = [&](int64_t kc) {
+#pragma unroll
+        for (int m = 0; m < kShMine; ++m) {
+            const int64_t ch0 = kc + 32 * (wave + 4 * m);
+            const bool ok = live && ch0 + 16 * half < c;
+            const int off = (int)(ok ? lane_off : 0u);
+            const int64_t ch0c = ch0 < c - 16 ? ch0 : c - 16;      // in bounds; what it reads is discarded
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                d[m][i] = PACKED ? (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(code_buf, off, (int)((ch0c + i) * hw / 2), 0)
+                                 : (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(code_buf, off, (int)((ch0c + i) * hw), 0);
+        }
+    };
+    // the chunk's weights, one 16-byte segment per thread and round: rows past O and channels past
+    // C read as zero
+    constexpr int kSegs = kShChunk / 16;                   // segments per row
+    constexpr int kRounds = kShRows * kSegs / kBlock;      // segments per thread
+    i32x4 wreg[kRounds];
+    auto wload = [&](int64_t kc) {
+#pragma unroll
+        for (int q = 0; q < kRounds; ++q) {
+            const int32_t idx = threadIdx.x + q * kBlock;
+            const int32_t row = idx / kSegs, seg = idx - row * kSegs;
+            i32x4 v = {0, 0, 0, 0};
+            if (super * kShRows + row < o && kc + seg * 16 < c)
+                v = *(const i32x4 *)(wq + (super * kShRows + row) * c + kc + seg * 16);
+            wreg[q] = v;
+        }
+    };
+    fetch(0);
+    wload(0);
+    for (int64_t kc0 = 0; kc0 < c; kc0 += kShChunk) {
+        __syncthreads();                                   // the previous chunk's readers are done
+#pragma unroll
+        for (int q = 0; q < kRounds; ++q) {
+            const int32_t idx = threadIdx.x + q * kBlock;
+            const int32_t row = idx / kSegs, seg = idx - row * kSegs;
+            *(i32x4 *)(lds_w + row * kStride + seg * 16) = wreg[q];
+        }
+        // this wavefront's steps: discard what lies past C or belongs to no pixel, transpose, publish
+#pragma unroll
+        for (int m = 0; m < kShMine; ++m) {
+            const int step = wave + 4 * m;
+            const bool ok = live && kc0 + 32 * step + 16 * half < c;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                uint32_t t = ok ? d[m][i] : 0u;
+                if (PACKED) {                              // nibble i -> byte i
+                    t = (t | (t << 8)) & 0x00FF00FFu;
+                    t = (t | (t << 4)) & 0x0F0F0F0Fu;
+                }
+                d[m][i] = t;
+            }
+            i32x4 b[4];
+            transpose_16x4(d[m], b);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *(i32x4 *)(lds_b + step * kShTile + (j * kWave + lane) * 16) = b[j];
+        }
+        if (kc0 + kShChunk < c) {                          // in flight during the multiplies below
+            fetch(kc0 + kShChunk);
+            wload(kc0 + kShChunk);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kShSteps; ++s) {
+            if (kc0 + 32 * s >= c) break;                  // block-uniform
+            const i32x4 a0 = *(const i32x4 *)(lds_w + (wave * kConvRows + col) * kStride + 32 * s + 16 * half);
+            const i32x4 a1 = *(const i32x4 *)(lds_w + (wave * kConvRows + 32 + col) * kStride + 32 * s + 16 * half);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const i32x4 bj = *(const i32x4 *)(lds_b + s * kShTile + (j * kWave + lane) * 16);
+                acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, bj, acc[0][j], 0, 0, 0);
+                acc[1][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, bj, acc[1][j], 0, 0, 0);
+            }
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int t = 0; t < kConvOT; ++t) {
+        if (o_base + 32 * t >= o) break;                   // wave-uniform: o is a multiple of 32
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+            const double cz = (double)corr[oc];
+            const float sc = out_scale[oc];
+            f32x4 v;
+            v.x = sc * (float)((double)acc[t][0][r] - cz);
+            v.y = sc * (float)((double)acc[t][1][r] - cz);
+            v.z = sc * (float)((double)acc[t][2][r] - cz);
+            v.w = sc * (float)((double)acc[t][3][r] - cz);
+            store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
+        }
+    }
+}
+
 // Any shape: one thread per output element, integer loop over the channels.
 // PACKED: the codes are two per byte (element i in nibble i & 1 of byte i >> 1).
 template <typename OutT, bool PACKED>
@@ -308,6 +471,25 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
     // a lane stores four neighbouring pixels at once
     const bool mfma = bits <= 7 && c % 16 == 0 && o % 32 == 0 && hw % 4 == 0 && c * hw < ((int64_t)1 << 25) &&
                       ((uintptr_t)codes & (PACKED ? 1u : 3u)) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0;
+    // many output and input channels: four wavefronts share one pixel tile's transposed codes
+    if (mfma && GRANQ_CONV_SHARED && o >= GRANQ_CONV_SHARED_MIN_O && c >= GRANQ_CONV_SHARED_MIN_C) {
+        const int64_t groups_total = n * (hw / 4);
+        const int64_t tiles = (groups_total + 31) / 32;
+        const int64_t supers = (o + kShRows - 1) / kShRows;
+        if (tiles * supers >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
+        const size_t lds_bytes = (size_t)kShRows * (kShChunk + kConvPad) + (size_t)kShSteps * kShTile;
+        dim3 grid((uint32_t)(tiles * supers)), block(kBlock);
+        using kernel_t = void (*)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
+                                  int64_t, int64_t, int64_t, int32_t);
+        kernel_t kernel = y_dtype == GRANQ_F32 ? conv1x1_i8_mfma_shared<F32, PACKED>
+                        : (y_dtype == GRANQ_BF16 ? conv1x1_i8_mfma_shared<BF16, PACKED> : conv1x1_i8_mfma_shared<F16, PACKED>);
+        // more than the 64 KB of LDS a kernel gets without asking (a function attribute, no allocation)
+        if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return GRANQ_ERR_HIP;
+        launch_kernel(kernel, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o, groups_total,
+                      (int32_t)supers);
+        return launched();
+    }
     if (mfma) {
         const int64_t groups_total = n * (hw / 4);
         const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));

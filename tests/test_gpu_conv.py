@@ -46,6 +46,10 @@ def _case(shape, o, bits, law="linear", seed=0):
     ((4, 48, 2, 2), 32, 7), ((2, 64, 56, 56), 64, 4), ((1, 256, 1, 4), 64, 4), ((2, 16, 23, 12), 128, 2),
     # more channels than one LDS chunk of weights (512), with a 16-channel tail; many samples per wavefront
     ((2, 1040, 2, 4), 96, 4), ((1, 528, 4, 4), 64, 6), ((70, 32, 1, 4), 32, 4), ((3, 1024, 14, 14), 256, 4),
+    # many output and input channels: the variant whose four wavefronts share a pixel tile (a 16-channel
+    # tail, output channels that are no multiple of 64 or 256, two groups of 256, many samples per tile)
+    ((2, 128, 4, 4), 192, 4), ((1, 144, 2, 6), 224, 5), ((5, 272, 1, 4), 320, 3), ((40, 160, 1, 4), 512, 7),
+    ((2, 2048, 7, 8), 512, 4), ((1, 256, 3, 4), 1024, 4),
 ])
 def test_conv_mfma_path(shape, o, bits):
     _case(shape, o, bits)
@@ -154,7 +158,7 @@ def test_zero_point_term_beyond_32_bits():
 
 PACKED_SHAPES = [
     ((2, 16, 8, 8), 32), ((3, 64, 14, 14), 64), ((2, 32, 7, 12), 96), ((2, 1040, 2, 4), 96), ((70, 32, 1, 4), 32),
-    ((3, 1024, 14, 14), 256),                                   # matrix cores
+    ((3, 1024, 14, 14), 256), ((1, 144, 2, 6), 224), ((5, 272, 1, 4), 320),        # matrix cores
     ((2, 7, 5, 5), 3), ((1, 16, 7, 7), 32), ((1, 3, 3, 3), 2), ((1, 1, 1, 1), 1),     # plain kernel, odd counts
 ]
 
