@@ -88,7 +88,9 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // from the caches.  Blocks are numbered so that the blocks that share a pixel tile
 // (its `splits` groups of sweeps) are consecutive on ONE die: workgroups go to the
 // eight dies round-robin in launch order and each die has its own L2, so the
-// re-reads of a tile's codes by its other sweep groups hit that L2.  The channel loop is software-pipelined by hand: the loads of the next 32
+// re-reads of a tile's codes by its other sweep groups hit that L2; die d takes the d-th eighth of
+// the tiles, so that the cache lines a tile shares with its neighbours (a channel's row rarely
+// starts on a line) are fetched by one die only.  The channel loop is software-pipelined by hand: the loads of the next 32
 // channels are issued before the matrix instructions of the current ones, and
 // scheduling barriers keep them there.
 // OutT: storage of y (F32, BF16 or F16 traits): the binary32 result is narrowed on the store.
@@ -98,7 +100,7 @@ template <typename OutT, bool PACKED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
-    int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride)
+    int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride, int32_t tiles_per_die)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_w[];   // kConvRows x lds_stride bytes
     const int lane = threadIdx.x & (kWave - 1);
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     // launch order -> (pixel tile, sweep group): die = id % 8, then the sweep groups of a tile
     const uint32_t die = blockIdx.x % kConvDies, m = blockIdx.x / kConvDies;
     const uint32_t split = m % (uint32_t)splits;
-    const int64_t tile = (int64_t)(m / (uint32_t)splits) * kConvDies + die;
+    const int64_t tile = (int64_t)die * tiles_per_die + m / (uint32_t)splits;
     const int64_t g_first = (tile * (kBlock / kWave) + wave) * 32;
     const int64_t g = g_first + col;
     const bool live = g < groups_total;
@@ -257,7 +259,7 @@ template <typename OutT, bool PACKED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
-    int64_t groups_total, int32_t supers)
+    int64_t groups_total, int32_t supers, int32_t tiles_per_die)
 {
     static_assert(kShChunk % 128 == 0, "four wavefronts share the steps of a chunk evenly");
     constexpr int kStride = kShChunk + kConvPad;
@@ -267,15 +269,21 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
     const int lane = threadIdx.x & (kWave - 1);
     const int half = lane / 32, col = lane % 32;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
-    const int64_t tile = blockIdx.x / (uint32_t)supers;
-    const int64_t super = blockIdx.x % (uint32_t)supers;
+    // launch order -> pixel tile: workgroups go to the eight dies round-robin, so die d takes the d-th
+    // eighth of the tiles.  Neighbouring tiles then meet in ONE die's L2: a channel's row of H*W bytes
+    // rarely starts on a cache line, so each 128-byte piece shares its first and last line with the
+    // neighbouring tile's piece (with round-robin tiles every such line came from memory twice).
+    const uint32_t die = blockIdx.x % kConvDies, m = blockIdx.x / kConvDies;
+    const int64_t tile = (int64_t)die * tiles_per_die + m / (uint32_t)supers;
+    const int64_t super = m % (uint32_t)supers;
+    if (tile * 32 >= groups_total) return;                 // block-uniform: the last die's spare blocks
     const int64_t g_first = tile * 32;                     // all four wavefronts: the same 32 pixel groups
     const int64_t g = g_first + col;
     const bool live = g < groups_total;
     const int64_t hw4 = hw / 4;
     const int64_t n = live ? g / hw4 : 0;
     const int64_t pb = live ? 4 * (g - n * hw4) : 0;
-    const int64_t n_first = g_first / hw4;                 // g_first < groups_total for every launched block
+    const int64_t n_first = g_first / hw4;                 // g_first < groups_total from here on
     constexpr int kPerByte = PACKED ? 2 : 1;
     const __amdgpu_buffer_rsrc_t code_buf = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(codes + n_first * c * hw / kPerByte), 0, 0x7fffffff, 0x00020000);
@@ -476,18 +484,20 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         const int64_t groups_total = n * (hw / 4);
         const int64_t tiles = (groups_total + 31) / 32;
         const int64_t supers = (o + kShRows - 1) / kShRows;
-        if (tiles * supers >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
+        const int64_t tiles_per_die = (tiles + kConvDies - 1) / kConvDies;
+        const int64_t blocks = tiles_per_die * kConvDies * supers;
+        if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         const size_t lds_bytes = (size_t)kShRows * (kShChunk + kConvPad) + (size_t)kShSteps * kShTile;
-        dim3 grid((uint32_t)(tiles * supers)), block(kBlock);
+        dim3 grid((uint32_t)blocks), block(kBlock);
         using kernel_t = void (*)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
-                                  int64_t, int64_t, int64_t, int32_t);
+                                  int64_t, int64_t, int64_t, int32_t, int32_t);
         kernel_t kernel = y_dtype == GRANQ_F32 ? conv1x1_i8_mfma_shared<F32, PACKED>
                         : (y_dtype == GRANQ_BF16 ? conv1x1_i8_mfma_shared<BF16, PACKED> : conv1x1_i8_mfma_shared<F16, PACKED>);
         // more than the 64 KB of LDS a kernel gets without asking (a function attribute, no allocation)
         if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return GRANQ_ERR_HIP;
         launch_kernel(kernel, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o, groups_total,
-                      (int32_t)supers);
+                      (int32_t)supers, (int32_t)tiles_per_die);
         return launched();
     }
     if (mfma) {
@@ -505,18 +515,19 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         const int32_t lds_stride = (int32_t)kc + kConvPad;
         const size_t lds_bytes = (size_t)kConvRows * lds_stride;
         // tiles rounded up to a multiple of the dies; blocks of tiles past the end find no live group
-        const int64_t blocks = (gx + kConvDies - 1) / kConvDies * kConvDies * gy;
+        const int64_t tiles_per_die = (gx + kConvDies - 1) / kConvDies;
+        const int64_t blocks = tiles_per_die * kConvDies * gy;
         if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         dim3 grid((uint32_t)blocks), block(kBlock);
         if (y_dtype == GRANQ_F32)
             launch_kernel((conv1x1_i8_mfma<F32, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
+                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
         else if (y_dtype == GRANQ_BF16)
             launch_kernel((conv1x1_i8_mfma<BF16, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
+                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
         else
             launch_kernel((conv1x1_i8_mfma<F16, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride);
+                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
         if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
         return GRANQ_OK;
     }
