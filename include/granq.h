@@ -374,9 +374,11 @@ granq_status_t granq_distortion(const void *x, const granq_desc_t *desc,
  * granq_conv1x1_int8: codes [in] N*C*H*W bytes as written by granq_fakequant_fwd (desc
  * gives n, c, h, w; its dtype is ignored); y [out] N*O*H*W floats, NCHW with O channels.
  * The integer expression sum - corr is exact; it is rounded to binary32 once, then scaled.
- * The matrix-core kernel needs codes <= 127 (bits <= 7), C a multiple of 16, O a multiple
- * of 32, H*W a multiple of 4, C*H*W < 2^25, 4-byte aligned codes and 16-byte aligned wq
- * and y; anything else runs a plain integer kernel with identical results.
+ * The matrix-core kernels need codes <= 127 (bits <= 7), C a multiple of 16, O a multiple
+ * of 32, C*H*W < 2^25 and 16-byte aligned wq; with H*W a multiple of 4 also 4-byte aligned
+ * codes and 16-byte aligned y; with any other H*W >= 4 (7 x 7 maps) codes and y need the
+ * alignment of one element only.  Anything else runs a plain integer kernel with identical
+ * results.
  */
 granq_status_t granq_fold_weights(const float *w, const float *scale, const float *zero_point,
                                   int64_t o, int64_t c, int8_t *wq, int64_t *corr,
@@ -390,7 +392,7 @@ granq_status_t granq_conv1x1_int8(const uint8_t *codes, const granq_desc_t *desc
  * The same convolution with y stored as y_dtype: the binary32 result above is narrowed to
  * bfloat16 or binary16 with round to nearest even on the store (GRANQ_F32: identical to
  * granq_conv1x1_int8).  The output is what bounds this kernel, so 16-bit storage nearly
- * halves its time.  The matrix-core path then needs y 8-byte aligned.
+ * halves its time.  The matrix-core path then needs y 8-byte aligned (H*W a multiple of 4).
  */
 granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
                                      const int8_t *wq, const int64_t *corr, const float *out_scale,
@@ -410,7 +412,8 @@ granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *d
  * `packed` 2-byte aligned for float32 and 4-byte aligned for 16-bit tensors.
  *
  * granq_conv1x1_int8_packed4 = granq_conv1x1_int8_as reading such codes; identical results.
- * Its matrix-core path needs 2-byte aligned codes besides the conditions above.
+ * Its matrix-core path needs H*W a multiple of 4 and 2-byte aligned codes besides the
+ * conditions above.
  */
 granq_status_t granq_packed4_bytes(const granq_desc_t *desc, size_t *bytes_out);
 

@@ -62,6 +62,28 @@ __device__ __forceinline__ void store_pixels4(void *y, int64_t at, const f32x4 &
     }
 }
 
+// The same when H*W is not a multiple of 4: a group's first pixel is then aligned to one element
+// only, and a sample's last group has `valid` < 4 pixels.
+template <typename OutT>
+__device__ __forceinline__ void store_pixels_ragged(void *y, int64_t at, const f32x4 &v, int valid) {
+    typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+    typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
+    if (valid == 4) {
+        if constexpr (OutT::ESIZE == 4) {
+            __builtin_nontemporal_store(v, (f32x4_a4 *)((float *)y + at));
+        } else {
+            u32x2 w;
+            w.x = OutT::pack2(v.x, v.y);
+            w.y = OutT::pack2(v.z, v.w);
+            __builtin_nontemporal_store(w, (u32x2_a2 *)((uint16_t *)y + at));
+        }
+    } else {
+        OutT::store1(y, at, v.x);
+        if (valid > 1) OutT::store1(y, at + 1, v.y);
+        if (valid > 2) OutT::store1(y, at + 2, v.z);
+    }
+}
+
 // dword i of `d` holds four neighbouring pixels of channel i; the result's dword q of
 // operand j holds channels 4q .. 4q+3 of pixel j.
 __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&b)[4]) {
@@ -96,7 +118,11 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // OutT: storage of y (F32, BF16 or F16 traits): the binary32 result is narrowed on the store.
 // PACKED: the codes are two per byte; a lane then fetches its four pixels of a channel as one
 // 16-bit load and spreads the nibbles into bytes (six integer operations) before the transpose.
-template <typename OutT, bool PACKED>
+// RAGGED: H*W is not a multiple of 4 (7 x 7 maps), codes one per byte.  A sample then has
+// ceil(H*W / 4) groups; the dwords are fetched from addresses aligned to one byte; the last
+// group's dword is the LAST four bytes of the channel's row, shifted down so that the group's
+// `valid` pixels sit in the low bytes (above them stand codes of pixels that are never stored).
+template <typename OutT, bool PACKED, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
@@ -115,9 +141,13 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const int64_t g = g_first + col;
     const bool live = g < groups_total;
     const bool wave_live = __any(live);                // a dead wavefront only keeps the barriers
-    const int64_t hw4 = hw / 4;                        // hw % 4 == 0 on this path
+    static_assert(!(PACKED && RAGGED), "two codes per byte need H*W to be a multiple of 4");
+    const int64_t hw4 = RAGGED ? (hw + 3) / 4 : hw / 4;   // groups per sample
     const int64_t n = live ? g / hw4 : 0;
     const int64_t pb = live ? 4 * (g - n * hw4) : 0;
+    const int valid = RAGGED && hw - pb < 4 ? (int)(hw - pb) : 4;
+    const int64_t pl = valid == 4 ? pb : hw - 4;        // where the group's dword is fetched
+    const uint32_t shift = 8u * (uint32_t)(4 - valid);
     // addresses of the codes = wave-uniform base (scalar registers) + one 32-bit lane offset:
     // the wavefront's lanes lie within 33 samples of its first lane's sample (C*H*W < 2^25 here)
     const int64_t n_first = g_first < groups_total ? g_first / hw4 : 0;
@@ -127,7 +157,7 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     constexpr int kPerByte = PACKED ? 2 : 1;
     const __amdgpu_buffer_rsrc_t code_buf = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(codes + n_first * c * hw / kPerByte), 0, 0x7fffffff, 0x00020000);
-    const uint32_t lane_off = live ? (uint32_t)(((n - n_first) * c * hw + pb + 16 * half * hw) / kPerByte) : 0u;
+    const uint32_t lane_off = live ? (uint32_t)(((n - n_first) * c * hw + pl + 16 * half * hw) / kPerByte) : 0u;
 
     const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
     const int64_t s0 = (int64_t)split * sweeps_per_block;
@@ -184,6 +214,7 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
                 const bool ok = live && kc0 + (k) + 16 * half < c;                           \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i) {                             \
                     uint32_t t = ok ? d[i] : 0u;                                             \
+                    if (RAGGED) t >>= shift;                                                 \
                     if (PACKED) {                      /* nibble i -> byte i */              \
                         t = (t | (t << 8)) & 0x00FF00FFu;                                    \
                         t = (t | (t << 4)) & 0x0F0F0F0Fu;                                    \
@@ -230,7 +261,8 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
                 v.y = sc * (float)((double)acc[t][1][r] - cz);
                 v.z = sc * (float)((double)acc[t][2][r] - cz);
                 v.w = sc * (float)((double)acc[t][3][r] - cz);
-                store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
+                if constexpr (RAGGED) store_pixels_ragged<OutT>(y, (n * o + oc) * hw + pb, v, valid);
+                else store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
             }
         }
     }
@@ -255,7 +287,7 @@ constexpr int kShTile = kWave * 4 * 16;        // bytes of one step's four B ope
 constexpr int kShSteps = kShChunk / 32;        // 32-channel steps per chunk
 constexpr int kShMine = kShSteps / 4;          // steps a wavefront fetches and transposes per chunk
 
-template <typename OutT, bool PACKED>
+template <typename OutT, bool PACKED, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
@@ -280,14 +312,18 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
     const int64_t g_first = tile * 32;                     // all four wavefronts: the same 32 pixel groups
     const int64_t g = g_first + col;
     const bool live = g < groups_total;
-    const int64_t hw4 = hw / 4;
+    static_assert(!(PACKED && RAGGED), "two codes per byte need H*W to be a multiple of 4");
+    const int64_t hw4 = RAGGED ? (hw + 3) / 4 : hw / 4;   // groups per sample
     const int64_t n = live ? g / hw4 : 0;
     const int64_t pb = live ? 4 * (g - n * hw4) : 0;
+    const int valid = RAGGED && hw - pb < 4 ? (int)(hw - pb) : 4;
+    const int64_t pl = valid == 4 ? pb : hw - 4;        // where the group's dword is fetched
+    const uint32_t shift = 8u * (uint32_t)(4 - valid);
     const int64_t n_first = g_first / hw4;                 // g_first < groups_total from here on
     constexpr int kPerByte = PACKED ? 2 : 1;
     const __amdgpu_buffer_rsrc_t code_buf = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(codes + n_first * c * hw / kPerByte), 0, 0x7fffffff, 0x00020000);
-    const uint32_t lane_off = live ? (uint32_t)(((n - n_first) * c * hw + pb + 16 * half * hw) / kPerByte) : 0u;
+    const uint32_t lane_off = live ? (uint32_t)(((n - n_first) * c * hw + pl + 16 * half * hw) / kPerByte) : 0u;
     const int64_t o_base = super * kShRows + wave * kConvRows;       // this wavefront's 64 output channels
 
     i32x16 acc[kConvOT][4];
@@ -347,6 +383,7 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 uint32_t t = ok ? d[m][i] : 0u;
+                if (RAGGED) t >>= shift;
                 if (PACKED) {                              // nibble i -> byte i
                     t = (t | (t << 8)) & 0x00FF00FFu;
                     t = (t | (t << 4)) & 0x0F0F0F0Fu;
@@ -390,7 +427,8 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
             v.y = sc * (float)((double)acc[t][1][r] - cz);
             v.z = sc * (float)((double)acc[t][2][r] - cz);
             v.w = sc * (float)((double)acc[t][3][r] - cz);
-            store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
+            if constexpr (RAGGED) store_pixels_ragged<OutT>(y, (n * o + oc) * hw + pb, v, valid);
+            else store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
         }
     }
 }
@@ -461,6 +499,30 @@ __global__ __launch_bounds__(kBlock) void fold_weights_kernel(
 
 using namespace granq;
 
+typedef void (*conv_shared_t)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
+                              int64_t, int64_t, int64_t, int32_t, int32_t);
+typedef void (*conv_mfma_t)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
+                            int64_t, int64_t, int64_t, int32_t, int32_t, int32_t, int32_t);
+typedef void (*conv_plain_t)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
+                             int64_t, int64_t);
+
+template <bool PACKED, bool RAGGED>
+static conv_shared_t shared_kernel(granq_dtype_t t) {
+    return t == GRANQ_F32 ? conv1x1_i8_mfma_shared<F32, PACKED, RAGGED>
+                          : (t == GRANQ_BF16 ? conv1x1_i8_mfma_shared<BF16, PACKED, RAGGED>
+                                             : conv1x1_i8_mfma_shared<F16, PACKED, RAGGED>);
+}
+template <bool PACKED, bool RAGGED>
+static conv_mfma_t mfma_kernel(granq_dtype_t t) {
+    return t == GRANQ_F32 ? conv1x1_i8_mfma<F32, PACKED, RAGGED>
+                          : (t == GRANQ_BF16 ? conv1x1_i8_mfma<BF16, PACKED, RAGGED> : conv1x1_i8_mfma<F16, PACKED, RAGGED>);
+}
+template <bool PACKED>
+static conv_plain_t plain_kernel(granq_dtype_t t) {
+    return t == GRANQ_F32 ? conv1x1_i8_plain<F32, PACKED>
+                          : (t == GRANQ_BF16 ? conv1x1_i8_plain<BF16, PACKED> : conv1x1_i8_plain<F16, PACKED>);
+}
+
 // y_dtype: storage of y; the binary32 result is narrowed (round to nearest even) on the store.
 template <bool PACKED>
 static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, int64_t o,
@@ -476,12 +538,15 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
     const uintptr_t esize = y_dtype == GRANQ_F32 ? 4 : 2;
     if (((uintptr_t)corr & 7u) || ((uintptr_t)out_scale & 3u) || ((uintptr_t)y & (esize - 1))) return GRANQ_ERR_UNSUPPORTED;
     hipStream_t hs = (hipStream_t)stream;
-    // a lane stores four neighbouring pixels at once
-    const bool mfma = bits <= 7 && c % 16 == 0 && o % 32 == 0 && hw % 4 == 0 && c * hw < ((int64_t)1 << 25) &&
-                      ((uintptr_t)codes & (PACKED ? 1u : 3u)) == 0 && ((uintptr_t)wq & 15u) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0;
+    // a lane handles four neighbouring pixels of a sample at once: aligned when H*W is a multiple of
+    // 4, else (codes one per byte only) with accesses aligned to one element
+    const bool ragged = hw % 4 != 0;
+    const bool shape_ok = bits <= 7 && c % 16 == 0 && o % 32 == 0 && c * hw < ((int64_t)1 << 25) && ((uintptr_t)wq & 15u) == 0;
+    const bool mfma = shape_ok && (ragged ? !PACKED && hw >= 4
+                                          : ((uintptr_t)codes & (PACKED ? 1u : 3u)) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0);
+    const int64_t groups_total = n * ((hw + 3) / 4);
     // many output and input channels: four wavefronts share one pixel tile's transposed codes
     if (mfma && GRANQ_CONV_SHARED && o >= GRANQ_CONV_SHARED_MIN_O && c >= GRANQ_CONV_SHARED_MIN_C) {
-        const int64_t groups_total = n * (hw / 4);
         const int64_t tiles = (groups_total + 31) / 32;
         const int64_t supers = (o + kShRows - 1) / kShRows;
         const int64_t tiles_per_die = (tiles + kConvDies - 1) / kConvDies;
@@ -489,10 +554,9 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         const size_t lds_bytes = (size_t)kShRows * (kShChunk + kConvPad) + (size_t)kShSteps * kShTile;
         dim3 grid((uint32_t)blocks), block(kBlock);
-        using kernel_t = void (*)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
-                                  int64_t, int64_t, int64_t, int32_t, int32_t);
-        kernel_t kernel = y_dtype == GRANQ_F32 ? conv1x1_i8_mfma_shared<F32, PACKED>
-                        : (y_dtype == GRANQ_BF16 ? conv1x1_i8_mfma_shared<BF16, PACKED> : conv1x1_i8_mfma_shared<F16, PACKED>);
+        conv_shared_t kernel;
+        if constexpr (PACKED) kernel = shared_kernel<true, false>(y_dtype);
+        else kernel = ragged ? shared_kernel<false, true>(y_dtype) : shared_kernel<false, false>(y_dtype);
         // more than the 64 KB of LDS a kernel gets without asking (a function attribute, no allocation)
         if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return GRANQ_ERR_HIP;
@@ -501,7 +565,6 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         return launched();
     }
     if (mfma) {
-        const int64_t groups_total = n * (hw / 4);
         const int64_t gx = (groups_total + 32 * (kBlock / kWave) - 1) / (32 * (kBlock / kWave));
         if (gx >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         const int64_t sweeps = (o + kConvRows - 1) / kConvRows;
@@ -514,30 +577,20 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         const int64_t kc = c < kConvKChunk ? (c + 63) / 64 * 64 : kConvKChunk;
         const int32_t lds_stride = (int32_t)kc + kConvPad;
         const size_t lds_bytes = (size_t)kConvRows * lds_stride;
-        // tiles rounded up to a multiple of the dies; blocks of tiles past the end find no live group
+        // each die's range of tiles rounded up; blocks of tiles past the end find no live group
         const int64_t tiles_per_die = (gx + kConvDies - 1) / kConvDies;
         const int64_t blocks = tiles_per_die * kConvDies * gy;
         if (blocks >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         dim3 grid((uint32_t)blocks), block(kBlock);
-        if (y_dtype == GRANQ_F32)
-            launch_kernel((conv1x1_i8_mfma<F32, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
-        else if (y_dtype == GRANQ_BF16)
-            launch_kernel((conv1x1_i8_mfma<BF16, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
-        else
-            launch_kernel((conv1x1_i8_mfma<F16, PACKED>), grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o,
-                               groups_total, (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
-        if (launched() != GRANQ_OK) return GRANQ_ERR_HIP;
-        return GRANQ_OK;
+        conv_mfma_t kernel;
+        if constexpr (PACKED) kernel = mfma_kernel<true, false>(y_dtype);
+        else kernel = ragged ? mfma_kernel<false, true>(y_dtype) : mfma_kernel<false, false>(y_dtype);
+        launch_kernel(kernel, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o, groups_total,
+                      (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
+        return launched();
     }
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)o, (uint32_t)n), block(kBlock);
-    if (y_dtype == GRANQ_F32)
-        launch_kernel((conv1x1_i8_plain<F32, PACKED>), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
-    else if (y_dtype == GRANQ_BF16)
-        launch_kernel((conv1x1_i8_plain<BF16, PACKED>), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
-    else
-        launch_kernel((conv1x1_i8_plain<F16, PACKED>), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
+    launch_kernel(plain_kernel<PACKED>(y_dtype), grid, block, 0, hs, codes, wq, corr, out_scale, y, c, hw, o);
     return launched();
 }
 

@@ -55,10 +55,49 @@ def test_conv_mfma_path(shape, o, bits):
     _case(shape, o, bits)
 
 
+# matrix-core path with H*W no multiple of 4 (7 x 7 maps): a sample's last pixel group holds one, two or
+# three pixels and every access is aligned to one element only; both kernels (the second from 192 output
+# and 128 input channels on), tiles that span several samples, a ragged last tile
+@pytest.mark.parametrize("shape,o,bits", [
+    ((1, 16, 7, 7), 32, 4), ((3, 64, 7, 7), 64, 4), ((2, 64, 5, 5), 96, 3), ((1, 32, 3, 2), 32, 7),
+    ((2, 16, 9, 7), 64, 5), ((37, 48, 1, 5), 32, 4), ((2, 2048, 7, 7), 512, 4), ((5, 512, 7, 7), 2048, 4),
+    ((4, 128, 1, 5), 224, 6), ((3, 272, 3, 3), 320, 2), ((70, 160, 1, 7), 192, 4),
+])
+def test_conv_mfma_path_ragged_maps(shape, o, bits):
+    _case(shape, o, bits)
+
+
+def test_conv_ragged_maps_from_unaligned_pointers():
+    """With H*W no multiple of 4 the codes and y need the alignment of one element only."""
+    shape, o, bits = (3, 64, 7, 7), 64, 4
+    n, c, h, w = shape
+    x = workloads.make_activation(shape, "linear", (0.05, 20.0), 2, DEV)
+    out = gpu_path(x, bits)
+    g = torch.Generator(device=DEV).manual_seed(11)
+    wt = torch.randn(o, c, generator=g, device=DEV)
+    s = torch.from_numpy(out["scale"]).to(DEV)
+    z = torch.from_numpy(out["zero_point"]).to(DEV)
+    wq = torch.empty((o, c), dtype=torch.int8, device=DEV)
+    corr = torch.empty((o,), dtype=torch.int64, device=DEV)
+    a = torch.empty((o,), device=DEV)
+    G.granq_fold_weights(wt, s, z, wq, corr, a)
+    want = oracle.conv1x1_int8(out["codes"], wq.cpu().numpy(), corr.cpu().numpy(), a.cpu().numpy())
+    for shift in (1, 2, 3):
+        cbuf = torch.zeros(n * c * h * w + 8, dtype=torch.uint8, device=DEV)
+        codes = cbuf[shift:shift + n * c * h * w].view(shape)
+        codes.copy_(torch.from_numpy(out["codes"]).to(DEV))
+        ybuf = torch.full((n * o * h * w + 8,), float("nan"), device=DEV)
+        y = ybuf[shift:shift + n * o * h * w].view(n, o, h, w)
+        G.granq_conv1x1_int8(codes, wq, corr, a, bits, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_view(y.cpu().numpy()), bits_view(want)), shift
+        assert torch.isnan(ybuf[:shift]).all() and torch.isnan(ybuf[shift + n * o * h * w:]).all()
+
+
 # plain integer path: any other shape, and 8-bit codes
 @pytest.mark.parametrize("shape,o,bits", [
-    ((2, 7, 5, 5), 3, 4), ((1, 16, 7, 7), 32, 4), ((2, 24, 4, 4), 32, 4), ((2, 16, 4, 4), 40, 4),
-    ((2, 16, 8, 8), 32, 8), ((1, 1, 1, 1), 1, 1),
+    ((2, 7, 5, 5), 3, 4), ((1, 16, 1, 3), 32, 4), ((2, 24, 4, 4), 32, 4), ((2, 16, 4, 4), 40, 4),
+    ((2, 16, 8, 8), 32, 8), ((1, 1, 1, 1), 1, 1), ((2, 16, 7, 7), 32, 8),
 ])
 def test_conv_plain_path(shape, o, bits):
     _case(shape, o, bits)
@@ -66,7 +105,7 @@ def test_conv_plain_path(shape, o, bits):
 
 @pytest.mark.parametrize("ydtype", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
 @pytest.mark.parametrize("shape,o,bits", [((3, 64, 14, 14), 64, 4), ((2, 528, 4, 4), 96, 6), ((2, 7, 5, 5), 3, 4),
-                                          ((2, 16, 8, 8), 32, 8)])
+                                          ((2, 16, 8, 8), 32, 8), ((3, 64, 7, 7), 64, 4), ((2, 160, 5, 3), 256, 5)])
 def test_conv_output_in_16_bits(shape, o, bits, ydtype):
     """y stored as bfloat16 / binary16: the oracle's binary32 result narrowed with round to nearest
     even (torch's conversion for bfloat16, the oracle's own for binary16), bit for bit; both kernels."""
