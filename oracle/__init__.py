@@ -67,6 +67,7 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.granq_oracle_distortion.argtypes = [_ptr, _int, _i64, _i64, _i64, _ptr, _ptr, _int, _ptr, _ptr]
     lib.granq_oracle_fold_weights.argtypes = [_ptr, _ptr, _ptr, _i64, _i64, _ptr, _ptr, _ptr]
     lib.granq_oracle_conv1x1_int8.argtypes = [_ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
+    lib.granq_oracle_conv1x1_float.argtypes = [_ptr, _int, _i64, _i64, _i64, _i64, _ptr, _ptr]
     lib.granq_oracle_pack4.argtypes = [_ptr, _i64, _ptr]
     lib.granq_oracle_unpack4.argtypes = [_ptr, _i64, _ptr]
     lib.granq_oracle_accumulate_inloop.argtypes = [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _ptr]
@@ -231,6 +232,20 @@ def conv1x1_int8(codes: np.ndarray, wq: np.ndarray, corr: np.ndarray, out_scale:
     a = np.ascontiguousarray(out_scale, np.float32)
     y = np.empty((n, o) + codes.shape[2:], np.float32)
     lib.granq_oracle_conv1x1_int8(_p(codes), n, c, hw, o, _p(wq), _p(corr), _p(a), _p(y))
+    return y
+
+
+def conv1x1_float(x_hat: np.ndarray, w: np.ndarray, lib=None) -> np.ndarray:
+    """1x1 convolution over the pre-scaled activations in floating point (Eq. 6's accumulation):
+    y[n,o,...] = sum_c w[o,c] * x_hat[n,c,...], summed in binary64; returns float64.  w (O, C)
+    has x_hat's storage type."""
+    lib = lib or load()
+    n, c, hw = _nchw(x_hat)
+    if w.ndim != 2 or w.shape[1] != c or w.dtype != x_hat.dtype or not w.flags["C_CONTIGUOUS"]:
+        raise ValueError("w must be a C-contiguous (O, %d) array of x_hat's type" % c)
+    o = w.shape[0]
+    y = np.empty((n, o) + x_hat.shape[2:], np.float64)
+    lib.granq_oracle_conv1x1_float(_p(x_hat), _dtype_code(x_hat), n, c, hw, o, _p(w), _p(y))
     return y
 
 

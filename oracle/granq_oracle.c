@@ -475,6 +475,32 @@ void granq_oracle_conv1x1_int8(const uint8_t *codes, int64_t n, int64_t c, int64
 }
 
 /*
+ * The accumulation of Eq. 6 with a full weight matrix: the 1x1 convolution over the
+ * pre-scaled activations,
+ *     y[n,o,k] = sum_c w[o,c] * x_hat[n,c,k],
+ * in floating point.  This is the definition, summed in channel order in binary64: a product
+ * of two binary32 (or 16-bit) values is exact in binary64, so only the additions round, each
+ * to 2^-53.  w has x_hat's storage type, O rows of C.
+ */
+void granq_oracle_conv1x1_float(const void *x_hat, int dtype, int64_t n, int64_t c, int64_t hw,
+                                int64_t o, const void *w, double *y)
+{
+    for (int64_t in = 0; in < n; ++in) {
+        for (int64_t io = 0; io < o; ++io) {
+            for (int64_t k = 0; k < hw; ++k) {
+                double acc = 0.0;
+                for (int64_t ic = 0; ic < c; ++ic) {
+                    double wd = (double)load_elem(w, io * c + ic, dtype);
+                    double xd = (double)load_elem(x_hat, (in * c + ic) * hw + k, dtype);
+                    acc += wd * xd;
+                }
+                y[(in * o + io) * hw + k] = acc;
+            }
+        }
+    }
+}
+
+/*
  * Codes of at most four bits, two per byte (the integer operands of Eq. 3 stored at their own
  * width): byte i holds the code q of Eq. 1 of the element with flat index 2i in its low
  * nibble and that of element 2i + 1 in its high nibble; an odd element count leaves the last

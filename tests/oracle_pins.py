@@ -605,6 +605,64 @@ def check_packed_codes(lib=None):
     _eq(oracle.unpack4(oracle.pack4(codes, lib), codes.size, lib), codes.ravel(), "codes of a tensor")
 
 
+def check_float_convolution(lib=None):
+    """Eq. 6's accumulation with a full weight matrix: a hand-worked case, exact rational sums on
+    dyadic data, identity and permutation weights, numpy's float64 einsum, the one-weight-per-
+    channel sum it reduces to, Eq. 3's sum from the codes, and 16-bit storage."""
+    # by hand: x_hat (1,2,1,2) = [[1, 2], [3, 4]] (channel rows), w = [[1, 10], [0.5, -1]]
+    xh = np.array([[[[1.0, 2.0]], [[3.0, 4.0]]]], np.float32)
+    w = np.array([[1.0, 10.0], [0.5, -1.0]], np.float32)
+    y = oracle.conv1x1_float(xh, w, lib)
+    assert y.shape == (1, 2, 1, 2) and y.dtype == np.float64
+    _eq(y.ravel(), np.array([31.0, 42.0, -2.5, -3.0]), "hand-worked 2x2")
+    # dyadic values: every partial sum is exact, so the result is the rational sum
+    rng = np.random.default_rng(33)
+    n, c, hw, o = 2, 5, 3, 4
+    xh = (rng.integers(-64, 64, size=(n, c, hw)) / 8.0).astype(np.float32)
+    w = (rng.integers(-32, 32, size=(o, c)) / 4.0).astype(np.float32)
+    y = oracle.conv1x1_float(xh, w, lib)
+    for i in range(n):
+        for j in range(o):
+            for k in range(hw):
+                exact = sum(F(float(w[j, q])) * F(float(xh[i, q, k])) for q in range(c))
+                assert F(float(y[i, j, k])) == exact
+    # identity weights return x_hat, a permutation matrix permutes the channels, exactly
+    x = _workload_tensor("linear", (3, 6, 4, 5), seed=4)
+    xh, cd, s, z = oracle.fakequant(x, 4, lib)
+    _eq(oracle.conv1x1_float(xh, np.eye(6, dtype=np.float32), lib), xh.astype(np.float64), "identity")
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    _eq(oracle.conv1x1_float(xh, np.eye(6, dtype=np.float32)[perm], lib), xh[:, perm].astype(np.float64), "permutation")
+    # numpy's own contraction in float64 (another summation order: equal to rounding)
+    w = rng.standard_normal((7, 6)).astype(np.float32)
+    y = oracle.conv1x1_float(xh, w, lib)
+    ref = np.einsum("oc,nchw->nohw", w.astype(np.float64), xh.astype(np.float64))
+    mag = np.einsum("oc,nchw->nohw", np.abs(w).astype(np.float64), np.abs(xh).astype(np.float64))
+    assert np.all(np.abs(y - ref) <= 8 * 2.0 ** -53 * mag)
+    # one output row is the one-weight-per-channel sum of Eq. 6 (binary32 there: to its rounding)
+    y6 = oracle.accumulate_prescaled(xh, w[2], lib)
+    assert np.all(np.abs(y6 - y[:, 2]) <= 8 * 2.0 ** -24 * mag[:, 2])
+    # Eq. 3 from the codes, sum_c w s_c (q - z_c), is the same sum: x_hat = s_c (q - z_c) rounded once
+    deq = s.astype(np.float64).reshape(1, -1, 1, 1) * (cd.astype(np.float64) - z.astype(np.float64).reshape(1, -1, 1, 1))
+    y3 = np.einsum("oc,nchw->nohw", w.astype(np.float64), deq)
+    assert np.all(np.abs(y - y3) <= 2.0 ** -23 * mag)
+    # linear in the weights
+    w2 = rng.standard_normal((7, 6)).astype(np.float32)
+    both = oracle.conv1x1_float(xh, (w + w2).astype(np.float32), lib)
+    wsum = (w + w2).astype(np.float32).astype(np.float64)
+    assert np.all(np.abs(both - np.einsum("oc,nchw->nohw", wsum, xh.astype(np.float64))) <= 8 * 2.0 ** -53 * 4 * mag + 1e-300)
+    # 16-bit storage: the stored values widen exactly, the sum is over the widened values
+    xb = (xh.view(np.uint32) >> 16).astype(np.uint16)      # truncated to bfloat16: any bfloat16 values do
+    wb = (w.view(np.uint32) >> 16).astype(np.uint16)
+    yb = oracle.conv1x1_float(xb, wb, lib)
+    refb = np.einsum("oc,nchw->nohw", oracle.f32_from_bf16_bits(wb).astype(np.float64),
+                     oracle.f32_from_bf16_bits(xb).astype(np.float64))
+    assert np.all(np.abs(yb - refb) <= 8 * 2.0 ** -53 * mag * 1.1)
+    xf, wf = xh.astype(np.float16), w.astype(np.float16)
+    yf = oracle.conv1x1_float(xf, wf, lib)
+    reff = np.einsum("oc,nchw->nohw", wf.astype(np.float64), xf.astype(np.float64))
+    assert np.all(np.abs(yf - reff) <= 8 * 2.0 ** -53 * mag * 1.1)
+
+
 ALL_CHECKS = [
     check_golden,
     check_dyadic_grid_exhaustive,
@@ -625,4 +683,5 @@ ALL_CHECKS = [
     check_integer_accumulation,
     check_large_zero_point_term,
     check_packed_codes,
+    check_float_convolution,
 ]

@@ -56,6 +56,10 @@ MUTANTS = [
     ("unpack4_nibbles_swapped", "codes[i] = (i % 2 == 0) ? (uint8_t)(byte & 0x0F) : (uint8_t)(byte >> 4);", "codes[i] = (i % 2 == 1) ? (uint8_t)(byte & 0x0F) : (uint8_t)(byte >> 4);", 1),
     ("conv_correction_added", "(float)(acc - corr[io])", "(float)(acc + corr[io])", 1),
     ("conv_weights_transposed", "acc += (int64_t)wq[io * c + ic] * (int64_t)codes[(in * c + ic) * hw + k];", "acc += (int64_t)wq[ic * o + io] * (int64_t)codes[(in * c + ic) * hw + k];", 1),
+    ("float_conv_weights_transposed", "double wd = (double)load_elem(w, io * c + ic, dtype);", "double wd = (double)load_elem(w, ic * o + io, dtype);", 1),
+    ("float_conv_single_precision_sum", "double acc = 0.0;\n                for (int64_t ic = 0; ic < c; ++ic) {\n                    double wd", "float acc = 0.0;\n                for (int64_t ic = 0; ic < c; ++ic) {\n                    double wd", 1),
+    ("float_conv_skips_first_channel", "for (int64_t ic = 0; ic < c; ++ic) {\n                    double wd", "for (int64_t ic = 1; ic < c; ++ic) {\n                    double wd", 1),
+    ("float_conv_pixel_stride_is_channels", "double xd = (double)load_elem(x_hat, (in * c + ic) * hw + k, dtype);", "double xd = (double)load_elem(x_hat, (in * hw + k) * c + ic, dtype);", 1),
     ("bf16_ties_round_up", "(dropped == 0x8000u && (kept & 1u))", "(dropped == 0x8000u)", 1),
     ("bf16_truncates", "if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))", "if (0)", 1),
     ("f16_ties_round_up", "double steps = rint(ldexp((double)a, 10 - e));", "double steps = floor(ldexp((double)a, 10 - e) + 0.5);", 1),
