@@ -425,7 +425,7 @@ def integer_accumulation(wl, bits, device):
     weights) against torch's float32 and bfloat16 convolutions on x_hat (Eq. 6)."""
     stream = torch.cuda.current_stream()
     rows = {}
-    for c, o, hw in ((64, 64, 56), (64, 256, 56), (256, 64, 56), (1024, 256, 14)):
+    for c, o, hw in ((64, 64, 56), (64, 256, 56), (256, 64, 56), (1024, 256, 14), (512, 2048, 7), (2048, 512, 7)):
         shape = (wl.batch, c, hw, hw)
         x = workloads.make_activation(shape, "relu", wl.sigma, 1, device)
         q = G.ActivationQuantizer(shape, torch.float32, bits, device)
@@ -448,16 +448,25 @@ def integer_accumulation(wl, bits, device):
         # codes two per byte (4-bit and below): half a byte per element written and read
         packed = torch.empty(G.granq_packed4_bytes(q.desc), dtype=torch.uint8, device=device)
         t_qp = t_intp = None
-        if bits <= 4:
+        if bits <= 4 and (hw * hw) % 4 == 0:       # two codes per byte on the matrix cores: H*W a multiple of 4
             t_qp = _timeit(lambda: G.granq_fakequant_fwd_packed4(x_keep, q.scale, q.zero_point, bits, None, packed, stream, q.desc))
             t_intp = _timeit(lambda: G.granq_conv1x1_int8_packed4(packed, shape, wq, corr, a, bits, y, stream))
             G.granq_conv1x1_int8(codes, wq, corr, a, bits, y, stream)
         del x_keep, packed
+        # Eq. 6's accumulation in floating point: this library's kernel and torch's convolution
+        w2 = wt.view(o, c).contiguous()
+        yf = torch.empty_like(y)
+        t_own32 = _timeit(lambda: G.granq_conv1x1_float(xh, w2, yf, stream))
+        rel = float((y - yf).norm() / yf.norm())
         t_f32 = _timeit(lambda: torch.nn.functional.conv2d(xh, wt))
         ref = torch.nn.functional.conv2d(xh, wt)
-        rel = float((y - ref).norm() / ref.norm())
-        del ref
+        rel_own = float((yf - ref).norm() / ref.norm())
+        del ref, yf
         xh16, wt16 = xh.to(torch.bfloat16), wt.to(torch.bfloat16)
+        w216 = wt16.view(o, c).contiguous()
+        y16 = torch.empty(shape[0], o, hw, hw, dtype=torch.bfloat16, device=device)
+        t_own16 = _timeit(lambda: G.granq_conv1x1_float(xh16, w216, y16, stream))
+        del y16
         t_b16 = _timeit(lambda: torch.nn.functional.conv2d(xh16, wt16))
         e = codes.numel()
         ops = 2.0 * o * c * shape[0] * hw * hw
@@ -468,12 +477,16 @@ def integer_accumulation(wl, bits, device):
             "quantize_to_codes_only_us": round(t_q, 1), "quantize_GBs": round(e * 5 / t_q / 1e3, 1),
             "quantize_to_packed_codes_only_us": round(t_qp, 1) if t_qp else None,
             "int8_mfma_from_packed_codes_us": round(t_intp, 1) if t_intp else None,
+            "float_conv_on_x_hat_us": round(t_own32, 1), "float_conv_TFLOPs": round(ops / t_own32 / 1e6, 1),
+            "float_conv_on_bf16_x_hat_us": round(t_own16, 1),
             "torch_f32_conv_on_x_hat_us": round(t_f32, 1), "torch_bf16_conv_on_bf16_x_hat_us": round(t_b16, 1),
-            "relative_difference_to_float_conv": round(rel, 5)}
+            "relative_difference_to_float_conv": round(rel, 5),
+            "float_conv_relative_difference_to_torch": float("%.2e" % rel_own)}
         del xh, xh16, codes, y
         torch.cuda.empty_cache()
-    rows["note"] = ("int8 path reads 1 byte per activation and writes float32; torch float32 reads 4 and "
-                    "writes 4, torch bfloat16 reads 2 and writes 2")
+    rows["note"] = ("int8 path (Eq. 3 folded) reads 1 byte per activation and writes float32; the float "
+                    "convolutions (Eq. 6: this library's float_conv and torch's) read 4 and write 4 in float32, "
+                    "2 and 2 in bfloat16; float_conv accumulates in binary32 on the matrix cores for both")
     return rows
 
 

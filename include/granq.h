@@ -399,6 +399,26 @@ granq_status_t granq_conv1x1_int8_as(const uint8_t *codes, const granq_desc_t *d
                                      int bits, granq_dtype_t y_dtype, void *y, void *stream);
 
 /*
+ * The accumulation of Eq. 6 itself: the same 1x1 convolution in floating point over the
+ * pre-scaled activations x_hat = s_c (q - z_c) that granq_fakequant_fwd wrote,
+ *     y[n,o,k] = sum_c w[o,c] * x_hat[n,c,k],   k over H*W,
+ * the float-domain counterpart of granq_conv1x1_int8 (which computes Eq. 3's sum from the
+ * integer codes).  Products and sums are binary32, in an order the kernel chooses: for
+ * operands of magnitude far from the ends of the binary32 range the result lies within
+ * (C + 2) * 2^-24 * sum_c |w[o,c] x_hat[n,c,k]| of the exact sum; it is then rounded to y's type.
+ *   x_hat [in]  N*C*H*W elements of desc->dtype, NCHW;  w [in] O*C elements of the same type,
+ *   row o holding the C weights of output channel o;  y [out] N*O*H*W elements of the same type.
+ *   No pointer may alias another.
+ * The matrix-core kernel needs C a multiple of 8, O a multiple of 32, H*W >= 4 and w aligned
+ * to four elements; with H*W a multiple of 4 also x_hat and y aligned to four elements (with
+ * any other H*W the alignment of one element suffices).  Anything else runs a plain kernel
+ * (one thread per output, channels in order).  GRANQ_ERR_UNSUPPORTED: O or N >= 65536,
+ * C >= 2^24, or a pointer not aligned to its element.
+ */
+granq_status_t granq_conv1x1_float(const void *x_hat, const granq_desc_t *desc, int64_t o,
+                                   const void *w, void *y, void *stream);
+
+/*
  * Codes at their own width: for bits <= 4 the code q of Eq. 1 fits a nibble, and the integer
  * operands of Eq. 3 can be stored two per byte -- half a byte per element written by the
  * quantize step and read by the convolution.

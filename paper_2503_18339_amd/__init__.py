@@ -14,6 +14,7 @@ from .binding import (granq_rowwise_fakequant_bwd_multi, granq_rowwise_fakequant
 from .binding import granq_calibrate, granq_calibrate_fakequant_fwd, granq_conv1x1_int8, granq_conv1x1_int8_as, granq_fold_weights
 from .binding import granq_distortion, granq_distortion_workspace_bytes
 from .binding import granq_conv1x1_int8_packed4, granq_fakequant_fwd_packed4, granq_packed4_bytes
+from .binding import granq_conv1x1_float
 from .binding import (granq_calibrate_fakequant_fwd_resident, granq_resident_state_bytes,
                       granq_resident_state_init)
 from .binding import (granq_cmp_accumulate_inloop, granq_cmp_accumulate_prescaled,
@@ -25,7 +26,7 @@ __all__ = [
     "GRANQ_ERR_HIP", "GRANQ_F32", "GRANQ_BF16", "GRANQ_F16", "GranqError", "granq_desc_t", "make_desc", "desc_of",
     "granq_workspace_bytes", "granq_plan_describe", "granq_range_reduce", "granq_range_reduce_noalloc", "granq_prescale", "granq_calibrate", "granq_calibrate_fakequant_fwd", "granq_conv1x1_int8_as", "granq_fakequant_fwd",
     "granq_fakequant_bwd", "load", "library_path", "status_string", "version",
-    "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_packed4", "granq_fakequant_fwd_packed4",
+    "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_packed4", "granq_conv1x1_float", "granq_fakequant_fwd_packed4",
     "granq_packed4_bytes",
     "granq_distortion", "granq_distortion_workspace_bytes",
     "granq_calibrate_fakequant_fwd_resident", "granq_resident_state_bytes", "granq_resident_state_init",

@@ -33,7 +33,7 @@ EXPORTS = ("granq_status_string", "granq_version", "granq_workspace_bytes", "gra
            "granq_fakequant_fwd_mask", "granq_fakequant_bwd_mask", "granq_rowwise_fakequant_multi",
            "granq_rowwise_fakequant_bwd_multi", "granq_distortion_workspace_bytes", "granq_distortion",
            "granq_fold_weights", "granq_conv1x1_int8", "granq_conv1x1_int8_as", "granq_packed4_bytes",
-           "granq_fakequant_fwd_packed4", "granq_conv1x1_int8_packed4")
+           "granq_fakequant_fwd_packed4", "granq_conv1x1_int8_packed4", "granq_conv1x1_float")
 COMPARE_EXPORTS = ("granq_cmp_channel_loop_fwd", "granq_cmp_accumulate_inloop",
                    "granq_cmp_accumulate_prescaled")
 
@@ -107,6 +107,7 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.granq_packed4_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_fakequant_fwd_packed4.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp]
     lib.granq_conv1x1_int8_packed4.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int, _vp, _vp]
+    lib.granq_conv1x1_float.argtypes = [_vp, dp, ctypes.c_int64, _vp, _vp, _vp]
     lib.granq_distortion_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.granq_distortion.argtypes = [_vp, dp, _vp, _vp, ctypes.c_int, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.granq_cmp_channel_loop_fwd.argtypes = [_vp, dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -501,6 +502,22 @@ def granq_conv1x1_int8_packed4(packed: torch.Tensor, shape, wq: torch.Tensor, co
                                              _dev(corr, "corr"), _vec(out_scale, o, "out_scale"), int(bits),
                                              dtype_code(y.dtype), _dev(y, "y"), _stream(stream)),
            "granq_conv1x1_int8_packed4")
+
+
+def granq_conv1x1_float(x_hat: torch.Tensor, w: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    """y[n,o] = sum_c w[o,c] * x_hat[n,c] over an (N, C, H, W) tensor; w (O, C) and y (N, O, H, W)
+    have x_hat's dtype."""
+    if x_hat.dim() != 4:
+        raise ValueError("x_hat must be an (N, C, H, W) tensor")
+    n, c, h, wd = (int(v) for v in x_hat.shape)
+    o = int(w.shape[0])
+    if w.dtype != x_hat.dtype or w.numel() != o * c:
+        raise ValueError("w must be (O, C) of x_hat's dtype")
+    if y.dtype != x_hat.dtype or y.numel() != n * o * h * wd:
+        raise ValueError("y must be (N, O, H, W) of x_hat's dtype")
+    d = make_desc(n, c, h, wd, dtype_code(x_hat.dtype))
+    _check(load().granq_conv1x1_float(_dev(x_hat, "x_hat"), ctypes.byref(d), o, _dev(w, "w"), _dev(y, "y"),
+                                      _stream(stream)), "granq_conv1x1_float")
 
 
 def granq_distortion_workspace_bytes(desc: granq_desc_t) -> int:

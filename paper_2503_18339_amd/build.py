@@ -14,9 +14,10 @@ SOURCES = [os.path.join(CSRC, "granq_kernels.hip"), os.path.join(CSRC, "granq_co
            os.path.join(CSRC, "granq_rowwise.hip"),
            os.path.join(CSRC, "granq_metrics.hip"),
            os.path.join(CSRC, "granq_conv.hip"),
+           os.path.join(CSRC, "granq_fconv.hip"),
            os.path.join(CSRC, "granq_fused.hip")]
 HEADERS = [os.path.join(CSRC, "granq_device.h"), os.path.join(CSRC, "granq_plan.h"),
-           os.path.join(CSRC, "granq_block.h"), os.path.join(CSRC, "granq_launch.h"), os.path.join(CSRC, "granq_internal.h"), os.path.join(CSRC, "granq_tiling.h"),
+           os.path.join(CSRC, "granq_block.h"), os.path.join(CSRC, "granq_pixels.h"), os.path.join(CSRC, "granq_launch.h"), os.path.join(CSRC, "granq_internal.h"), os.path.join(CSRC, "granq_tiling.h"),
            os.path.join(CSRC, "granq_quotient.h"), os.path.join(INCLUDE, "granq.h"),
            os.path.join(INCLUDE, "granq_compare.h")]
 

@@ -22,6 +22,7 @@
 #include "granq.h"
 #include "granq_device.h"
 #include "granq_launch.h"
+#include "granq_pixels.h"
 
 namespace granq {
 
@@ -48,41 +49,6 @@ constexpr int kConvDies = 8;               // XCDs of the chip
 #define GRANQ_CONV_SHARED_MIN_C 128
 #endif
 constexpr int kConvPad = 16;               // bytes between LDS rows: 16-byte reads of 32 rows spread over all banks
-
-// Four neighbouring output pixels to y at element index `at` (a multiple of 4).
-template <typename OutT>
-__device__ __forceinline__ void store_pixels4(void *y, int64_t at, const f32x4 &v) {
-    if constexpr (OutT::ESIZE == 4) {
-        __builtin_nontemporal_store(v, (f32x4 *)((float *)y + at));
-    } else {
-        u32x2 w;
-        w.x = OutT::pack2(v.x, v.y);
-        w.y = OutT::pack2(v.z, v.w);
-        __builtin_nontemporal_store(w, (u32x2 *)((uint16_t *)y + at));
-    }
-}
-
-// The same when H*W is not a multiple of 4: a group's first pixel is then aligned to one element
-// only, and a sample's last group has `valid` < 4 pixels.
-template <typename OutT>
-__device__ __forceinline__ void store_pixels_ragged(void *y, int64_t at, const f32x4 &v, int valid) {
-    typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
-    typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
-    if (valid == 4) {
-        if constexpr (OutT::ESIZE == 4) {
-            __builtin_nontemporal_store(v, (f32x4_a4 *)((float *)y + at));
-        } else {
-            u32x2 w;
-            w.x = OutT::pack2(v.x, v.y);
-            w.y = OutT::pack2(v.z, v.w);
-            __builtin_nontemporal_store(w, (u32x2_a2 *)((uint16_t *)y + at));
-        }
-    } else {
-        OutT::store1(y, at, v.x);
-        if (valid > 1) OutT::store1(y, at + 1, v.y);
-        if (valid > 2) OutT::store1(y, at + 2, v.z);
-    }
-}
 
 // dword i of `d` holds four neighbouring pixels of channel i; the result's dword q of
 // operand j holds channels 4q .. 4q+3 of pixel j.
