@@ -161,6 +161,124 @@ __global__ __launch_bounds__(kBlock, 2) void fconv1x1_mfma(
     }
 }
 
+// 16-bit storage on the 16-bit matrix instruction (v_mfma_f32_32x32x16_bf16 / _f16: products of
+// the stored values exact, sums binary32).  Operands: A row l % 32, B column l % 32, both the
+// eight consecutive k starting at 8 * (l / 32), two per dword; D as above.  A lane loads, for its
+// eight channels, four neighbouring pixels each (8 bytes) and transposes the 8 x 4 halfwords in
+// registers (v_perm_b32) into four B operands; its weights of a step are 16 consecutive bytes of
+// its row.  One step = sixteen channels; tiles, tasks and the ragged case as in the kernel above.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ f32x16 mfma16(BF16, const u32x4 &a, const u32x4 &b, const f32x16 &c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma16(F16, const u32x4 &a, const u32x4 &b, const f32x16 &c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+constexpr int kFc16Step = 16;              // channels per matrix step
+
+template <typename T, bool RAGGED>
+__global__ __launch_bounds__(kBlock, 2) void fconv1x1_mfma16(
+    const void *__restrict__ x, const void *__restrict__ w, void *__restrict__ y, int64_t c, int64_t hw,
+    int64_t o, int64_t groups_total, int64_t tasks, int32_t sweeps, int32_t blocks_per_die)
+{
+    static_assert(T::ESIZE == 2, "16-bit storage");
+    typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
+    const int lane = threadIdx.x & (kWave - 1);
+    const int half = lane / 32, col = lane % 32;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    const uint32_t die = blockIdx.x % kFcDies, m = blockIdx.x / kFcDies;
+    const int64_t task = ((int64_t)die * blocks_per_die + m) * (kBlock / kWave) + wave;
+    if (task >= tasks) return;                          // wave-uniform; the kernel has no barrier
+    const int64_t tile = task / sweeps;
+    const int64_t o_base = (task - tile * sweeps) * kFcRows;
+    const int64_t g = tile * 32 + col;
+    const bool live = g < groups_total;
+    const int64_t hw4 = RAGGED ? (hw + 3) / 4 : hw / 4;
+    const int64_t n = live ? g / hw4 : 0;
+    const int64_t pb = live ? 4 * (g - n * hw4) : 0;
+    const int valid = RAGGED && hw - pb < 4 ? (int)(hw - pb) : 4;
+    const int64_t pl = valid == 4 ? pb : hw - 4;
+    const int down = 16 * (4 - valid);                  // bits to move the last group's vector down by
+    const uint16_t *xp = (const uint16_t *)x + (n * c + 8 * half) * hw + pl;
+    const uint16_t *wp[kFcT];
+#pragma unroll
+    for (int t = 0; t < kFcT; ++t) {
+        const int64_t row = o_base + 32 * t + col < o ? o_base + 32 * t + col : o - 1;
+        wp[t] = (const uint16_t *)w + row * c + 8 * half;
+    }
+
+    f32x16 acc[kFcT][4];
+#pragma unroll
+    for (int t = 0; t < kFcT; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][j][r] = 0.0f;
+
+    // a step's raw loads: the weights as they are, the lane's eight channels x four pixels
+    auto fetch = [&](int64_t c0, u32x4 (&fa)[kFcT], u32x2 (&fd)[8]) {
+#pragma unroll
+        for (int t = 0; t < kFcT; ++t) fa[t] = *(const u32x4 *)(wp[t] + c0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (RAGGED) fd[i] = *(const u32x2_a2 *)(xp + (c0 + i) * hw);
+            else fd[i] = *(const u32x2 *)(xp + (c0 + i) * hw);
+        }
+    };
+    auto multiply = [&](const u32x4 (&fa)[kFcT], const u32x2 (&fd)[8]) {
+        u32x4 b[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32x2 d0 = fd[2 * q], d1 = fd[2 * q + 1];
+            if (RAGGED) {
+                const uint64_t s0 = (((uint64_t)d0.y << 32) | d0.x) >> down, s1 = (((uint64_t)d1.y << 32) | d1.x) >> down;
+                d0 = (u32x2){(uint32_t)s0, (uint32_t)(s0 >> 32)};
+                d1 = (u32x2){(uint32_t)s1, (uint32_t)(s1 >> 32)};
+            }
+            // v_perm_b32(hi, lo, sel): selector bytes 0..3 pick bytes of lo, 4..7 bytes of hi
+            b[0][q] = __builtin_amdgcn_perm(d1.x, d0.x, 0x05040100u);   // pixel 0 of channels 2q, 2q + 1
+            b[1][q] = __builtin_amdgcn_perm(d1.x, d0.x, 0x07060302u);   // pixel 1
+            b[2][q] = __builtin_amdgcn_perm(d1.y, d0.y, 0x05040100u);   // pixel 2
+            b[3][q] = __builtin_amdgcn_perm(d1.y, d0.y, 0x07060302u);   // pixel 3
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int t = 0; t < kFcT; ++t) acc[t][j] = mfma16(T{}, fa[t], b[j], acc[t][j]);
+    };
+    u32x4 a[kFcT];
+    u32x2 d[8];
+    fetch(0, a, d);
+    for (int64_t c0 = 0; c0 < c; c0 += kFc16Step) {
+        u32x4 na[kFcT];
+        u32x2 nd[8];
+        const bool more = c0 + kFc16Step < c;           // wave-uniform
+        if (more) fetch(c0 + kFc16Step, na, nd);
+        multiply(a, d);
+        if (more) {
+#pragma unroll
+            for (int t = 0; t < kFcT; ++t) a[t] = na[t];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) d[i] = nd[i];
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int t = 0; t < kFcT; ++t) {
+        if (o_base + 32 * t >= o) break;                // wave-uniform
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+            const f32x4 v = {acc[t][0][r], acc[t][1][r], acc[t][2][r], acc[t][3][r]};
+            if constexpr (RAGGED) store_pixels_ragged<T>(y, (n * o + oc) * hw + pb, v, valid);
+            else store_pixels4<T>(y, (n * o + oc) * hw + pb, v);
+        }
+    }
+}
+
 // Any shape: one thread per output element, binary32 multiply and add in channel order.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fconv1x1_plain(
@@ -186,10 +304,13 @@ typedef void (*fconv_mfma_t)(const void *, const void *, void *, int64_t, int64_
                              int32_t, int32_t);
 typedef void (*fconv_plain_t)(const void *, const void *, void *, int64_t, int64_t, int64_t);
 
+// 16-bit storage: the 16-bit matrix instruction when C is a multiple of 16 (and the eight weights
+// of a lane are 16-byte aligned), else the binary32 one on widened values
 template <bool RAGGED>
-static fconv_mfma_t fconv_mfma_kernel(granq_dtype_t t) {
-    return t == GRANQ_F32 ? fconv1x1_mfma<F32, RAGGED>
-                          : (t == GRANQ_BF16 ? fconv1x1_mfma<BF16, RAGGED> : fconv1x1_mfma<F16, RAGGED>);
+static fconv_mfma_t fconv_mfma_kernel(granq_dtype_t t, bool sixteen) {
+    if (t == GRANQ_F32) return fconv1x1_mfma<F32, RAGGED>;
+    if (t == GRANQ_BF16) return sixteen ? fconv1x1_mfma16<BF16, RAGGED> : fconv1x1_mfma<BF16, RAGGED>;
+    return sixteen ? fconv1x1_mfma16<F16, RAGGED> : fconv1x1_mfma<F16, RAGGED>;
 }
 
 extern "C" granq_status_t granq_conv1x1_float(const void *x_hat, const granq_desc_t *desc, int64_t o,
@@ -218,7 +339,8 @@ extern "C" granq_status_t granq_conv1x1_float(const void *x_hat, const granq_des
         const int64_t blocks_per_die = ((tasks + per_block - 1) / per_block + kFcDies - 1) / kFcDies;
         if (blocks_per_die * kFcDies >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
         dim3 grid((uint32_t)(blocks_per_die * kFcDies)), block(kBlock);
-        fconv_mfma_t kernel = ragged ? fconv_mfma_kernel<true>(t) : fconv_mfma_kernel<false>(t);
+        const bool sixteen = esize == 2 && c % kFc16Step == 0 && ((uintptr_t)w & 15u) == 0;
+        fconv_mfma_t kernel = ragged ? fconv_mfma_kernel<true>(t, sixteen) : fconv_mfma_kernel<false>(t, sixteen);
         launch_kernel(kernel, grid, block, 0, hs, x_hat, w, y, c, hw, o, groups_total, tasks, (int32_t)sweeps,
                       (int32_t)blocks_per_die);
         return launched();
