@@ -51,11 +51,18 @@ def _short(name: str) -> str:
     return name[:cut] if cut > 0 else name
 
 
-def summarise_trace(stats_csv: str) -> str:
+def summarise_trace(stats_csv: str, match: str = "") -> str:
+    """One line per kernel of a rocprofv3 --stats file.  `match`: a regular expression; only kernels
+    whose name matches are listed (a run that also holds a framework's search or warm-up kernels),
+    however small their share."""
+    import re
     rows = list(csv.DictReader(open(stats_csv)))
     out = ["%-58s %7s %12s %10s %7s" % ("kernel", "calls", "avg_us", "total_ms", "%")]
     for r in rows:
-        if float(r["Percentage"]) < 0.05:
+        if match:
+            if not re.search(match, r["Name"]):
+                continue
+        elif float(r["Percentage"]) < 0.05:
             continue
         out.append("%-58s %7d %12.2f %10.2f %7.2f" % (
             _short(r["Name"])[:58], int(r["Calls"]), float(r["AverageNs"]) / 1e3,
@@ -179,6 +186,7 @@ def main(argv=None):
     t.add_argument("stats_csv")
     t.add_argument("--title", help="what was run (default: the default benchmark run)")
     t.add_argument("--command", help="the rocprofv3 command that made the file")
+    t.add_argument("--match", default="", help="regular expression a kernel name must match to be listed")
     c = sub.add_parser("counters")
     c.add_argument("fetch_csv")
     c.add_argument("write_csv")
@@ -193,10 +201,10 @@ def main(argv=None):
     if args.cmd == "trace":
         if args.title:
             print(_header(args.title, args.command or "", "python -m paper_2503_18339_amd.profiling trace "
-                          "<stats csv> --title ... --command ..."))
+                          "<stats csv> --title ... --command ..." + (" --match '%s'" % args.match if args.match else "")))
         else:
             print(TRACE_HEADER)
-        print(summarise_trace(args.stats_csv))
+        print(summarise_trace(args.stats_csv, args.match))
     elif args.cmd == "pmc":
         print(_header(args.title, args.command, "python -m paper_2503_18339_amd.profiling pmc "
                       "<counter_collection csv> --title ... --command ..."))
