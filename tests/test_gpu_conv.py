@@ -267,3 +267,38 @@ def test_packed_codes_argument_checks():
     assert lib.granq_fakequant_fwd_packed4(16, ctypes.byref(d), 16, 16, 4, 16, 0, 0) == G.GRANQ_ERR_INVALID_ARG
     assert lib.granq_conv1x1_int8_packed4(16, ctypes.byref(d), 32, 16, 16, 16, 5, 0, 16, 0) == G.GRANQ_ERR_INVALID_ARG
     assert G.granq_packed4_bytes(G.make_desc(1, 1, 1, 9, 0)) == 5
+
+
+@pytest.mark.parametrize("c,o,hw", [(1024, 256, 14), (2048, 512, 7), (64, 256, 56)])
+def test_conv_at_benchmark_size_on_sampled_outputs(c, o, hw):
+    """The shapes and the batch that bench.py times (a launch of the same configuration): 4096 sampled
+    outputs, each recomputed from the definition in exact integer arithmetic (the oracle's expression,
+    one output at a time), must match bit for bit; the packed form must give the same tensor."""
+    n, bits = 256, 4
+    g = torch.Generator(device=DEV).manual_seed(c + o)
+    codes = torch.randint(0, 1 << bits, (n, c, hw, hw), dtype=torch.uint8, generator=g, device=DEV)
+    wq = torch.randint(-127, 128, (o, c), dtype=torch.int8, generator=g, device=DEV)
+    corr = torch.randint(-(1 << 20), 1 << 20, (o,), dtype=torch.int64, generator=g, device=DEV)
+    a = torch.rand(o, generator=g, device=DEV) * 0.01 + 1e-4
+    y = torch.full((n, o, hw, hw), float("nan"), device=DEV)
+    G.granq_conv1x1_int8(codes, wq, corr, a, bits, y)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    idx_n = rng.integers(0, n, 4096)
+    idx_o = rng.integers(0, o, 4096)
+    idx_k = rng.integers(0, hw * hw, 4096)
+    # always among the samples: the corners and a sample's last pixel (the ragged group of a 7 x 7 map)
+    idx_n[:4], idx_o[:4], idx_k[:4] = [0, n - 1, 0, n - 1], [0, o - 1, o - 1, 0], [0, hw * hw - 1, hw * hw - 1, 0]
+    cn = codes.view(n, c, hw * hw)[torch.from_numpy(idx_n).to(DEV), :, torch.from_numpy(idx_k).to(DEV)].cpu().numpy().astype(np.int64)
+    wn = wq.cpu().numpy().astype(np.int64)[idx_o]
+    acc = (cn * wn).sum(axis=1) - corr.cpu().numpy()[idx_o]
+    want = a.cpu().numpy()[idx_o] * acc.astype(np.float32)          # one conversion, one product: as the oracle
+    got = y.view(n, o, hw * hw).cpu().numpy()[idx_n, idx_o, idx_k]
+    assert np.array_equal(bits_view(got), bits_view(want.astype(np.float32)))
+    assert not torch.isnan(y).any()
+    if (hw * hw) % 4 == 0:
+        packed = torch.from_numpy(oracle.pack4(codes.cpu().numpy())).to(DEV)
+        y2 = torch.full((n, o, hw, hw), float("nan"), device=DEV)
+        G.granq_conv1x1_int8_packed4(packed, (n, c, hw, hw), wq, corr, a, bits, y2)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y2)

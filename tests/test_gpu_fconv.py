@@ -152,3 +152,29 @@ def test_float_conv_unaligned_pointers_and_argument_checks():
     assert lib.granq_conv1x1_float(18, ctypes.byref(d), 32, 16, 16, 0) == G.GRANQ_ERR_UNSUPPORTED
     bad = G.make_desc(2, 16, 4, 4, 7)
     assert lib.granq_conv1x1_float(16, ctypes.byref(bad), 32, 16, 16, 0) == G.GRANQ_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("name", ["f32", "bf16"])
+@pytest.mark.parametrize("c,o,hw", [(1024, 256, 14), (2048, 512, 7), (64, 64, 56)])
+def test_float_conv_at_benchmark_size_on_sampled_outputs(c, o, hw, name):
+    """The shapes and the batch that bench.py times: 4096 sampled outputs, each recomputed from the
+    definition in binary64, within the bound of this file's header."""
+    n = 256
+    g = torch.Generator(device=DEV).manual_seed(c + o + 1)
+    xh = (torch.randn(n, c, hw, hw, generator=g, device=DEV) * 3).to(TORCH[name])
+    w = _weights(o, c, TORCH[name], seed=c)
+    y = torch.full((n, o, hw, hw), float("nan"), dtype=TORCH[name], device=DEV)
+    G.granq_conv1x1_float(xh, w, y)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    idx_n, idx_o, idx_k = rng.integers(0, n, 4096), rng.integers(0, o, 4096), rng.integers(0, hw * hw, 4096)
+    idx_n[:4], idx_o[:4], idx_k[:4] = [0, n - 1, 0, n - 1], [0, o - 1, o - 1, 0], [0, hw * hw - 1, hw * hw - 1, 0]
+    tn, tk, to = (torch.from_numpy(v).to(DEV) for v in (idx_n, idx_k, idx_o))
+    xs = xh.view(n, c, hw * hw)[tn, :, tk].double().cpu().numpy()
+    ws = w[to].double().cpu().numpy()
+    want = (xs * ws).sum(axis=1)
+    mag = (np.abs(xs) * np.abs(ws)).sum(axis=1)
+    got = y.view(n, o, hw * hw)[tn, to, tk].double().cpu().numpy()
+    tol = (c + 2) * 2.0 ** -24 * mag + HALF_ULP[name] * 1.0001 * np.abs(want) + 2.0 ** -100
+    assert np.all(np.abs(got - want) <= tol)
+    assert not torch.isnan(y.float()).any()
