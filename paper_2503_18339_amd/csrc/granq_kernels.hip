@@ -1634,11 +1634,23 @@ namespace granq {
 // Polls of a hand-over slot before a waiting wavefront of the finishing forward computes the
 // parameters itself (about a microsecond each).  GRANQ_SPIN_LIMIT in the environment
 // overrides it; tests set it to 0 so that every waiting wavefront takes that path.
-static int32_t spin_limit() {
+// Small tensors with large maps do not wait at all: their launch is over in a few microseconds, of
+// which the finishers' gather -> Eq. 5 -> publish -> poll chain is two to three, while a wavefront
+// that gathers its own channel's partials (from the caches) loses about one.  Elsewhere the order
+// reverses: on large tensors thousands of blocks would each repeat the gather, and where a
+// wavefront's row of vectors spans many channels (7 x 7 maps) it would gather them one by one.
+#ifndef GRANQ_SELF_DERIVE_MAX_BYTES
+#define GRANQ_SELF_DERIVE_MAX_BYTES (24u << 20)
+#endif
+static int32_t spin_limit(const granq_desc_t *desc = nullptr) {
     const char *e = getenv("GRANQ_SPIN_LIMIT");
     if (e && *e) {
         const long v = strtol(e, nullptr, 10);
         return (int32_t)(v < 0 ? 0 : (v > (1 << 24) ? (1 << 24) : v));
+    }
+    if (desc) {
+        const int64_t wave_span = (int64_t)kWave * (desc->dtype == GRANQ_F32 ? 4 : 8);   // elements of one vector per lane
+        if (tensor_bytes(desc) <= (int64_t)GRANQ_SELF_DERIVE_MAX_BYTES && desc->h * desc->w >= wave_span) return 0;
     }
     return 20000;
 }
@@ -1692,7 +1704,7 @@ granq_status_t calibrate_fwd_two_launches(const void *x, const granq_desc_t *des
     fa.zero_point = zero_point;
     fa.rplan = cp;
     fa.finisher_rows = (int32_t)finisher_rows;
-    fa.spin_limit = spin_limit();
+    fa.spin_limit = spin_limit(desc);
     const int kind = !x_hat ? kCodesOnly : (codes_or_null ? kCodes : kNoExtra);
     if (desc->dtype == GRANQ_F32) launch_fwd_finish<F32, GRANQ_E_V_F32>(fp, x, x_hat, codes_or_null, kind, qmax, fa, hs);
     else if (desc->dtype == GRANQ_BF16) launch_fwd_finish<BF16, GRANQ_E_V_BF16>(fp, x, x_hat, codes_or_null, kind, qmax, fa, hs);
