@@ -181,9 +181,11 @@ granq_status_t granq_calibrate(const void *x, const granq_desc_t *desc, int bits
  * vector path take TWO: the first pass of the reduction, then the forward, whose leading
  * blocks finish the reduction (second pass, Eq. 5), write the four vectors and hand scale
  * and zero-point to the other blocks through the workspace (a block that finds them pending
- * fetches its rows, then polls; after GRANQ_SPIN_LIMIT polls -- environment, default 20000,
- * tests set 0 -- it derives them from the partials itself, so no block depends on another
- * one being scheduled); anything else takes the three launches of the two calls.
+ * fetches its rows, then polls; after GRANQ_SPIN_LIMIT polls -- environment; default 20000,
+ * and 0 for tensors up to 24 MB whose maps hold at least 64 vectors' elements, where waiting
+ * costs more than the work; tests set 0 -- it derives them from the partials itself, so no
+ * block depends on another one being scheduled); anything else takes the three launches of
+ * the two calls.
  */
 granq_status_t granq_calibrate_fakequant_fwd(const void *x, const granq_desc_t *desc, int bits,
                                              float *ch_min, float *ch_max,
