@@ -78,9 +78,9 @@ __device__ __forceinline__ void transpose_16x4(const uint32_t (&d)[16], i32x4 (&
 // eight dies round-robin in launch order and each die has its own L2, so the
 // re-reads of a tile's codes by its other sweep groups hit that L2; die d takes the d-th eighth of
 // the tiles, so that the cache lines a tile shares with its neighbours (a channel's row rarely
-// starts on a line) are fetched by one die only.  The channel loop is software-pipelined by hand: the loads of the next 32
-// channels are issued before the matrix instructions of the current ones, and
-// scheduling barriers keep them there.
+// starts on a line) are fetched by one die only.  The channel loop is software-pipelined by
+// hand: the loads of the next 32 channels are issued before the matrix instructions of the
+// current ones, and scheduling barriers keep them there.
 // OutT: storage of y (F32, BF16 or F16 traits): the binary32 result is narrowed on the store.
 // PACKED: the codes are two per byte; a lane then fetches its four pixels of a channel as one
 // 16-bit load and spreads the nibbles into bytes (six integer operations) before the transpose.
@@ -240,10 +240,10 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
 // codes are fetched and transposed once per 256 output channels instead of once per 64.
 // Channels go in chunks of 128 (four 32-channel steps; 256 with two blocks' worth of LDS measured
 // slower: 52 against 39 us on 1024 -> 256 channels at 14 x 14, batch 256): wavefront w fetches and
-// transposes step w (w + 4, ... with longer chunks) and writes its four B operands to LDS in exactly the lane order in which every
-// wavefront then reads them back; the chunk's weights (256 rows x 128 bytes) are staged beside
-// them.  The fetches of the next chunk (codes and weights, into registers) are in flight
-// during the multiplies of the current one.
+// transposes step w (w + 4, ... with longer chunks) and writes its four B operands to LDS in exactly
+// the lane order in which every wavefront then reads them back; the chunk's weights (256 rows x 128
+// bytes) are staged beside them.  The fetches of the next chunk (codes and weights, into registers)
+// are in flight during the multiplies of the current one.
 #ifndef GRANQ_CONV_SHARED_CHUNK
 #define GRANQ_CONV_SHARED_CHUNK 128
 #endif
