@@ -92,7 +92,7 @@ template <typename OutT, bool PACKED, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
-    int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride, int32_t tiles_per_die)
+    int64_t groups_total, int32_t sweeps_per_block, int32_t splits, int32_t lds_stride, int32_t tiles_per_die, int32_t stream_out)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_w[];   // kConvRows x lds_stride bytes
     const int lane = threadIdx.x & (kWave - 1);
@@ -212,25 +212,32 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma(
 #undef GRANQ_CONV_MULTIPLY
         }
         if (!live) continue;
+        auto epilogue = [&](auto stream) {
+            constexpr bool kStream = decltype(stream)::value;
+            if (!kStream) keep_apart();
 #pragma unroll
-        for (int t = 0; t < kConvOT; ++t) {
-            if (o_base + 32 * t >= o) break;           // wave-uniform: o is a multiple of 32
+            for (int t = 0; t < kConvOT; ++t) {
+                if (o_base + 32 * t >= o) break;       // wave-uniform: o is a multiple of 32
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
-                // the difference is exact in binary64 (|corr| < 2^48), so narrowing it rounds once:
-                // the same value as the conversion of the 64-bit integer difference
-                const double cz = (double)corr[oc];
-                const float sc = out_scale[oc];
-                f32x4 v;
-                v.x = sc * (float)((double)acc[t][0][r] - cz);
-                v.y = sc * (float)((double)acc[t][1][r] - cz);
-                v.z = sc * (float)((double)acc[t][2][r] - cz);
-                v.w = sc * (float)((double)acc[t][3][r] - cz);
-                if constexpr (RAGGED) store_pixels_ragged<OutT>(y, (n * o + oc) * hw + pb, v, valid);
-                else store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+                    // the difference is exact in binary64 (|corr| < 2^48), so narrowing it rounds once:
+                    // the same value as the conversion of the 64-bit integer difference
+                    const double cz = (double)corr[oc];
+                    const float sc = out_scale[oc];
+                    f32x4 v;
+                    v.x = sc * (float)((double)acc[t][0][r] - cz);
+                    v.y = sc * (float)((double)acc[t][1][r] - cz);
+                    v.z = sc * (float)((double)acc[t][2][r] - cz);
+                    v.w = sc * (float)((double)acc[t][3][r] - cz);
+                    if constexpr (RAGGED) store_pixels_ragged<OutT, kStream>(y, (n * o + oc) * hw + pb, v, valid);
+                    else store_pixels4<OutT, kStream>(y, (n * o + oc) * hw + pb, v);
+                }
             }
-        }
+            if (!kStream) keep_apart();
+        };
+        if (stream_out) epilogue(Flag<true>{});
+        else epilogue(Flag<false>{});
     }
 }
 
@@ -257,7 +264,7 @@ template <typename OutT, bool PACKED, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
     const uint8_t *__restrict__ codes, const int8_t *__restrict__ wq, const int64_t *__restrict__ corr,
     const float *__restrict__ out_scale, void *__restrict__ y, int64_t c, int64_t hw, int64_t o,
-    int64_t groups_total, int32_t supers, int32_t tiles_per_die)
+    int64_t groups_total, int32_t supers, int32_t tiles_per_die, int32_t stream_out)
 {
     static_assert(kShChunk % 128 == 0, "four wavefronts share the steps of a chunk evenly");
     constexpr int kStride = kShChunk + kConvPad;
@@ -380,23 +387,30 @@ __global__ __launch_bounds__(kBlock, 2) void conv1x1_i8_mfma_shared(
         }
     }
     if (!live) return;
+    auto epilogue = [&](auto stream) {
+        constexpr bool kStream = decltype(stream)::value;
+        if (!kStream) keep_apart();
 #pragma unroll
-    for (int t = 0; t < kConvOT; ++t) {
-        if (o_base + 32 * t >= o) break;                   // wave-uniform: o is a multiple of 32
+        for (int t = 0; t < kConvOT; ++t) {
+            if (o_base + 32 * t >= o) break;               // wave-uniform: o is a multiple of 32
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
-            const double cz = (double)corr[oc];
-            const float sc = out_scale[oc];
-            f32x4 v;
-            v.x = sc * (float)((double)acc[t][0][r] - cz);
-            v.y = sc * (float)((double)acc[t][1][r] - cz);
-            v.z = sc * (float)((double)acc[t][2][r] - cz);
-            v.w = sc * (float)((double)acc[t][3][r] - cz);
-            if constexpr (RAGGED) store_pixels_ragged<OutT>(y, (n * o + oc) * hw + pb, v, valid);
-            else store_pixels4<OutT>(y, (n * o + oc) * hw + pb, v);
+            for (int r = 0; r < 16; ++r) {
+                const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+                const double cz = (double)corr[oc];
+                const float sc = out_scale[oc];
+                f32x4 v;
+                v.x = sc * (float)((double)acc[t][0][r] - cz);
+                v.y = sc * (float)((double)acc[t][1][r] - cz);
+                v.z = sc * (float)((double)acc[t][2][r] - cz);
+                v.w = sc * (float)((double)acc[t][3][r] - cz);
+                if constexpr (RAGGED) store_pixels_ragged<OutT, kStream>(y, (n * o + oc) * hw + pb, v, valid);
+                else store_pixels4<OutT, kStream>(y, (n * o + oc) * hw + pb, v);
+            }
         }
-    }
+        if (!kStream) keep_apart();
+    };
+    if (stream_out) epilogue(Flag<true>{});
+    else epilogue(Flag<false>{});
 }
 
 // Any shape: one thread per output element, integer loop over the channels.
@@ -466,9 +480,9 @@ __global__ __launch_bounds__(kBlock) void fold_weights_kernel(
 using namespace granq;
 
 typedef void (*conv_shared_t)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
-                              int64_t, int64_t, int64_t, int32_t, int32_t);
+                              int64_t, int64_t, int64_t, int32_t, int32_t, int32_t);
 typedef void (*conv_mfma_t)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
-                            int64_t, int64_t, int64_t, int32_t, int32_t, int32_t, int32_t);
+                            int64_t, int64_t, int64_t, int32_t, int32_t, int32_t, int32_t, int32_t);
 typedef void (*conv_plain_t)(const uint8_t *, const int8_t *, const int64_t *, const float *, void *, int64_t,
                              int64_t, int64_t);
 
@@ -511,6 +525,7 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
     const bool mfma = shape_ok && (ragged ? !PACKED && hw >= 4
                                           : ((uintptr_t)codes & (PACKED ? 1u : 3u)) == 0 && ((uintptr_t)y & (4 * esize - 1)) == 0);
     const int64_t groups_total = n * ((hw + 3) / 4);
+    const int32_t stream_out = n * o * hw * (int64_t)esize > GRANQ_CONV_STREAM_OUT_BYTES;
     // many output and input channels: four wavefronts share one pixel tile's transposed codes
     if (mfma && GRANQ_CONV_SHARED && o >= GRANQ_CONV_SHARED_MIN_O && c >= GRANQ_CONV_SHARED_MIN_C) {
         const int64_t tiles = (groups_total + 31) / 32;
@@ -527,7 +542,7 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return GRANQ_ERR_HIP;
         launch_kernel(kernel, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o, groups_total,
-                      (int32_t)supers, (int32_t)tiles_per_die);
+                      (int32_t)supers, (int32_t)tiles_per_die, stream_out);
         return launched();
     }
     if (mfma) {
@@ -552,7 +567,7 @@ static granq_status_t conv_impl(const uint8_t *codes, const granq_desc_t *desc, 
         if constexpr (PACKED) kernel = mfma_kernel<true, false>(y_dtype);
         else kernel = ragged ? mfma_kernel<false, true>(y_dtype) : mfma_kernel<false, false>(y_dtype);
         launch_kernel(kernel, grid, block, lds_bytes, hs, codes, wq, corr, out_scale, y, c, hw, o, groups_total,
-                      (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die);
+                      (int32_t)spb, (int32_t)gy, lds_stride, (int32_t)tiles_per_die, stream_out);
         return launched();
     }
     dim3 grid((uint32_t)((hw + kBlock - 1) / kBlock), (uint32_t)o, (uint32_t)n), block(kBlock);

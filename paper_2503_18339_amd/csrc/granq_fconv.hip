@@ -69,7 +69,7 @@ __device__ __forceinline__ f32x4 load4(const void *p, int64_t at) {
 template <typename T, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void fconv1x1_mfma(
     const void *__restrict__ x, const void *__restrict__ w, void *__restrict__ y, int64_t c, int64_t hw,
-    int64_t o, int64_t groups_total, int64_t tasks, int32_t sweeps, int32_t blocks_per_die)
+    int64_t o, int64_t groups_total, int64_t tasks, int32_t sweeps, int32_t blocks_per_die, int32_t stream_out)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int half = lane / 32, col = lane % 32;
@@ -148,17 +148,24 @@ __global__ __launch_bounds__(kBlock, 2) void fconv1x1_mfma(
         }
     }
     if (!live) return;
+    auto epilogue = [&](auto stream) {
+        constexpr bool kStream = decltype(stream)::value;
+        if (!kStream) keep_apart();
 #pragma unroll
-    for (int t = 0; t < kFcT; ++t) {
-        if (o_base + 32 * t >= o) break;                // wave-uniform
+        for (int t = 0; t < kFcT; ++t) {
+            if (o_base + 32 * t >= o) break;            // wave-uniform
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
-            const f32x4 v = {acc[t][0][r], acc[t][1][r], acc[t][2][r], acc[t][3][r]};
-            if constexpr (RAGGED) store_pixels_ragged<T>(y, (n * o + oc) * hw + pb, v, valid);
-            else store_pixels4<T>(y, (n * o + oc) * hw + pb, v);
+            for (int r = 0; r < 16; ++r) {
+                const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+                const f32x4 v = {acc[t][0][r], acc[t][1][r], acc[t][2][r], acc[t][3][r]};
+                if constexpr (RAGGED) store_pixels_ragged<T, kStream>(y, (n * o + oc) * hw + pb, v, valid);
+                else store_pixels4<T, kStream>(y, (n * o + oc) * hw + pb, v);
+            }
         }
-    }
+        if (!kStream) keep_apart();
+    };
+    if (stream_out) epilogue(Flag<true>{});
+    else epilogue(Flag<false>{});
 }
 
 // 16-bit storage on the 16-bit matrix instruction (v_mfma_f32_32x32x16_bf16 / _f16: products of
@@ -182,7 +189,7 @@ constexpr int kFc16Step = 16;              // channels per matrix step
 template <typename T, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void fconv1x1_mfma16(
     const void *__restrict__ x, const void *__restrict__ w, void *__restrict__ y, int64_t c, int64_t hw,
-    int64_t o, int64_t groups_total, int64_t tasks, int32_t sweeps, int32_t blocks_per_die)
+    int64_t o, int64_t groups_total, int64_t tasks, int32_t sweeps, int32_t blocks_per_die, int32_t stream_out)
 {
     static_assert(T::ESIZE == 2, "16-bit storage");
     typedef uint32_t u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
@@ -266,17 +273,24 @@ __global__ __launch_bounds__(kBlock, 2) void fconv1x1_mfma16(
         }
     }
     if (!live) return;
+    auto epilogue = [&](auto stream) {
+        constexpr bool kStream = decltype(stream)::value;
+        if (!kStream) keep_apart();
 #pragma unroll
-    for (int t = 0; t < kFcT; ++t) {
-        if (o_base + 32 * t >= o) break;                // wave-uniform
+        for (int t = 0; t < kFcT; ++t) {
+            if (o_base + 32 * t >= o) break;            // wave-uniform
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
-            const f32x4 v = {acc[t][0][r], acc[t][1][r], acc[t][2][r], acc[t][3][r]};
-            if constexpr (RAGGED) store_pixels_ragged<T>(y, (n * o + oc) * hw + pb, v, valid);
-            else store_pixels4<T>(y, (n * o + oc) * hw + pb, v);
+            for (int r = 0; r < 16; ++r) {
+                const int64_t oc = o_base + 32 * t + 8 * (r / 4) + 4 * half + (r % 4);
+                const f32x4 v = {acc[t][0][r], acc[t][1][r], acc[t][2][r], acc[t][3][r]};
+                if constexpr (RAGGED) store_pixels_ragged<T, kStream>(y, (n * o + oc) * hw + pb, v, valid);
+                else store_pixels4<T, kStream>(y, (n * o + oc) * hw + pb, v);
+            }
         }
-    }
+        if (!kStream) keep_apart();
+    };
+    if (stream_out) epilogue(Flag<true>{});
+    else epilogue(Flag<false>{});
 }
 
 // Any shape: one thread per output element, binary32 multiply and add in channel order.
@@ -301,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void fconv1x1_plain(
 using namespace granq;
 
 typedef void (*fconv_mfma_t)(const void *, const void *, void *, int64_t, int64_t, int64_t, int64_t, int64_t,
-                             int32_t, int32_t);
+                             int32_t, int32_t, int32_t);
 typedef void (*fconv_plain_t)(const void *, const void *, void *, int64_t, int64_t, int64_t);
 
 // 16-bit storage: the 16-bit matrix instruction when C is a multiple of 16 (and the eight weights
@@ -342,7 +356,7 @@ extern "C" granq_status_t granq_conv1x1_float(const void *x_hat, const granq_des
         const bool sixteen = esize == 2 && c % kFc16Step == 0 && ((uintptr_t)w & 15u) == 0;
         fconv_mfma_t kernel = ragged ? fconv_mfma_kernel<true>(t, sixteen) : fconv_mfma_kernel<false>(t, sixteen);
         launch_kernel(kernel, grid, block, 0, hs, x_hat, w, y, c, hw, o, groups_total, tasks, (int32_t)sweeps,
-                      (int32_t)blocks_per_die);
+                      (int32_t)blocks_per_die, (int32_t)(n * o * hw * (int64_t)esize > GRANQ_CONV_STREAM_OUT_BYTES));
         return launched();
     }
     if ((hw + kBlock - 1) / kBlock >= ((int64_t)1 << 31)) return GRANQ_ERR_UNSUPPORTED;
